@@ -1,0 +1,191 @@
+"""Pins for the oracle's budgets and hard top-k (Sec. 3.1, 3.3, 3.4) and for the
+Soft-TopK helper that serves as an independent check (Sec. 3.2, App. A.1).  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import lkv_oracle as O
+from oracle import soft_topk as ST
+from paper_2605_06676_amd import workloads as W
+
+
+# ----- budgets --------------------------------------------------------------
+
+def test_budget_floor_rule_and_total():
+    r = np.array([[0.5, 0.1], [0.0999, 0.9999]])
+    b = O.integer_budgets(r, 1000)
+    assert b.tolist() == [[500, 100], [99, 999]]
+    # sum of floors never exceeds the floor of the sum (the constraint of Sec. 3.1)
+    rng = np.random.default_rng(0)
+    for _ in range(50):
+        L, H, t = 4, 8, int(rng.integers(100, 5000))
+        R = float(rng.uniform(0.05, 0.5))
+        p = rng.dirichlet(np.ones(L * H))
+        r = np.minimum(p * R * L * H, 0.999)
+        assert int(O.integer_budgets(r, t).sum()) <= O.total_budget(R, L, H, t)
+    assert O.total_budget(0.15, 32, 8, 204800) == 7864320
+
+
+def test_offsets_are_exclusive_prefix_sums():
+    off = O.segment_offsets(np.array([[3, 0], [5, 1]]))
+    assert off.tolist() == [0, 3, 3, 8, 9]
+
+
+@pytest.mark.parametrize("cid", [0, 1, 2, 3, 4])
+def test_workload_budget_generator_invariants(cid):
+    w = W.CONFIGS[cid]
+    T = int(W.seq_lengths(w)[0])
+    b = W.draw_budgets(w, T)
+    assert b.shape == (w.L, w.H)
+    assert b.min() >= w.b_min and b.max() <= T
+    assert int(b.sum()) <= O.total_budget(w.R, w.L, w.H, T)
+    assert int(b.sum()) >= O.total_budget(w.R, w.L, w.H, T) - w.L * w.H
+    if cid == 4:
+        assert b.max() == T  # alpha = 0.1 drives at least one head into the cap
+
+
+# ----- order key --------------------------------------------------------------
+
+def test_order_key_is_monotone_and_handles_specials():
+    vals = np.array([-np.inf, -3.5, -1e-40, -0.0, 0.0, 1e-40, 2.0, np.inf], dtype=np.float32)
+    keys = O.order_key(vals)
+    assert np.all(np.diff(keys.astype(np.int64)) > 0)        # strictly increasing, -0 < +0
+    assert O.order_key(np.array([np.nan], dtype=np.float32))[0] == keys[0]  # NaN ranks as -inf
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal(1000).astype(np.float32)
+    k = O.order_key(x).astype(np.int64)
+    i, j = rng.integers(0, 1000, 500), rng.integers(0, 1000, 500)
+    assert np.array_equal(np.sign(x[i] - x[j]), np.sign(k[i] - k[j]))
+
+
+# ----- hard top-k ------------------------------------------------------------
+
+def _brute(u, b):
+    ranked = sorted(range(len(u)), key=lambda i: (-float(u[i]), i))
+    return sorted(ranked[:b])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_select_matches_brute_force_sort(seed):
+    rng = np.random.default_rng(seed)
+    T = int(rng.integers(1, 300))
+    u = rng.standard_normal(T).astype(np.float32)
+    if seed % 2:
+        u = np.round(u * 2) / 2          # many exact ties
+    for b in {0, 1, T // 3, T - 1 if T > 1 else 0, T}:
+        assert O.select(u, b).tolist() == _brute(u, b)
+
+
+def _check_invariants(u, b, idx):
+    T = u.size
+    assert idx.dtype == np.int32 and idx.size == b
+    assert np.all(np.diff(idx) > 0)
+    if b:
+        assert 0 <= idx[0] and idx[-1] < T
+    kept = np.zeros(T, bool); kept[idx] = True
+    key = O.order_key(u).astype(np.int64)
+    if 0 < b < T:
+        thr = key[kept].min()
+        assert thr >= key[~kept].max()
+        eq_kept = np.flatnonzero(kept & (key == thr))
+        eq_drop = np.flatnonzero(~kept & (key == thr))
+        if eq_drop.size:
+            assert eq_kept.max() < eq_drop.min()
+
+
+def test_select_invariants_on_workload_scores():
+    w = W.scaled(W.CONFIGS[0], L=1, H=4, T=1024, b_min=8)
+    K, V = W.draw_kv(w, 1024)
+    sc = W.draw_scorer(w)
+    u = O.score(O.bf16_bits_to_f64(K), O.bf16_bits_to_f64(V),
+                {"kind": "linear", "w1": O.bf16_bits_to_f64(sc["w1"]), "b1": sc["b1"]})
+    b = W.draw_budgets(w, 1024)
+    idx, off = O.select_all(u, b)
+    assert off[-1] == b.sum() and idx.size == b.sum()
+    assert b.sum() / (w.L * w.H * 1024) <= w.R
+    for h in range(4):
+        _check_invariants(u[0, h], int(b[0, h]), idx[off[h]:off[h + 1]])
+
+
+def test_select_forced_ties_keep_lowest_indices():
+    u = np.full(100, 0.25, dtype=np.float32)
+    assert O.select(u, 17).tolist() == list(range(17))
+    # duplicated rows: the copy with the lower index wins
+    u = np.array([1.0, 5.0, 3.0, 5.0, 3.0, 3.0, 0.0], dtype=np.float32)
+    assert O.select(u, 1).tolist() == [1]
+    assert O.select(u, 3).tolist() == [1, 2, 3]
+    assert O.select(u, 4).tolist() == [1, 2, 3, 4]
+
+
+def test_select_specials():
+    u = np.array([np.nan, -np.inf, 0.0, -0.0, np.inf, np.nan], dtype=np.float32)
+    assert O.select(u, 1).tolist() == [4]
+    assert O.select(u, 2).tolist() == [2, 4]          # +0 before -0
+    assert O.select(u, 3).tolist() == [2, 3, 4]
+    assert O.select(u, 4).tolist() == [0, 2, 3, 4]    # NaN ties with -inf, lower index first
+    assert O.select(u, 5).tolist() == [0, 1, 2, 3, 4]
+    with pytest.raises(ValueError):
+        O.select(u, 7)
+
+
+def test_select_invariant_under_order_preserving_maps():
+    rng = np.random.default_rng(5)
+    u = rng.standard_normal(500).astype(np.float32)
+    base = O.select(u, 77)
+    assert np.array_equal(O.select(u * np.float32(4.0), 77), base)       # exact scaling by 2^2
+    assert np.array_equal(O.select(np.exp(u.astype(np.float64)).astype(np.float32), 77), base)
+    perm = rng.permutation(500)
+    assert np.array_equal(np.sort(perm[O.select(u[perm], 77)]), base)     # relabelling tokens (tie-free)
+
+
+# ----- Soft-TopK helper and its hard limit ------------------------------------
+
+@pytest.mark.parametrize("seed", range(4))
+def test_soft_topk_properties(seed):
+    rng = np.random.default_rng(seed)
+    n = int(rng.integers(5, 60))
+    x = rng.standard_normal(n) * 2
+    k = float(rng.uniform(0.5, n - 0.5))
+    y = ST.soft_topk(x, k)
+    assert np.all((y > 0) & (y < 1))
+    assert y.sum() == pytest.approx(k, rel=1e-12)                          # normalisation
+    order = np.argsort(x)
+    assert np.all(np.diff(y[order]) >= -1e-15)                             # order preservation
+    assert np.allclose(ST.soft_topk(x + 3.7, k), y, rtol=1e-10)             # translation invariance
+    # the threshold solves the constraint as a root of sum f(x - lam) - k
+    lam, m = ST.soft_topk_lambda(x, k)
+    lo, hi = x.min() - 50, x.max() + 50
+    for _ in range(200):
+        mid = 0.5 * (lo + hi)
+        if ST.laplace_cdf(x - mid).sum() > k:
+            lo = mid
+        else:
+            hi = mid
+    assert lam == pytest.approx(0.5 * (lo + hi), abs=1e-9)
+    # and agrees with the printed closed form when the split index is interior
+    if 1 <= m < n:
+        xs = np.sort(x)[::-1]
+        s1, s2 = np.exp(-xs[:m]).sum(), np.exp(xs[m:]).sum()
+        assert lam == pytest.approx(math.log((math.sqrt((k - m) ** 2 + s1 * s2) - (k - m)) / s1), abs=1e-9)
+
+
+def test_soft_topk_k1_is_softmax():
+    rng = np.random.default_rng(9)
+    x = rng.standard_normal(40) * 0.5      # flat enough: largest softmax probability < 1/2
+    sm = np.exp(x - x.max()); sm /= sm.sum()
+    assert sm.max() < 0.5
+    assert np.allclose(ST.soft_topk(x, 1.0), sm, rtol=1e-12)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_hard_topk_is_the_zero_temperature_limit_of_soft_topk(seed):
+    rng = np.random.default_rng(100 + seed)
+    T = int(rng.integers(20, 200))
+    u = rng.standard_normal(T).astype(np.float32)
+    assert np.unique(u).size == T          # tie-free
+    b = int(rng.integers(1, T))
+    soft = ST.soft_topk(u.astype(np.float64), float(b), tau=1e-4)
+    mask = np.zeros(T); mask[O.select(u, b)] = 1.0
+    assert np.array_equal(np.round(soft), mask)
+    assert soft.sum() == pytest.approx(b, rel=1e-9)
