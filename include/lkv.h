@@ -1,0 +1,157 @@
+/*
+ * lkv.h -- C ABI of the MI355X (gfx950) implementation of LKV's inference-time
+ * KV-cache eviction path: token scoring, head-wise budgeted top-k, compaction
+ * into a padding-free ragged cache, and GQA decode attention over that cache.
+ *
+ * General conventions
+ * -------------------
+ * Memory.   Every pointer is marked HOST or DEVICE.  All device buffers are
+ *           allocated, owned and freed by the caller; the library allocates no
+ *           device memory inside the four hot calls.  The context owns only a
+ *           small ring of pinned host staging buffers.  Device pointers must be
+ *           16-byte aligned.
+ * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
+ *           stream).  The hot calls only enqueue work on it; they do not
+ *           synchronise the host with the device and results are valid once the
+ *           caller has synchronised the stream.
+ * Layout.   Cache tensors are bf16, row-major [n_layers, n_kv_heads, T, 128]
+ *           per sequence.  A "segment" is one (sequence, layer, kv head); the
+ *           segments are numbered s = (seq * n_layers + layer) * n_kv_heads +
+ *           head.  Within a segment kept tokens are in ascending token order.
+ * Errors.   Every call returns an lkv_status and never throws.  All argument
+ *           checks happen on the host before anything is launched; on failure
+ *           nothing has been enqueued and lkv_last_error() describes the cause.
+ *           LKV_ERR_HIP reports a failed HIP runtime call.
+ * Threads.  A context must not be used from two host threads at once.
+ */
+#ifndef LKV_H_
+#define LKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lkv_ctx lkv_ctx;
+
+typedef enum {
+  LKV_OK = 0,
+  LKV_ERR_INVALID_ARG = 1, /* null / misaligned pointer, inconsistent sizes, budget outside [0, T] */
+  LKV_ERR_UNSUPPORTED = 2, /* head_dim != 128, hidden not a multiple of 16 in [16, 128], group > 16 */
+  LKV_ERR_WORKSPACE = 3,   /* workspace missing or smaller than the *_workspace_bytes() figure */
+  LKV_ERR_HIP = 4          /* a HIP runtime call failed */
+} lkv_status;
+
+typedef enum { LKV_SCORER_LINEAR = 0, LKV_SCORER_MLP = 1 } lkv_scorer_kind;
+typedef enum { LKV_ACT_SILU = 0, LKV_ACT_GELU_ERF = 1 } lkv_act;
+
+/* Geometry of a prefilled KV cache (Sec. 3.1 of the paper: per layer and KV
+ * head, K and V are t x d matrices).  The struct and the arrays it points to
+ * are HOST memory and are read during the call only. */
+typedef struct {
+  int32_t n_seq;            /* number of sequences (>= 1) */
+  int32_t n_layers;         /* L */
+  int32_t n_kv_heads;       /* H */
+  int32_t n_q_heads;        /* Hq, a multiple of H; query head hq reads KV head hq / (Hq / H) */
+  int32_t head_dim;         /* d, must be 128 */
+  const int32_t *seq_len;   /* HOST [n_seq]: T_s >= 1 */
+  const void *const *k;     /* HOST [n_seq] of DEVICE pointers: bf16 [L, H, T_s, d] */
+  const void *const *v;     /* HOST [n_seq] of DEVICE pointers: bf16 [L, H, T_s, d] */
+} lkv_cache;
+
+/* Parameters of the LKV-T token scorer (Sec. 3.4: u_i = MLP([k_i ; v_i]); the
+ * input is the 256-vector made of the key row followed by the value row).
+ * LINEAR : u = w1 . x + b1
+ * MLP    : u = w2 . act(W1 x + b1) (+ b2); Table 5 of the paper uses
+ *          256 -> 128 -> 1 with SiLU, a hidden bias and no output bias.
+ * The struct is HOST memory; the arrays are DEVICE memory, caller-owned.
+ * Hs = n_kv_heads when per_head != 0 (one scorer per head, as in the paper),
+ * Hs = 1 otherwise (one scorer per layer shared by its heads). */
+typedef struct {
+  int32_t kind;      /* lkv_scorer_kind */
+  int32_t act;       /* lkv_act, MLP only */
+  int32_t hidden;    /* MLP only: multiple of 16 in [16, 128] */
+  int32_t per_head;  /* 0 or 1 */
+  const void *w1;    /* DEVICE bf16. LINEAR [L, Hs, 256]; MLP [L, Hs, hidden, 256] (one row per hidden unit) */
+  const float *b1;   /* DEVICE fp32. LINEAR [L, Hs] (scalar bias); MLP [L, Hs, hidden] */
+  const float *w2;   /* DEVICE fp32. MLP [L, Hs, hidden]; LINEAR: ignored */
+  const float *b2;   /* DEVICE fp32. MLP [L, Hs], or NULL for no output bias; LINEAR: ignored */
+} lkv_scorer;
+
+/* Create / destroy a context bound to HIP device `device`.  lkv_create selects
+ * that device for the calling thread. */
+lkv_status lkv_create(lkv_ctx **out, int device);
+void lkv_destroy(lkv_ctx *ctx);
+
+/* Text of the last error recorded on `ctx` (valid until the next call on it). */
+const char *lkv_last_error(const lkv_ctx *ctx);
+
+/* Library version string. */
+const char *lkv_version(void);
+
+/* Token scoring (Sec. 3.4, "Head-Specific Intrinsic Scoring").
+ * For every sequence s, layer l, head h and token i writes
+ *   scores[s][(l*H + h)*T_s + i] = f_{l,h}([K[l,h,i,:] ; V[l,h,i,:]])
+ * as fp32.  bf16 inputs, fp32 accumulation.  Each K/V row is read once.
+ * scores : HOST [n_seq] of DEVICE pointers, each fp32 [L, H, T_s]. */
+lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *scorer,
+                     float *const *scores, void *stream);
+
+/* Head-wise budgeted hard top-k (Sec. 3.4, inference: m = TopK(u, b); budgets
+ * b = floor(r t) come from LKV-H, Sec. 3.3, and are an input here).
+ * For segment s keeps the budgets[s] tokens with the largest score; equal
+ * scores are resolved towards the lower token index; a NaN score ranks as
+ * -inf; scores are compared by the total order of their fp32 bit patterns
+ * (-0.0 below +0.0).  Writes
+ *   offsets[s]              = sum of budgets of the segments before s (s = 0..n_segments),
+ *   idx[offsets[s] + j]     = j-th kept token of segment s, ascending.
+ * The result is unique, hence reproducible bit for bit.
+ * scores  : HOST [n_seq] of DEVICE pointers, fp32 [L, H, T_s] (as written by lkv_score)
+ * budgets : HOST int32 [n_seq * L * H], 0 <= budgets[s] <= T_seq(s); sum < 2^31
+ * idx     : DEVICE int32 [sum of budgets]
+ * offsets : DEVICE int32 [n_seq * L * H + 1] */
+lkv_status lkv_select(lkv_ctx *ctx, const lkv_cache *cache, const float *const *scores,
+                      const int32_t *budgets, int32_t *idx, int32_t *offsets, void *stream);
+
+/* Compaction into the padding-free ragged cache (Sec. 4.5: the compressed
+ * cache is flattened so that no padding is stored).
+ *   kp[offsets[s] + j, :] = K[seq, l, h, idx[offsets[s] + j], :]   (same for vp / V)
+ * Rows are copied bit for bit.
+ * idx, offsets : DEVICE, as written by lkv_select
+ * total_kept   : sum of the budgets (HOST scalar; equals offsets[n_segments])
+ * kp, vp       : DEVICE bf16 [total_kept, d] */
+lkv_status lkv_compact(lkv_ctx *ctx, const lkv_cache *cache, const int32_t *idx,
+                       const int32_t *offsets, int64_t total_kept, void *kp, void *vp,
+                       void *stream);
+
+/* Bytes of DEVICE workspace lkv_decode_attn needs for this problem size. */
+size_t lkv_decode_workspace_bytes(int32_t n_segments, int64_t total_kept, int32_t n_q_heads,
+                                  int32_t n_kv_heads);
+
+/* One decode step of grouped-query attention over the ragged cache (Eq. 1 of
+ * the paper restricted to the kept tokens; the retention mask is per KV head,
+ * so all query heads of a group read the same segment, Sec. 3.1).
+ * For query row r = (seq*L + l)*Hq + hq, segment s = (seq*L + l)*H + hq/(Hq/H):
+ *   p_j = softmax_j(scale * q[r,:] . kp[offsets[s] + j, :]),  out[r,:] = sum_j p_j vp[offsets[s] + j, :]
+ *   lse[r] = log sum_j exp(scale * q . k_j)
+ * An empty segment gives out = 0 and lse = -inf.  bf16 inputs, fp32 softmax
+ * and accumulation, fp32 output.
+ * q        : DEVICE bf16 [n_seq, L, Hq, d]
+ * kp, vp   : DEVICE bf16 [total_kept, d]
+ * offsets  : DEVICE int32 [n_seq*L*H + 1]
+ * out      : DEVICE fp32 [n_seq, L, Hq, d]
+ * lse      : DEVICE fp32 [n_seq, L, Hq], or NULL
+ * workspace: DEVICE, at least lkv_decode_workspace_bytes(...) bytes, 256-byte aligned;
+ *            contents are scratch and need not be initialised. */
+lkv_status lkv_decode_attn(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads,
+                           int32_t n_q_heads, int32_t head_dim, const void *q, const void *kp,
+                           const void *vp, const int32_t *offsets, int64_t total_kept,
+                           float scale, float *out, float *lse, void *workspace,
+                           size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LKV_H_ */

@@ -1,0 +1,79 @@
+// Compaction of the kept K/V rows into the padding-free ragged cache (Sec. 4.5
+// of the paper: the compressed cache is flattened so that no padding is kept).
+//
+// A pure gather: packed row p of segment s copies row idx[p] of that segment's
+// head, 256 bytes of K and 256 bytes of V, bit for bit.  The grid is flat over
+// packed rows, so skewed budgets do not unbalance it.  Sixteen lanes move one
+// row with one 16-byte load and store each; a block of 256 threads owns 256
+// consecutive packed rows.  The segment of the block's first row is found by a
+// wave-uniform binary search over the offsets; later rows walk forward from it.
+#include "lkv_common.h"
+
+namespace lkv {
+
+constexpr int kCompactThreads = 256;
+constexpr int kCompactRowsPerBlock = 256;
+constexpr int kCompactUnroll = 4;
+
+__global__ void __launch_bounds__(kCompactThreads)
+compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __restrict__ offsets,
+               int n_segments, int heads_per_seq, int seq_lo, int64_t total_kept,
+               uint4* __restrict__ kp, uint4* __restrict__ vp) {
+  const int64_t p0 = (int64_t)blockIdx.x * kCompactRowsPerBlock;
+  // last segment s0 with offsets[s0] <= p0 (offsets is non-decreasing, offsets[0] = 0)
+  int lo = 0, hi = n_segments;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if ((int64_t)offsets[mid] <= p0) lo = mid; else hi = mid;
+  }
+  const int s0 = lo;
+
+  const int rslot = threadIdx.x >> 4;   // 16 rows per pass over the block
+  const int c = threadIdx.x & 15;
+#pragma unroll 1
+  for (int it = 0; it < kCompactRowsPerBlock / 16; it += kCompactUnroll) {
+    uint4 kk[kCompactUnroll], vv[kCompactUnroll];
+    bool live[kCompactUnroll];
+#pragma unroll
+    for (int u = 0; u < kCompactUnroll; ++u) {
+      const int64_t p = p0 + (it + u) * 16 + rslot;
+      live[u] = false;
+      if (p < total_kept) {
+        int s = s0;
+        while ((int64_t)offsets[s + 1] <= p) ++s;     // skips empty segments too; p < offsets[n_segments]
+        const int seq = s / heads_per_seq;
+        const int lh = s - seq * heads_per_seq;
+        const int sl = seq - seq_lo;                  // this launch describes sequences seq_lo .. seq_lo + tab.n - 1
+        if (sl >= 0 && sl < tab.n) {
+          // a token index outside [0, T) cannot come from lkv_select; it is clamped, never followed
+          const int T = tab.T[sl];
+          const int tok = min(max(idx[p], 0), T - 1);
+          const size_t src = ((size_t)lh * (size_t)T + (size_t)tok) * kChunksPerRow + c;
+          kk[u] = reinterpret_cast<const uint4*>(tab.k[sl])[src];
+          vv[u] = reinterpret_cast<const uint4*>(tab.v[sl])[src];
+          live[u] = true;
+        }
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kCompactUnroll; ++u) {
+      const int64_t p = p0 + (it + u) * 16 + rslot;
+      if (live[u]) {
+        kp[p * kChunksPerRow + c] = kk[u];
+        vp[p * kChunksPerRow + c] = vv[u];
+      }
+    }
+  }
+}
+
+void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
+                    int heads_per_seq, int seq_lo, int64_t total_kept, void* kp, void* vp,
+                    hipStream_t stream) {
+  if (total_kept <= 0) return;
+  const int blocks = (int)((total_kept + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock);
+  hipLaunchKernelGGL(compact_kernel, dim3(blocks), dim3(kCompactThreads), 0, stream, tab, idx, offsets,
+                     n_segments, heads_per_seq, seq_lo, total_kept, reinterpret_cast<uint4*>(kp),
+                     reinterpret_cast<uint4*>(vp));
+}
+
+}  // namespace lkv

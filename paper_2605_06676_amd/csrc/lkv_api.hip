@@ -1,0 +1,317 @@
+// Host side of the C ABI declared in include/lkv.h: argument checks, launch
+// tables, the pinned staging ring for the offsets upload, and error reporting.
+// Every check runs before anything is enqueued.
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+#include "../../include/lkv.h"
+#include "lkv_kernels.h"
+
+namespace {
+
+constexpr int kStageSlots = 8;
+constexpr size_t kStageBytes = 1u << 20;   // 1 MiB per slot: up to 262143 segments
+
+}  // namespace
+
+struct lkv_ctx {
+  int device = 0;
+  std::string err;
+  void* stage[kStageSlots] = {};
+  hipEvent_t stage_done[kStageSlots] = {};
+  bool stage_used[kStageSlots] = {};
+  int stage_next = 0;
+};
+
+namespace {
+
+lkv_status fail(lkv_ctx* ctx, lkv_status st, const char* fmt, ...) {
+  if (ctx != nullptr) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof(buf), fmt, ap);
+    va_end(ap);
+    ctx->err = buf;
+  }
+  return st;
+}
+
+lkv_status hip_fail(lkv_ctx* ctx, hipError_t e, const char* what) {
+  return fail(ctx, LKV_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+lkv_status check_cache(lkv_ctx* ctx, const lkv_cache* c, bool need_kv) {
+  if (c == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "cache is NULL");
+  if (c->n_seq < 1 || c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers, n_kv_heads and n_q_heads must be >= 1");
+  if (c->n_q_heads % c->n_kv_heads != 0)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads (%d) is not a multiple of n_kv_heads (%d)", c->n_q_heads,
+                c->n_kv_heads);
+  if (c->head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", c->head_dim);
+  if (c->seq_len == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "seq_len is NULL");
+  if (need_kv && (c->k == nullptr || c->v == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "k or v table is NULL");
+  const int64_t heads = (int64_t)c->n_layers * c->n_kv_heads;
+  if (heads * c->n_seq >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  for (int s = 0; s < c->n_seq; ++s) {
+    if (c->seq_len[s] < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "seq_len[%d] = %d must be >= 1", s, c->seq_len[s]);
+    if (need_kv) {
+      if (c->k[s] == nullptr || c->v[s] == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "k[%d] or v[%d] is NULL", s, s);
+      if (!aligned16(c->k[s]) || !aligned16(c->v[s]))
+        return fail(ctx, LKV_ERR_INVALID_ARG, "k[%d] or v[%d] is not 16-byte aligned", s, s);
+    }
+  }
+  return LKV_OK;
+}
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+}  // namespace
+
+extern "C" {
+
+const char* lkv_version(void) { return "lkv-mi355x 0.1 (gfx950)"; }
+
+lkv_status lkv_create(lkv_ctx** out, int device) {
+  if (out == nullptr) return LKV_ERR_INVALID_ARG;
+  *out = nullptr;
+  int n_dev = 0;
+  if (hipGetDeviceCount(&n_dev) != hipSuccess || device < 0 || device >= n_dev) return LKV_ERR_HIP;
+  if (hipSetDevice(device) != hipSuccess) return LKV_ERR_HIP;
+  lkv_ctx* ctx = new (std::nothrow) lkv_ctx();
+  if (ctx == nullptr) return LKV_ERR_HIP;
+  ctx->device = device;
+  for (int i = 0; i < kStageSlots; ++i) {
+    if (hipHostMalloc(&ctx->stage[i], kStageBytes, hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&ctx->stage_done[i], hipEventDisableTiming) != hipSuccess) {
+      lkv_destroy(ctx);
+      return LKV_ERR_HIP;
+    }
+  }
+  if (lkv::select_prepare() != hipSuccess || lkv::decode_prepare() != hipSuccess ||
+      lkv::score_mlp_prepare() != hipSuccess) {
+    lkv_destroy(ctx);
+    return LKV_ERR_HIP;
+  }
+  *out = ctx;
+  return LKV_OK;
+}
+
+void lkv_destroy(lkv_ctx* ctx) {
+  if (ctx == nullptr) return;
+  for (int i = 0; i < kStageSlots; ++i) {
+    if (ctx->stage_done[i] != nullptr) {
+      if (ctx->stage_used[i]) (void)hipEventSynchronize(ctx->stage_done[i]);
+      (void)hipEventDestroy(ctx->stage_done[i]);
+    }
+    if (ctx->stage[i] != nullptr) (void)hipHostFree(ctx->stage[i]);
+  }
+  delete ctx;
+}
+
+const char* lkv_last_error(const lkv_ctx* ctx) { return ctx != nullptr ? ctx->err.c_str() : "context is NULL"; }
+
+lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* scorer, float* const* scores,
+                     void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (scorer == nullptr || scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer or scores is NULL");
+  if (scorer->kind != LKV_SCORER_LINEAR && scorer->kind != LKV_SCORER_MLP)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", scorer->kind);
+  if (scorer->w1 == nullptr || scorer->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
+  if (!aligned16(scorer->w1)) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 is not 16-byte aligned");
+  if (scorer->per_head != 0 && scorer->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
+  if (scorer->kind == LKV_SCORER_MLP) {
+    if (scorer->act != LKV_ACT_SILU && scorer->act != LKV_ACT_GELU_ERF)
+      return fail(ctx, LKV_ERR_INVALID_ARG, "unknown activation %d", scorer->act);
+    if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
+    if (scorer->hidden < 16 || scorer->hidden > 128 || scorer->hidden % 16 != 0)
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must be a multiple of 16 in [16, 128]", scorer->hidden);
+    if (scorer->hidden > 64)
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d: widths above 64 are not built yet", scorer->hidden);
+  }
+  const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    if (scores[s] == nullptr || !aligned16(scores[s]))
+      return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL or not 16-byte aligned", s);
+  }
+  const int heads_per_row = scorer->per_head ? 1 : cache->n_kv_heads;
+  hipStream_t st = as_stream(stream);
+
+  // launches of up to kMaxSeqPerLaunch sequences; MLP launches also need one tile size per launch
+  int s = 0;
+  while (s < cache->n_seq) {
+    lkv::SeqTable tab;
+    memset(&tab, 0, sizeof(tab));
+    int64_t blocks = 0;
+    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s]) : 0;
+    int n = 0;
+    while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
+      const int T = cache->seq_len[s];
+      int64_t per_head;
+      if (scorer->kind == LKV_SCORER_MLP) {
+        if (lkv::score_mlp_rows_per_block(T) != rpb0) break;
+        per_head = (T + rpb0 - 1) / rpb0;
+      } else {
+        per_head = lkv::score_linear_blocks_per_head(T);
+      }
+      if (blocks + per_head * heads >= ((int64_t)1 << 31) - 1) {
+        if (n == 0) return fail(ctx, LKV_ERR_UNSUPPORTED, "sequence %d is too long for one launch", s);
+        break;
+      }
+      tab.k[n] = static_cast<const uint16_t*>(cache->k[s]);
+      tab.v[n] = static_cast<const uint16_t*>(cache->v[s]);
+      tab.scores[n] = scores[s];
+      tab.T[n] = T;
+      tab.first[n] = (int32_t)blocks;
+      blocks += per_head * heads;
+      ++n;
+      ++s;
+    }
+    tab.first[n] = (int32_t)blocks;
+    tab.n = n;
+    if (scorer->kind == LKV_SCORER_LINEAR) {
+      lkv::launch_score_linear(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, (int)heads,
+                               heads_per_row, st);
+    } else {
+      lkv::launch_score_mlp(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, scorer->w2, scorer->b2,
+                            scorer->hidden, scorer->act == LKV_ACT_SILU ? 0 : 1, heads_per_row, rpb0, st);
+    }
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_score launch");
+  }
+  return LKV_OK;
+}
+
+lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
+                      int32_t* idx, int32_t* offsets, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, false)) return st;
+  if (scores == nullptr || budgets == nullptr || offsets == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "scores, budgets or offsets is NULL");
+  const int heads = cache->n_layers * cache->n_kv_heads;
+  const int64_t n_seg = (int64_t)heads * cache->n_seq;
+  if ((size_t)(n_seg + 1) * sizeof(int32_t) > kStageBytes)
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "%lld segments exceed the staging capacity", (long long)n_seg);
+  int64_t total = 0;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    if (scores[s] == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL", s);
+    const int T = cache->seq_len[s];
+    for (int h = 0; h < heads; ++h) {
+      const int32_t b = budgets[(size_t)s * heads + h];
+      if (b < 0 || b > T)
+        return fail(ctx, LKV_ERR_INVALID_ARG, "budget %d of segment %lld is outside [0, %d]", b,
+                    (long long)s * heads + h, T);
+      total += b;
+    }
+  }
+  if (total >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "sum of budgets %lld >= 2^31", (long long)total);
+  if (total > 0 && idx == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "idx is NULL");
+  hipStream_t st = as_stream(stream);
+
+  // offsets: computed on the host (budgets are host data), uploaded through a pinned slot
+  const int slot = ctx->stage_next;
+  ctx->stage_next = (slot + 1) % kStageSlots;
+  if (ctx->stage_used[slot]) {
+    if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
+  }
+  int32_t* host_off = static_cast<int32_t*>(ctx->stage[slot]);
+  int32_t run = 0;
+  for (int64_t i = 0; i < n_seg; ++i) {
+    host_off[i] = run;
+    run += budgets[i];
+  }
+  host_off[n_seg] = run;
+  if (hipError_t e = hipMemcpyAsync(offsets, host_off, (size_t)(n_seg + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st))
+    return hip_fail(ctx, e, "offsets upload");
+  if (hipError_t e = hipEventRecord(ctx->stage_done[slot], st)) return hip_fail(ctx, e, "staging event");
+  ctx->stage_used[slot] = true;
+
+  for (int s0 = 0; s0 < cache->n_seq; s0 += lkv::kMaxSeqPerLaunch) {
+    lkv::SeqTable tab;
+    memset(&tab, 0, sizeof(tab));
+    const int n = cache->n_seq - s0 < lkv::kMaxSeqPerLaunch ? cache->n_seq - s0 : lkv::kMaxSeqPerLaunch;
+    for (int i = 0; i < n; ++i) {
+      tab.scores[i] = const_cast<float*>(scores[s0 + i]);
+      tab.T[i] = cache->seq_len[s0 + i];
+      tab.first[i] = i * heads;
+    }
+    tab.first[n] = n * heads;
+    tab.n = n;
+    lkv::launch_select(tab, offsets, idx, s0 * heads, st);
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_select launch");
+  }
+  return LKV_OK;
+}
+
+lkv_status lkv_compact(lkv_ctx* ctx, const lkv_cache* cache, const int32_t* idx, const int32_t* offsets,
+                       int64_t total_kept, void* kp, void* vp, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (offsets == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "offsets is NULL");
+  if (total_kept < 0 || total_kept >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "total_kept = %lld is outside [0, 2^31)", (long long)total_kept);
+  if (total_kept == 0) return LKV_OK;
+  if (idx == nullptr || kp == nullptr || vp == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "idx, kp or vp is NULL");
+  if (!aligned16(kp) || !aligned16(vp)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is not 16-byte aligned");
+  const int heads = cache->n_layers * cache->n_kv_heads;
+  const int n_seg = heads * cache->n_seq;
+  hipStream_t st = as_stream(stream);
+  for (int s0 = 0; s0 < cache->n_seq; s0 += lkv::kMaxSeqPerLaunch) {
+    lkv::SeqTable tab;
+    memset(&tab, 0, sizeof(tab));
+    const int n = cache->n_seq - s0 < lkv::kMaxSeqPerLaunch ? cache->n_seq - s0 : lkv::kMaxSeqPerLaunch;
+    for (int i = 0; i < n; ++i) {
+      tab.k[i] = static_cast<const uint16_t*>(cache->k[s0 + i]);
+      tab.v[i] = static_cast<const uint16_t*>(cache->v[s0 + i]);
+      tab.T[i] = cache->seq_len[s0 + i];
+    }
+    tab.n = n;
+    lkv::launch_compact(tab, idx, offsets, n_seg, heads, s0, total_kept, kp, vp, st);
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_compact launch");
+  }
+  return LKV_OK;
+}
+
+size_t lkv_decode_workspace_bytes(int32_t n_segments, int64_t total_kept, int32_t n_q_heads, int32_t n_kv_heads) {
+  if (n_segments < 0 || total_kept < 0 || n_kv_heads < 1 || n_q_heads < n_kv_heads) return 0;
+  return lkv::decode_workspace_bytes(n_segments, total_kept, n_q_heads / n_kv_heads);
+}
+
+lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads, int32_t n_q_heads,
+                           int32_t head_dim, const void* q, const void* kp, const void* vp, const int32_t* offsets,
+                           int64_t total_kept, float scale, float* out, float* lse, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (n_seq < 1 || n_layers < 1 || n_kv_heads < 1 || n_q_heads < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers, n_kv_heads and n_q_heads must be >= 1");
+  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  const int G = n_q_heads / n_kv_heads;
+  if (G > lkv::kDecodeMaxGroup) return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", G, lkv::kDecodeMaxGroup);
+  const int64_t n_seg = (int64_t)n_seq * n_layers * n_kv_heads;
+  if (n_seg >= (int64_t)1 << 28) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  if (total_kept < 0 || total_kept >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "total_kept = %lld is outside [0, 2^31)", (long long)total_kept);
+  if (q == nullptr || offsets == nullptr || out == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q, offsets or out is NULL");
+  if (total_kept > 0 && (kp == nullptr || vp == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is NULL");
+  if (!aligned16(q) || !aligned16(kp) || !aligned16(vp) || !aligned16(out))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, kp, vp or out is not 16-byte aligned");
+  const size_t need = lkv::decode_workspace_bytes((int)n_seg, total_kept, G);
+  if (workspace == nullptr || workspace_bytes < need)
+    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace is not 256-byte aligned");
+  if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, (int)n_seg, total_kept, scale, out, lse,
+                                        static_cast<float*>(workspace), as_stream(stream)))
+    return hip_fail(ctx, e, "lkv_decode_attn launch");
+  return LKV_OK;
+}
+
+}  // extern "C"

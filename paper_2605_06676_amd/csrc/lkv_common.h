@@ -1,0 +1,75 @@
+// Shared device-side definitions of the LKV eviction kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace lkv {
+
+constexpr int kHeadDim = 128;          // d; a K or V row is 128 bf16 = 256 bytes = 16 lanes x 16 bytes
+constexpr int kChunksPerRow = 16;      // 16-byte pieces per row
+constexpr int kMaxSeqPerLaunch = 32;   // sequences described by one by-value launch table
+
+// Per-launch description of up to kMaxSeqPerLaunch sequences, passed by value
+// in the kernel arguments (about 1 KB) so that no device-side table has to be
+// uploaded.  `first[i]` is the first work unit (block or segment) of sequence
+// i in this launch; first[n] is the total.
+struct SeqTable {
+  const uint16_t* k[kMaxSeqPerLaunch];
+  const uint16_t* v[kMaxSeqPerLaunch];
+  float* scores[kMaxSeqPerLaunch];
+  int32_t T[kMaxSeqPerLaunch];
+  int32_t first[kMaxSeqPerLaunch + 1];
+  int32_t n;
+};
+
+// Index of the sequence that owns work unit `unit`.  `unit` is wave-uniform,
+// so this runs on the scalar unit.
+__device__ __forceinline__ int seq_of_unit(const SeqTable& tab, int unit) {
+  int s = 0;
+  while (s + 1 < tab.n && unit >= tab.first[s + 1]) ++s;
+  return s;
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Unpack the eight bf16 values of a 16-byte piece to fp32 (exact).
+__device__ __forceinline__ void unpack8(const uint4& p, float (&f)[8]) {
+  f[0] = bf16_lo(p.x); f[1] = bf16_hi(p.x);
+  f[2] = bf16_lo(p.y); f[3] = bf16_hi(p.y);
+  f[4] = bf16_lo(p.z); f[5] = bf16_hi(p.z);
+  f[6] = bf16_lo(p.w); f[7] = bf16_hi(p.w);
+}
+
+// DPP controls: lane permutations inside a row of 16 lanes, free on the VALU.
+constexpr int kDppQuadXor1 = 0xB1;      // quad_perm [1,0,3,2]
+constexpr int kDppQuadXor2 = 0x4E;      // quad_perm [2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+template <int kCtrl>
+__device__ __forceinline__ float dpp_f32(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), kCtrl, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
+// A K or V row is spread over exactly such a row of lanes.
+__device__ __forceinline__ float row16_allreduce_sum(float x) {
+  x += dpp_f32<kDppQuadXor1>(x);
+  x += dpp_f32<kDppQuadXor2>(x);
+  x += dpp_f32<kDppRowHalfMirror>(x);
+  x += dpp_f32<kDppRowMirror>(x);
+  return x;
+}
+
+// 16-byte load of cache data that this kernel reads exactly once.
+__device__ __forceinline__ uint4 load_stream16(const uint4* p) {
+#ifdef LKV_NONTEMPORAL_LOADS
+  return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
+}
+
+}  // namespace lkv

@@ -1,0 +1,38 @@
+// Host-side launch interface of the kernels (internal to the library).
+#pragma once
+
+#include "lkv_common.h"
+
+namespace lkv {
+
+// score_linear.hip
+void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b1, int n_heads,
+                         int heads_per_scorer_row, hipStream_t stream);
+int score_linear_blocks_per_head(int T);
+
+// score_mlp.hip
+hipError_t score_mlp_prepare();
+void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
+                      const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
+                      hipStream_t stream);
+int score_mlp_rows_per_block(int T);
+
+// select.hip
+hipError_t select_prepare();
+void launch_select(const SeqTable& tab, const int32_t* offsets, int32_t* idx, int seg_base,
+                   hipStream_t stream);
+
+// compact.hip
+void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
+                    int heads_per_seq, int seq_lo, int64_t total_kept, void* kp, void* vp,
+                    hipStream_t stream);
+
+// decode.hip
+constexpr int kDecodeMaxGroup = 8;
+hipError_t decode_prepare();
+size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G);
+hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
+                         int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
+                         hipStream_t stream);
+
+}  // namespace lkv

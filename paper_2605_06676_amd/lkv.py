@@ -1,0 +1,177 @@
+"""Thin Python binding over the C ABI of include/lkv.h (ctypes).
+
+Argument marshalling only: every step of the path runs in the HIP kernels of
+the shared library.  torch tensors supply device memory and the stream.  There
+is no fallback: if the library has not been built, or no GPU is present, the
+calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblkv.so")
+
+LKV_OK = 0
+SCORER_LINEAR, SCORER_MLP = 0, 1
+ACT_SILU, ACT_GELU_ERF = 0, 1
+_STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "LKV_ERR_WORKSPACE", 4: "LKV_ERR_HIP"}
+
+EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
+           "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn")
+
+
+class LkvError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class _Cache(C.Structure):
+    _fields_ = [("n_seq", C.c_int32), ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("n_q_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("seq_len", C.POINTER(C.c_int32)), ("k", C.POINTER(C.c_void_p)), ("v", C.POINTER(C.c_void_p))]
+
+
+class _Scorer(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("act", C.c_int32), ("hidden", C.c_int32), ("per_head", C.c_int32),
+                ("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load liblkv.so (built by paper_2605_06676_amd/build.py); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_06676_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    lib.lkv_create.argtypes = [C.POINTER(C.c_void_p), C.c_int]
+    lib.lkv_create.restype = C.c_int
+    lib.lkv_destroy.argtypes = [C.c_void_p]
+    lib.lkv_destroy.restype = None
+    lib.lkv_last_error.argtypes = [C.c_void_p]
+    lib.lkv_last_error.restype = C.c_char_p
+    lib.lkv_version.argtypes = []
+    lib.lkv_version.restype = C.c_char_p
+    lib.lkv_score.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(_Scorer), C.POINTER(C.c_void_p), C.c_void_p]
+    lib.lkv_score.restype = C.c_int
+    lib.lkv_select.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.POINTER(C.c_int32),
+                               C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.lkv_select.restype = C.c_int
+    lib.lkv_compact.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                C.c_void_p, C.c_void_p]
+    lib.lkv_compact.restype = C.c_int
+    lib.lkv_decode_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int32, C.c_int32]
+    lib.lkv_decode_workspace_bytes.restype = C.c_size_t
+    lib.lkv_decode_attn.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lkv_decode_attn.restype = C.c_int
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _stream_ptr(stream) -> Optional[int]:
+    import torch
+
+    s = torch.cuda.current_stream() if stream is None else stream
+    return C.c_void_p(s.cuda_stream)
+
+
+class Cache:
+    """Host-side description of a prefilled cache: lists of per-sequence K and V tensors,
+    each bf16 [L, H, T_s, 128] and contiguous on the GPU."""
+
+    def __init__(self, k: Sequence, v: Sequence, n_q_heads: int):
+        import torch
+
+        assert len(k) == len(v) and len(k) >= 1
+        L, H, _, d = k[0].shape
+        for a, b in zip(k, v):
+            assert a.dtype == torch.bfloat16 and b.dtype == torch.bfloat16
+            assert a.is_cuda and b.is_cuda and a.is_contiguous() and b.is_contiguous()
+            assert a.shape == b.shape and a.shape[0] == L and a.shape[1] == H and a.shape[3] == d
+        self.k, self.v = list(k), list(v)
+        self.n_seq, self.L, self.H, self.Hq, self.d = len(k), L, H, n_q_heads, d
+        self.seq_len = [int(a.shape[2]) for a in k]
+        self._lens = (C.c_int32 * self.n_seq)(*self.seq_len)
+        self._kp = (C.c_void_p * self.n_seq)(*[a.data_ptr() for a in k])
+        self._vp = (C.c_void_p * self.n_seq)(*[a.data_ptr() for a in v])
+        self.c = _Cache(self.n_seq, L, H, n_q_heads, d, self._lens, self._kp, self._vp)
+
+    @property
+    def n_segments(self) -> int:
+        return self.n_seq * self.L * self.H
+
+
+class Context:
+    def __init__(self, device: int = 0):
+        self.lib = load_library()
+        self.h = C.c_void_p()
+        st = self.lib.lkv_create(C.byref(self.h), device)
+        if st != LKV_OK:
+            raise LkvError(st, "lkv_create failed (is a GPU present?)")
+
+    def close(self):
+        if self.h:
+            self.lib.lkv_destroy(self.h)
+            self.h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != LKV_OK:
+            raise LkvError(st, self.lib.lkv_last_error(self.h).decode())
+
+
+def lkv_score(ctx: Context, cache: Cache, scorer: dict, scores: Sequence, stream=None) -> None:
+    """scorer: dict(kind, act, hidden, per_head, w1, b1, w2, b2) of GPU tensors (w1 bf16, others fp32).
+    scores: per-sequence fp32 [L, H, T_s] GPU tensors, written in place."""
+    kind = SCORER_LINEAR if scorer["kind"] == "linear" else SCORER_MLP
+    act = ACT_SILU if scorer.get("act", "silu") == "silu" else ACT_GELU_ERF
+    sc = _Scorer(kind, act, int(scorer.get("hidden", 0)), int(bool(scorer.get("per_head", False))),
+                 _ptr(scorer["w1"]), _ptr(scorer["b1"]), _ptr(scorer.get("w2")), _ptr(scorer.get("b2")))
+    sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    ctx._check(ctx.lib.lkv_score(ctx.h, C.byref(cache.c), C.byref(sc), sp, _stream_ptr(stream)))
+
+
+def lkv_select(ctx: Context, cache: Cache, scores: Sequence, budgets, idx, offsets, stream=None) -> None:
+    """budgets: host int32 array [n_seq * L * H]; idx (int32 [sum b]) and offsets (int32 [n_seg + 1]) GPU tensors."""
+    import numpy as np
+
+    b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
+    assert b.size == cache.n_segments
+    sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    ctx._check(ctx.lib.lkv_select(ctx.h, C.byref(cache.c), sp, b.ctypes.data_as(C.POINTER(C.c_int32)),
+                                  _ptr(idx), _ptr(offsets), _stream_ptr(stream)))
+
+
+def lkv_compact(ctx: Context, cache: Cache, idx, offsets, total_kept: int, kp, vp, stream=None) -> None:
+    ctx._check(ctx.lib.lkv_compact(ctx.h, C.byref(cache.c), _ptr(idx), _ptr(offsets), int(total_kept),
+                                   _ptr(kp), _ptr(vp), _stream_ptr(stream)))
+
+
+def lkv_decode_workspace_bytes(n_segments: int, total_kept: int, n_q_heads: int, n_kv_heads: int) -> int:
+    return int(load_library().lkv_decode_workspace_bytes(n_segments, int(total_kept), n_q_heads, n_kv_heads))
+
+
+def lkv_decode_attn(ctx: Context, n_seq: int, L: int, H: int, Hq: int, d: int, q, kp, vp, offsets,
+                    total_kept: int, scale: float, out, lse, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ctx._check(ctx.lib.lkv_decode_attn(ctx.h, n_seq, L, H, Hq, d, _ptr(q), _ptr(kp), _ptr(vp), _ptr(offsets),
+                                       int(total_kept), float(scale), _ptr(out), _ptr(lse), _ptr(workspace),
+                                       ws_bytes, _stream_ptr(stream)))

@@ -1,0 +1,31 @@
+"""The C-ABI library loads and exports every symbol that include/lkv.h declares.  No GPU needed."""
+import os
+import re
+
+from paper_2605_06676_amd import lkv
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "lkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(lkv_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    lib = lkv.load_library()
+    names = _declared()
+    assert set(names) == set(lkv.EXPORTS)
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_calls_that_need_no_gpu():
+    lib = lkv.load_library()
+    assert b"gfx950" in lib.lkv_version()
+    # workspace sizing is host arithmetic: slots = segments + chunks of 256 rows, (128 + 2) floats per query head
+    n = lkv.lkv_decode_workspace_bytes(256, 1258291, 32, 8)
+    slots = 256 + (1258291 + 255) // 256
+    assert n == (slots * 4 * 130 * 4 + 255) // 256 * 256
+    assert lkv.lkv_decode_workspace_bytes(-1, 10, 32, 8) == 0
