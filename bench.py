@@ -1,0 +1,200 @@
+#!/usr/bin/env python3
+"""Benchmark of the LKV eviction hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic batch that is already
+resident in HBM: lkv_score -> lkv_select -> lkv_compact -> lkv_decode_attn.
+Prints ONE JSON line.  `value` is KV entries evicted per second over the three
+eviction calls ((head-tokens - kept) / time); the decode leg is reported as
+achieved HBM GB/s in `decode`.  The `roofline` object is for the kernel that
+moves most of the bytes, the token scorer.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the Llama-3-8B-shaped 32k cache)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time cap of the oracle sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every (sequence, layer, head) is independent, "
+              "so more GPUs would just take disjoint heads); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2605_06676_amd import lkv
+    from paper_2605_06676_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = W.CONFIGS[args.config]
+    ctx = lkv.Context(0)
+
+    # ---- inputs, resident in HBM before the timed region --------------------------------
+    Ts = [int(t) for t in W.seq_lengths(w)]
+    Ks, Vs = [], []
+    for s, T in enumerate(Ts):
+        k, v = W.device_kv(w, T, s, dev)
+        Ks.append(k); Vs.append(v)
+    cache = lkv.Cache(Ks, Vs, w.Hq)
+    sc_host = W.draw_scorer(w)
+
+    def to_dev(a, bf16=False):
+        if a is None:
+            return None
+        if bf16:
+            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
+
+    scorer = {"kind": sc_host["kind"], "act": sc_host["act"], "hidden": sc_host["hidden"],
+              "per_head": sc_host["per_head"], "w1": to_dev(sc_host["w1"], True), "b1": to_dev(sc_host["b1"]),
+              "w2": to_dev(sc_host["w2"]), "b2": to_dev(sc_host["b2"])}
+    budgets = [W.draw_budgets(w, T, s) for s, T in enumerate(Ts)]
+    budgets_flat = np.concatenate([b.reshape(-1) for b in budgets]).astype(np.int32)
+    total = int(budgets_flat.sum())
+    N = sum(w.L * w.H * T for T in Ts)
+    scores = [torch.empty((w.L, w.H, T), dtype=torch.float32, device=dev) for T in Ts]
+    idx = torch.empty((total,), dtype=torch.int32, device=dev)
+    offsets = torch.empty((cache.n_segments + 1,), dtype=torch.int32, device=dev)
+    kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
+    vp = torch.empty_like(kp)
+    q = torch.stack([to_dev(W.draw_q(w, s), True) for s in range(w.n_seq)]).contiguous()
+    out = torch.empty((w.n_seq, w.L, w.Hq, w.d), dtype=torch.float32, device=dev)
+    lse = torch.empty((w.n_seq, w.L, w.Hq), dtype=torch.float32, device=dev)
+    ws = torch.empty((lkv.lkv_decode_workspace_bytes(cache.n_segments, total, w.Hq, w.H),), dtype=torch.uint8, device=dev)
+    scale = 1.0 / math.sqrt(w.d)
+
+    def step(ev=None):
+        if ev: ev[0].record()
+        lkv.lkv_score(ctx, cache, scorer, scores)
+        if ev: ev[1].record()
+        lkv.lkv_select(ctx, cache, scores, budgets_flat, idx, offsets)
+        if ev: ev[2].record()
+        lkv.lkv_compact(ctx, cache, idx, offsets, total, kp, vp)
+        if ev: ev[3].record()
+        lkv.lkv_decode_attn(ctx, w.n_seq, w.L, w.H, w.Hq, w.d, q, kp, vp, offsets, total, scale, out, lse, ws)
+        if ev: ev[4].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # the kernels are enqueued on torch's current stream, which is also where these events are recorded
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ph = np.array([[ev[j].elapsed_time(ev[j + 1]) for j in range(4)] for ev in events])   # ms
+    t_score, t_select, t_compact, t_decode = ph.mean(axis=0)
+    t_evict = t_score + t_select + t_compact
+    rho = total / N
+    evict_bytes = N * 520 + total * 1032
+    decode_bytes = total * 512 + w.n_seq * w.L * w.Hq * w.d * (2 + 4)
+    score_bytes = N * 516
+
+    result = {
+        "metric": "KV tokens evicted/sec (score+select+compact); ragged decode-attn HBM GB/s in `decode`",
+        "value": (N - total) / (t_evict * 1e-3),
+        "unit": "evicted KV entries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16 in, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": w.name, "n_seq": w.n_seq, "layers": w.L, "kv_heads": w.H, "q_heads": w.Hq,
+                   "seq_len": Ts if len(set(Ts)) > 1 else Ts[0], "head_tokens": N, "kept": total,
+                   "retention": rho, "scorer": w.scorer if w.scorer == "linear" else f"mlp256-{w.hidden}-{w.act}"},
+        "phases_ms": {"score": t_score, "select": t_select, "compact": t_compact, "decode": t_decode,
+                      "evict": t_evict, "step_gpu": float(ph.sum(axis=1).mean())},
+        "evict": {"bytes": evict_bytes, "GBps": evict_bytes / (t_evict * 1e6),
+                  "frac_of_peak": evict_bytes / (t_evict * 1e6) / HBM_PEAK_GBS,
+                  "context_tokens_per_s": sum(Ts) / (t_evict * 1e-3)},
+        "decode": {"bytes": decode_bytes, "GBps": decode_bytes / (t_decode * 1e6),
+                   "frac_of_peak": decode_bytes / (t_decode * 1e6) / HBM_PEAK_GBS},
+        "roofline": {"kernel": "score_linear_kernel" if w.scorer == "linear" else "score_mlp_kernel",
+                     "bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS, "traffic": None,
+                     "launches_per_step": 1 if w.n_seq <= 32 else math.ceil(w.n_seq / 32),
+                     "bytes_per_launch": score_bytes},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+def cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, cap_s):
+    """The oracle as it stands, timed on the host cores over whole layers of sequence 0 until the cap."""
+    import torch
+    from threadpoolctl import threadpool_info
+
+    from oracle import lkv_oracle as O
+
+    T = Ts[0]
+    done_tokens = done_kept = 0
+    layers = 0
+    spent = 0.0
+    evict_s = 0.0
+    scale = 1.0 / math.sqrt(w.d)
+    qh = q[0].view(torch.int16).cpu().numpy().view(np.uint16)
+    while layers < w.L and spent < cap_s:
+        l = layers
+        Kb = Ks[0][l].view(torch.int16).cpu().numpy().view(np.uint16)[None]     # [1, H, T, d]
+        Vb = Vs[0][l].view(torch.int16).cpu().numpy().view(np.uint16)[None]
+        sc = {"kind": sc_host["kind"], "act": sc_host["act"], "w1": sc_host["w1"][l:l + 1],
+              "b1": sc_host["b1"][l:l + 1], "w2": None if sc_host["w2"] is None else sc_host["w2"][l:l + 1],
+              "b2": None if sc_host["b2"] is None else sc_host["b2"][l:l + 1]}
+        t0 = time.perf_counter()
+        sco = dict(sc)
+        sco["w1"] = O.bf16_bits_to_f64(sc["w1"])
+        u = O.score(O.bf16_bits_to_f64(Kb), O.bf16_bits_to_f64(Vb), sco)
+        b = budgets[0][l:l + 1]
+        idx, off = O.select_all(u, b)
+        Kp, Vp = O.compact(Kb, Vb, idx, off)
+        t_ev = time.perf_counter() - t0
+        O.decode_attn(O.bf16_bits_to_f64(qh[l:l + 1]), O.bf16_bits_to_f64(Kp), O.bf16_bits_to_f64(Vp), off, w.H, scale)
+        spent += time.perf_counter() - t0
+        done_tokens += w.H * T
+        done_kept += int(b.sum())
+        layers += 1
+        evict_s += t_ev
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    return {"value": (done_tokens - done_kept) / evict_s, "unit": "evicted KV entries/s",
+            "cores": threads, "kind": "oracle",
+            "sample": f"layers 0..{layers - 1} of sequence 0 ({done_tokens} head-tokens), numpy fp64, "
+                      f"{spent:.1f} s including the decode leg",
+            "host_cpus": os.cpu_count()}
+
+
+if __name__ == "__main__":
+    main()

@@ -133,7 +133,7 @@ def test_results_are_reproducible(ctx):
 
 
 def test_argument_errors_are_reported_before_launch(ctx):
-    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=8, T=128)
+    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=8, T=128, b_min=4)
     K, V, Q, sc, B = _inputs(w, [128])
     run = G.GpuRun(ctx, K, V, Q, sc, B, w.Hq)
     bad = run.budgets.copy(); bad[1] = 129
