@@ -20,13 +20,8 @@ compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __r
                int n_segments, int heads_per_seq, int seq_lo, int64_t total_kept,
                uint4* __restrict__ kp, uint4* __restrict__ vp) {
   const int64_t p0 = (int64_t)blockIdx.x * kCompactRowsPerBlock;
-  // last segment s0 with offsets[s0] <= p0 (offsets is non-decreasing, offsets[0] = 0)
-  int lo = 0, hi = n_segments;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if ((int64_t)offsets[mid] <= p0) lo = mid; else hi = mid;
-  }
-  const int s0 = lo;
+  // the segment that contains row p0: the last one with offsets[s] <= p0
+  const int s0 = wave_upper_segment(offsets, n_segments, p0, threadIdx.x & 63);
 
   const int rslot = threadIdx.x >> 4;   // 16 rows per pass over the block
   const int c = threadIdx.x & 15;

@@ -2,188 +2,264 @@
 // Eq. 1 of the paper restricted to the kept tokens of each KV head, with all
 // query heads of a GQA group reading the same segment (Sec. 3.1).
 //
-// Split-K over a flat list of fixed-size chunks of packed rows: block c owns
-// packed rows [c*C, (c+1)*C) whatever segments they belong to, so every block
-// streams the same number of bytes however skewed the head budgets are.  A
-// chunk that crosses segment boundaries is processed piece by piece.  Each
-// piece produces, per query head of its segment, an online-softmax partial
+// Work decomposition.  Split-K over a flat list of equal chunks of packed rows:
+// block c owns packed rows [c*C, (c+1)*C) whatever segments they belong to, so
+// every block streams the same number of bytes however skewed the head budgets
+// are.  C is chosen on the host so that the grid is a few blocks per compute
+// unit.  A chunk that crosses segment boundaries is processed piece by piece.
+// Each piece yields, per query head of its segment, an online-softmax partial
 // (running max m, denominator l, unnormalised output acc[128]).  A piece that
 // is a whole segment is normalised and written straight to the output; other
-// pieces go to the workspace slot (segment + chunk) -- distinct pieces have
-// distinct slots because segment and chunk indices both grow along the packed
-// rows -- and a second kernel merges the slots of each segment.
+// pieces go to workspace slot (segment + chunk) -- distinct pieces get distinct
+// slots because segment and chunk indices both grow along the packed rows --
+// and a second, small kernel merges the slots of each segment.  (Merging inside
+// the first kernel, by the block that delivers a segment's last piece, needs
+// device-scope fences; with one L2 per XCD those write back and invalidate L2
+// and were measured to cost more than the second launch.)
 //
-// K and V rows are read once each with 16-byte loads, 16 lanes per row.  Lane
-// (r, c) keeps channels 8c..8c+7 of the output for the rows of its row slot.
+// Arithmetic.  With up to 16 query heads per KV head the two products are
+// skinny GEMMs, and doing them on the vector ALUs costs more issue slots per
+// byte than the HBM stream leaves room for, so both run on the matrix cores
+// (v_mfma_f32_16x16x32_bf16, fp32 accumulate):
+//   S^T[token, head] = K[token, :] . Q[head, :]^T     (A = K tile, B = Q^T)
+//   O[head, ch]     += P[head, token] V[token, ch]    (A = P,      B = V tile)
+// The accumulator layout of S^T (lane (rb, head) holds tokens 4rb..4rb+3 of a
+// 16-token tile) is exactly the A-operand layout of P for a K-step made of two
+// such tiles, so probabilities go from the first product to the second without
+// leaving their lanes.  Rows are read from HBM once with coalesced 16-byte
+// loads, staged in a wave-private LDS tile, and read back as operands: K by
+// 16-byte reads (row stride 272 B), V by the transposing 8-byte LDS read of
+// gfx950 (row stride 288 B); both strides make the reads bank-conflict free.
+// The next 32 rows are prefetched into registers while the current 32 are
+// multiplied.  Softmax runs in fp32 in the log2 domain.
 #include "lkv_common.h"
 
 namespace lkv {
 
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
-constexpr int kDecChunk = 256;          // packed rows per block
-constexpr int kDecStates = kDecWaves * 4;   // independent online-softmax states per block (wave x row slot)
-constexpr int kDecUnroll = 4;
+constexpr int kDecTile = 32;                 // rows per wave iteration: one K-step of the P.V product
+constexpr int kDecKStride = 272;             // LDS bytes per staged K row
+constexpr int kDecVStride = 288;             // LDS bytes per staged V row
+constexpr int kDecWaveLds = kDecTile * (kDecKStride + kDecVStride);   // 17920
+constexpr int kDecMaxGroup = 16;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
+#ifndef LKV_DEC_TARGET_BLOCKS
+#define LKV_DEC_TARGET_BLOCKS 512
+#endif
+#ifndef LKV_DEC_MIN_CHUNK
+#define LKV_DEC_MIN_CHUNK 128
+#endif
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-template <int G>
-struct DecShared {
-  float m[kDecStates][G];
-  float l[kDecStates][G];
-  float acc[kDecStates][G][kHeadDim];
+// Per-block LDS: the four wave tiles; after a piece, reused for the cross-wave merge.
+struct DecMerge {
+  float m[kDecWaves][kDecMaxGroup];
+  float l[kDecWaves][kDecMaxGroup];
+  float acc[kDecWaves][kDecMaxGroup][kHeadDim];
 };
+static_assert(sizeof(DecMerge) <= (size_t)kDecWaves * kDecWaveLds, "merge scratch must fit the staging tiles");
 
-template <int G>
-__global__ void __launch_bounds__(kDecThreads)
+__device__ __forceinline__ s16x4_t lds_read_tr16(const unsigned char* p) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4_t*)(p));
+}
+
+__global__ void __launch_bounds__(kDecThreads, 2)
 decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ kp,
                       const uint4* __restrict__ vp, const int32_t* __restrict__ offsets, int n_segments,
-                      int64_t total_kept, float scale, float* __restrict__ out, float* __restrict__ lse,
-                      float* __restrict__ ws_acc, float* __restrict__ ws_m, float* __restrict__ ws_l) {
+                      int64_t total_kept, int chunk_rows, int G, float scale, float* __restrict__ out,
+                      float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_m,
+                      float* __restrict__ ws_l) {
   extern __shared__ __align__(16) unsigned char smem[];
-  DecShared<G>& sh = *reinterpret_cast<DecShared<G>*>(smem);
 
   const int chunk = blockIdx.x;
-  const int64_t p0 = (int64_t)chunk * kDecChunk;
-  const int64_t p1 = min(p0 + (int64_t)kDecChunk, total_kept);
-  // last segment with offsets[s] <= p0: the segment that contains row p0
-  int lo = 0, hi = n_segments;
-  while (hi - lo > 1) {
-    const int mid = (lo + hi) >> 1;
-    if ((int64_t)offsets[mid] <= p0) lo = mid; else hi = mid;
-  }
-
+  const int64_t p0 = (int64_t)chunk * chunk_rows;
+  const int64_t p1 = min(p0 + (int64_t)chunk_rows, total_kept);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
-  const int r = lane >> 4;
-  const int c = lane & 15;
-  const int state = wave * 4 + r;
-  const float qscale = scale * kLog2e;   // scores are kept in the log2 domain
+  const int r = lane >> 4;     // load view: row slot.   operand view: K-block kb / accumulator row block rb
+  const int c = lane & 15;     // load view: 16-byte piece. operand view: token / head / channel index
+  unsigned char* k_lds = smem + wave * kDecWaveLds;
+  unsigned char* v_lds = k_lds + kDecTile * kDecKStride;
+  DecMerge& mg = *reinterpret_cast<DecMerge*>(smem);
+  const float qscale = scale * kLog2e;
+  // first segment of this block: the one that contains row p0, i.e. the last with offsets[s] <= p0
+  const int s_first = wave_upper_segment(offsets, n_segments, p0, lane);
 
 #pragma unroll 1
-  for (int s = lo; s < n_segments; ++s) {
+  for (int s = s_first; s < n_segments; ++s) {
     const int64_t seg_lo = offsets[s], seg_hi = offsets[s + 1];
     if (seg_lo >= p1) break;
     const int64_t a = max(p0, seg_lo), b = min(p1, seg_hi);
-    if (b <= a) continue;   // empty segment
-
-    // this lane's slice (channels 8c..8c+7) of the G query vectors of segment s
-    float qv[G][8];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      const uint4 qq = reinterpret_cast<const uint4*>(q + ((size_t)s * G + h) * kHeadDim)[c];
-      unpack8(qq, qv[h]);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qv[h][e] *= qscale;
-    }
-    float m[G], l[G], acc[G][8];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      m[h] = -INFINITY; l[h] = 0.f;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
-    }
-
+    if (b <= a) continue;   // empty segment (the merge kernel zeroes its output)
     const int n_rows = (int)(b - a);
+    const int n_tiles = (n_rows + kDecTile - 1) / kDecTile;
+
+    // B operand of the first product: Q^T, lane (head c, K-block r) holds q[head c][32 ks + 8 r .. +7]
+    bf16x8_t qfrag[4];
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (c < G) v = reinterpret_cast<const uint4*>(q + ((size_t)s * G + c) * kHeadDim)[ks * 4 + r];
+      qfrag[ks] = __builtin_bit_cast(bf16x8_t, v);
+    }
+    float m_run = -INFINITY;   // running max of head c (log2 domain), identical in the four lanes of a head
+    float l_run = 0.f;         // this lane's share of the denominator
+    f32x4_t acc_o[8];          // O[head 4r+e][channel 16 ct + c]
+#pragma unroll
+    for (int ct = 0; ct < 8; ++ct) acc_o[ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    uint4 kk[8], vv[8];
+    auto load_tile = [&](int t) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        int row = t * kDecTile + 4 * j + r;
+        const bool ok = row < n_rows;
+        row = ok ? row : n_rows - 1;
+        kk[j] = load_stream16(kp + (a + row) * kChunksPerRow + c);
+        vv[j] = load_stream16(vp + (a + row) * kChunksPerRow + c);
+        if (!ok) { kk[j] = make_uint4(0, 0, 0, 0); vv[j] = make_uint4(0, 0, 0, 0); }
+      }
+    };
+    if (wave < n_tiles) load_tile(wave);
+
 #pragma unroll 1
-    for (int i0 = 0; i0 * 16 < n_rows; i0 += kDecUnroll) {
-      uint4 kk[kDecUnroll], vv[kDecUnroll];
-      bool valid[kDecUnroll];
+    for (int t = wave; t < n_tiles; t += kDecWaves) {
+      // stage 32 rows: row 4j + r, piece c
 #pragma unroll
-      for (int u = 0; u < kDecUnroll; ++u) {
-        int row = (i0 + u) * 16 + state;
-        valid[u] = row < n_rows;
-        row = valid[u] ? row : n_rows - 1;
-        kk[u] = load_stream16(kp + (a + row) * kChunksPerRow + c);
-        vv[u] = load_stream16(vp + (a + row) * kChunksPerRow + c);
+      for (int j = 0; j < 8; ++j) {
+        *reinterpret_cast<uint4*>(k_lds + (4 * j + r) * kDecKStride + c * 16) = kk[j];
+        *reinterpret_cast<uint4*>(v_lds + (4 * j + r) * kDecVStride + c * 16) = vv[j];
       }
-      float sc[kDecUnroll][G];
+      if (t + kDecWaves < n_tiles) load_tile(t + kDecWaves);   // prefetch
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+      // S^T for the two 16-token halves: lane (rb = r, head c) gets tokens 16 tt + 4 r + e
+      f32x4_t sacc[2];
 #pragma unroll
-      for (int u = 0; u < kDecUnroll; ++u) {
-        float fk[8];
-        unpack8(kk[u], fk);
+      for (int tt = 0; tt < 2; ++tt) {
+        sacc[tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-          float d = 0.f;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) d = fmaf(fk[e], qv[h][e], d);
-          d = row16_allreduce_sum(d);
-          sc[u][h] = valid[u] ? d : -INFINITY;
+        for (int ks = 0; ks < 4; ++ks) {
+          const uint4 kx = *reinterpret_cast<const uint4*>(k_lds + (tt * 16 + c) * kDecKStride + ks * 64 + r * 16);
+          sacc[tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx), qfrag[ks], sacc[tt],
+                                                             0, 0, 0);
         }
       }
+      // online softmax for head c over the 8 tokens of this lane and the other three lanes of the head
+      float sv[8];
+      float mx = m_run;
+      const int tok0 = t * kDecTile;
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        float mx = m[h];
+      for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
-        for (int u = 0; u < kDecUnroll; ++u) mx = fmaxf(mx, sc[u][h]);
-        const float ref = mx == -INFINITY ? 0.f : mx;
-        const float alpha = fast_exp2(m[h] - ref);
-        m[h] = mx;
-        l[h] *= alpha;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[h][e] *= alpha;
-#pragma unroll
-        for (int u = 0; u < kDecUnroll; ++u) sc[u][h] = fast_exp2(sc[u][h] - ref);
-      }
-#pragma unroll
-      for (int u = 0; u < kDecUnroll; ++u) {
-        float fv[8];
-        unpack8(vv[u], fv);
-#pragma unroll
-        for (int h = 0; h < G; ++h) {
-          l[h] += sc[u][h];
-#pragma unroll
-          for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(sc[u][h], fv[e], acc[h][e]);
+        for (int e = 0; e < 4; ++e) {
+          const bool ok = tok0 + tt * 16 + 4 * r + e < n_rows;
+          sv[tt * 4 + e] = ok ? sacc[tt][e] * qscale : -INFINITY;
+          mx = fmaxf(mx, sv[tt * 4 + e]);
         }
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float ref = mx == -INFINITY ? 0.f : mx;
+      const float alpha = fast_exp2(m_run - ref);     // exp2(-inf) = 0 on the first tile
+      m_run = mx;
+      float psum = 0.f;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) { sv[i] = fast_exp2(sv[i] - ref); psum += sv[i]; }
+      l_run = l_run * alpha + psum;
+      // A operand of the second product: P[head c][K-slots 8 r .. 8 r + 7] = this lane's own 8 values
+      bf16x8_t pfrag;
+#pragma unroll
+      for (int i = 0; i < 8; ++i) pfrag[i] = (__bf16)sv[i];
+      // rescale the output rows (heads 4r+e) when any running max moved
+      if (__ballot(alpha != 1.f) != 0ull) {
+        float al[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) al[e] = __shfl(alpha, 4 * r + e, 64);
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc_o[ct][e] *= al[e];
       }
+      // O += P V: B operand lane (channel c of tile ct, K-block r) holds V[tokens 4r..4r+3 and 16+4r..16+4r+3][ch]
+#pragma unroll
+      for (int ct = 0; ct < 8; ++ct) {
+        const unsigned char* base = v_lds + (4 * r + (c >> 2)) * kDecVStride + ct * 32 + (c & 3) * 8;
+        const s16x4_t v0 = lds_read_tr16(base);
+        const s16x4_t v1 = lds_read_tr16(base + 16 * kDecVStride);
+        const s16x8_t vb = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+        acc_o[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pfrag, __builtin_bit_cast(bf16x8_t, vb), acc_o[ct], 0, 0, 0);
+      }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 
-    // combine the 16 states of the block through LDS
+    // ---- combine the four waves through LDS (the staging tiles are free now) ----
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    __syncthreads();   // every wave is done with its staging tile
+    if (r == 0 && c < G) { mg.m[wave][c] = m_run; mg.l[wave][c] = l_run; }
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      if (c == 0) { sh.m[state][h] = m[h]; sh.l[state][h] = l[h]; }
-      float4* dst = reinterpret_cast<float4*>(&sh.acc[state][h][c * 8]);
-      dst[0] = make_float4(acc[h][0], acc[h][1], acc[h][2], acc[h][3]);
-      dst[1] = make_float4(acc[h][4], acc[h][5], acc[h][6], acc[h][7]);
+    for (int e = 0; e < 4; ++e) {
+      const int h = 4 * r + e;
+      if (h < G) {
+#pragma unroll
+        for (int ct = 0; ct < 8; ++ct) mg.acc[wave][h][ct * 16 + c] = acc_o[ct][e];
+      }
     }
     __syncthreads();
     const bool whole = seg_lo >= p0 && seg_hi <= p1;
     const size_t slot = (size_t)s + (size_t)chunk;
     for (int o = tid; o < G * kHeadDim; o += kDecThreads) {
       const int h = o / kHeadDim, ch = o - h * kHeadDim;
-      float mx = -INFINITY;
+      float mxw = -INFINITY;
 #pragma unroll
-      for (int st = 0; st < kDecStates; ++st) mx = fmaxf(mx, sh.m[st][h]);
+      for (int w = 0; w < kDecWaves; ++w) mxw = fmaxf(mxw, mg.m[w][h]);
       float num = 0.f, den = 0.f;
 #pragma unroll
-      for (int st = 0; st < kDecStates; ++st) {
-        const float wgt = fast_exp2(sh.m[st][h] - mx);   // exp2(-inf) = 0 for states that saw no row
-        num = fmaf(sh.acc[st][h][ch], wgt, num);
-        den = fmaf(sh.l[st][h], wgt, den);
+      for (int w = 0; w < kDecWaves; ++w) {
+        const float wgt = fast_exp2(mg.m[w][h] - mxw);   // 0 for a wave that saw no row (m = -inf)
+        num = fmaf(mg.acc[w][h][ch], wgt, num);
+        den = fmaf(mg.l[w][h], wgt, den);
       }
       if (whole) {
         out[((size_t)s * G + h) * kHeadDim + ch] = num / den;
-        if (ch == 0 && lse != nullptr) lse[(size_t)s * G + h] = mx * kLn2 + __logf(den);
+        if (ch == 0 && lse != nullptr) lse[(size_t)s * G + h] = mxw * kLn2 + __logf(den);
       } else {
         ws_acc[(slot * G + h) * kHeadDim + ch] = num;
-        if (ch == 0) { ws_m[slot * G + h] = mx; ws_l[slot * G + h] = den; }
+        if (ch == 0) { ws_m[slot * G + h] = mxw; ws_l[slot * G + h] = den; }
       }
     }
-    __syncthreads();   // the LDS states are rewritten by the next piece
+    __syncthreads();   // the merge scratch becomes staging tiles again
   }
 }
 
-// Merge of the per-piece partials of one (segment, query head); 128 threads, one per channel.
-__global__ void __launch_bounds__(kHeadDim)
-decode_merge_kernel(const int32_t* __restrict__ offsets, int G, const float* __restrict__ ws_acc,
-                    const float* __restrict__ ws_m, const float* __restrict__ ws_l,
-                    float* __restrict__ out, float* __restrict__ lse) {
-  const int s = blockIdx.x / G;
-  const int h = blockIdx.x - s * G;
-  const int ch = threadIdx.x;
+// Merge of the per-piece partials of one segment; also zeroes the output of empty segments.
+// Each thread owns one output element (query head h, channel ch); a segment takes
+// ceil(G * 128 / 256) blocks.  The kernel is a short chain of dependent memory latencies, so
+// the partials of up to eight pieces are loaded together and folded in with a running maximum:
+// the chain is the offsets load plus one round per eight pieces.
+__global__ void __launch_bounds__(kDecThreads)
+decode_merge_kernel(const int32_t* __restrict__ offsets, int G, int blocks_per_segment, int chunk_rows,
+                    const float* __restrict__ ws_acc, const float* __restrict__ ws_m,
+                    const float* __restrict__ ws_l, float* __restrict__ out, float* __restrict__ lse) {
+  const int s = blockIdx.x / blocks_per_segment;
+  const int o = (blockIdx.x - s * blocks_per_segment) * kDecThreads + threadIdx.x;
+  if (o >= G * kHeadDim) return;
+  const int h = o / kHeadDim, ch = o - h * kHeadDim;
   const int64_t a = offsets[s], b = offsets[s + 1];
   const size_t row = (size_t)s * G + h;
   if (b <= a) {   // empty segment: zero output, lse = -inf
@@ -191,23 +267,49 @@ decode_merge_kernel(const int32_t* __restrict__ offsets, int G, const float* __r
     if (ch == 0 && lse != nullptr) lse[row] = -INFINITY;
     return;
   }
-  const int c_first = (int)(a / kDecChunk), c_last = (int)((b - 1) / kDecChunk);
+  const int c_first = (int)(a / chunk_rows), c_last = (int)((b - 1) / chunk_rows);
   if (c_first == c_last) return;   // a whole segment inside one chunk was finished by the first kernel
-  float mx = -INFINITY;
-  for (int cc = c_first; cc <= c_last; ++cc) mx = fmaxf(mx, ws_m[((size_t)s + cc) * G + h]);
-  float num = 0.f, den = 0.f;
-  for (int cc = c_first; cc <= c_last; ++cc) {
-    const size_t slot = (size_t)s + cc;
-    const float wgt = fast_exp2(ws_m[slot * G + h] - mx);
-    num = fmaf(ws_acc[(slot * G + h) * kHeadDim + ch], wgt, num);
-    den = fmaf(ws_l[slot * G + h], wgt, den);
+  constexpr int kU = 8;
+  float mx = -INFINITY, num = 0.f, den = 0.f;
+  for (int c0 = c_first; c0 <= c_last; c0 += kU) {
+    float mv[kU], lv[kU], av[kU];
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const int cc = min(c0 + u, c_last);
+      const size_t sl = (size_t)s + cc;
+      mv[u] = ws_m[sl * G + h];
+      lv[u] = ws_l[sl * G + h];
+      av[u] = ws_acc[(sl * G + h) * kHeadDim + ch];
+    }
+    float mnew = mx;
+#pragma unroll
+    for (int u = 0; u < kU; ++u) mnew = fmaxf(mnew, mv[u]);   // finite: every piece holds at least one row
+    const float keep = fast_exp2(mx - mnew);                   // 0 in the first round
+    num *= keep;
+    den *= keep;
+    mx = mnew;
+#pragma unroll
+    for (int u = 0; u < kU; ++u) {
+      const float wgt = c0 + u <= c_last ? fast_exp2(mv[u] - mx) : 0.f;
+      num = fmaf(av[u], wgt, num);
+      den = fmaf(lv[u], wgt, den);
+    }
   }
   out[row * kHeadDim + ch] = num / den;
   if (ch == 0 && lse != nullptr) lse[row] = mx * kLn2 + __logf(den);
 }
 
-size_t decode_slots(int n_segments, int64_t total_kept) {
-  return (size_t)n_segments + (size_t)((total_kept + kDecChunk - 1) / kDecChunk);
+// Rows per block: a multiple of the wave tile, sized for LKV_DEC_TARGET_BLOCKS blocks.
+int decode_chunk_rows(int64_t total_kept) {
+  int64_t c = (total_kept + LKV_DEC_TARGET_BLOCKS - 1) / LKV_DEC_TARGET_BLOCKS;
+  c = (c + kDecTile - 1) / kDecTile * kDecTile;
+  if (c < LKV_DEC_MIN_CHUNK) c = LKV_DEC_MIN_CHUNK;
+  return (int)c;
+}
+
+static size_t decode_slots(int n_segments, int64_t total_kept) {
+  const int chunk = decode_chunk_rows(total_kept);
+  return (size_t)n_segments + (size_t)((total_kept + chunk - 1) / chunk);
 }
 
 size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G) {
@@ -216,53 +318,32 @@ size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G) {
   return (bytes + 255) & ~(size_t)255;
 }
 
-template <int G>
-static hipError_t launch_decode_g(const void* q, const void* kp, const void* vp, const int32_t* offsets,
-                                  int n_segments, int64_t total_kept, float scale, float* out, float* lse,
-                                  float* ws, hipStream_t stream) {
-  const size_t slots = decode_slots(n_segments, total_kept);
-  float* ws_acc = ws;
-  float* ws_m = ws + slots * G * kHeadDim;
-  float* ws_l = ws_m + slots * G;
-  const size_t lds = sizeof(DecShared<G>);
-  const int chunks = (int)((total_kept + kDecChunk - 1) / kDecChunk);
-  if (chunks > 0) {
-    hipLaunchKernelGGL(decode_partial_kernel<G>, dim3(chunks), dim3(kDecThreads), lds, stream,
-                       reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint4*>(kp),
-                       reinterpret_cast<const uint4*>(vp), offsets, n_segments, total_kept, scale, out, lse,
-                       ws_acc, ws_m, ws_l);
-  }
-  hipLaunchKernelGGL(decode_merge_kernel, dim3(n_segments * G), dim3(kHeadDim), 0, stream, offsets, G,
-                     ws_acc, ws_m, ws_l, out, lse);
-  return hipGetLastError();
-}
-
-// The LDS block of the larger groups exceeds the default 64 KB limit per workgroup.
+// The four staging tiles exceed the default 64 KB of LDS per workgroup.
 hipError_t decode_prepare() {
-#define LKV_DEC_PREP(g)                                                                              \
-  {                                                                                                  \
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel<g>),      \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize,                   \
-                                       (int)sizeof(DecShared<g>));                                   \
-    if (e != hipSuccess) return e;                                                                   \
-  }
-  LKV_DEC_PREP(1) LKV_DEC_PREP(2) LKV_DEC_PREP(3) LKV_DEC_PREP(4)
-  LKV_DEC_PREP(5) LKV_DEC_PREP(6) LKV_DEC_PREP(7) LKV_DEC_PREP(8)
-#undef LKV_DEC_PREP
-  return hipSuccess;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kDecWaves * kDecWaveLds);
 }
 
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
                          int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
                          hipStream_t stream) {
-#define LKV_DEC_CASE(g) \
-  case g: return launch_decode_g<g>(q, kp, vp, offsets, n_segments, total_kept, scale, out, lse, ws, stream);
-  switch (G) {
-    LKV_DEC_CASE(1) LKV_DEC_CASE(2) LKV_DEC_CASE(3) LKV_DEC_CASE(4)
-    LKV_DEC_CASE(5) LKV_DEC_CASE(6) LKV_DEC_CASE(7) LKV_DEC_CASE(8)
-    default: return hipErrorInvalidValue;
+  if (G < 1 || G > kDecMaxGroup) return hipErrorInvalidValue;
+  const size_t slots = decode_slots(n_segments, total_kept);
+  float* ws_acc = ws;
+  float* ws_m = ws + slots * G * kHeadDim;
+  float* ws_l = ws_m + slots * G;
+  const int chunk_rows = decode_chunk_rows(total_kept);
+  const int chunks = (int)((total_kept + chunk_rows - 1) / chunk_rows);
+  if (chunks > 0) {
+    hipLaunchKernelGGL(decode_partial_kernel, dim3(chunks), dim3(kDecThreads), kDecWaves * kDecWaveLds, stream,
+                       reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint4*>(kp),
+                       reinterpret_cast<const uint4*>(vp), offsets, n_segments, total_kept, chunk_rows, G, scale,
+                       out, lse, ws_acc, ws_m, ws_l);
   }
-#undef LKV_DEC_CASE
+  const int blocks_per_segment = (G * kHeadDim + kDecThreads - 1) / kDecThreads;
+  hipLaunchKernelGGL(decode_merge_kernel, dim3(n_segments * blocks_per_segment), dim3(kDecThreads), 0, stream,
+                     offsets, G, blocks_per_segment, chunk_rows, ws_acc, ws_m, ws_l, out, lse);
+  return hipGetLastError();
 }
 
 }  // namespace lkv

@@ -16,6 +16,7 @@ namespace {
 
 constexpr int kStageSlots = 8;
 constexpr size_t kStageBytes = 1u << 20;   // 1 MiB per slot: up to 262143 segments
+constexpr int64_t kMaxSegments = (int64_t)(kStageBytes / sizeof(int32_t)) - 1;
 
 }  // namespace
 
@@ -113,6 +114,7 @@ void lkv_destroy(lkv_ctx* ctx) {
     }
     if (ctx->stage[i] != nullptr) (void)hipHostFree(ctx->stage[i]);
   }
+
   delete ctx;
 }
 
@@ -296,7 +298,7 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
   const int G = n_q_heads / n_kv_heads;
   if (G > lkv::kDecodeMaxGroup) return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", G, lkv::kDecodeMaxGroup);
   const int64_t n_seg = (int64_t)n_seq * n_layers * n_kv_heads;
-  if (n_seg >= (int64_t)1 << 28) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  if (n_seg > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
   if (total_kept < 0 || total_kept >= (int64_t)1 << 31)
     return fail(ctx, LKV_ERR_INVALID_ARG, "total_kept = %lld is outside [0, 2^31)", (long long)total_kept);
   if (q == nullptr || offsets == nullptr || out == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q, offsets or out is NULL");

@@ -63,6 +63,23 @@ __device__ __forceinline__ float row16_allreduce_sum(float x) {
   return x;
 }
 
+// Largest s in [0, n - 1] with table[s] <= p, for a non-decreasing table with table[0] <= p.
+// The whole wave takes part (p must be wave-uniform): 64 probes per round, so two rounds
+// of loads cover 4096 entries where a binary search needs twelve dependent ones.
+__device__ __forceinline__ int wave_upper_segment(const int32_t* __restrict__ table, int n, int64_t p, int lane) {
+  int lo = 0, len = n;
+  while (len > 1) {
+    const int step = (len + 63) >> 6;
+    const int i = lo + lane * step;
+    const bool le = i < lo + len && (int64_t)table[i] <= p;
+    const int cnt = __popcll(__ballot(le));   // >= 1 because table[lo] <= p
+    const int new_lo = lo + (cnt - 1) * step;
+    len = min(step, lo + len - new_lo);
+    lo = new_lo;
+  }
+  return lo;
+}
+
 // 16-byte load of cache data that this kernel reads exactly once.
 __device__ __forceinline__ uint4 load_stream16(const uint4* p) {
 #ifdef LKV_NONTEMPORAL_LOADS

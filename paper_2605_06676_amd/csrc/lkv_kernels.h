@@ -28,7 +28,7 @@ void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offs
                     hipStream_t stream);
 
 // decode.hip
-constexpr int kDecodeMaxGroup = 8;
+constexpr int kDecodeMaxGroup = 16;
 hipError_t decode_prepare();
 size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G);
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
