@@ -124,11 +124,9 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
         int row = t * kDecTile + 4 * j + r;
-        const bool ok = row < n_rows;
-        row = ok ? row : n_rows - 1;
+        row = row < n_rows ? row : n_rows - 1;   // rows past the piece re-read its last row; zeroed when staged
         kk[j] = load_stream16(kp + (a + row) * kChunksPerRow + c);
         vv[j] = load_stream16(vp + (a + row) * kChunksPerRow + c);
-        if (!ok) { kk[j] = make_uint4(0, 0, 0, 0); vv[j] = make_uint4(0, 0, 0, 0); }
       }
     };
     if (wave < n_tiles) load_tile(wave);
@@ -136,10 +134,21 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
 #pragma unroll 1
     for (int t = wave; t < n_tiles; t += kDecWaves) {
       // stage 32 rows: row 4j + r, piece c
+      if ((t + 1) * kDecTile <= n_rows) {   // wave-uniform: a full tile
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        *reinterpret_cast<uint4*>(k_lds + (4 * j + r) * kDecKStride + c * 16) = kk[j];
-        *reinterpret_cast<uint4*>(v_lds + (4 * j + r) * kDecVStride + c * 16) = vv[j];
+        for (int j = 0; j < 8; ++j) {
+          *reinterpret_cast<uint4*>(k_lds + (4 * j + r) * kDecKStride + c * 16) = kk[j];
+          *reinterpret_cast<uint4*>(v_lds + (4 * j + r) * kDecVStride + c * 16) = vv[j];
+        }
+      } else {   // last tile of the piece: zero the rows past its end
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const uint32_t keep = t * kDecTile + 4 * j + r < n_rows ? 0xffffffffu : 0u;
+          *reinterpret_cast<uint4*>(k_lds + (4 * j + r) * kDecKStride + c * 16) =
+              make_uint4(kk[j].x & keep, kk[j].y & keep, kk[j].z & keep, kk[j].w & keep);
+          *reinterpret_cast<uint4*>(v_lds + (4 * j + r) * kDecVStride + c * 16) =
+              make_uint4(vv[j].x & keep, vv[j].y & keep, vv[j].z & keep, vv[j].w & keep);
+        }
       }
       if (t + kDecWaves < n_tiles) load_tile(t + kDecWaves);   // prefetch
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
