@@ -34,6 +34,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the Llama-3-8B-shaped 32k cache)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy before the timed region (a kernel of known "
+                         "traffic for scaling hardware byte counters under rocprofv3 --pmc)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time cap of the oracle sample")
     return ap.parse_args()
 
@@ -103,6 +106,13 @@ def main():
         lkv.lkv_decode_attn(ctx, w.n_seq, w.L, w.H, w.Hq, w.d, q, kp, vp, offsets, total, scale, out, lse, ws)
         if ev: ev[4].record()
 
+    if args.calibrate_copy:
+        src = torch.zeros((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()

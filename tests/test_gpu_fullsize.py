@@ -1,0 +1,162 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The whole workload is generated on the GPU and run through the four calls exactly as in
+bench.py.  The oracle cannot redo tens of millions of rows in test time, so it recomputes a
+sample: whole (layer, head) segments -- the first and last layer plus the heads with the
+smallest and the largest budget -- copied back to the host, so both sides see identical bytes.
+For every sampled head the scores are compared to the stated tolerance, the kept indices and
+the packed rows must match bit for bit (selection on the GPU's own scores), and the decode
+output of its query heads must match to the stated tolerance.  Properties that hold at any
+size are checked over the whole output: offsets, index ranges and order, finite outputs.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lkv_oracle as O
+from paper_2605_06676_amd import lkv
+from paper_2605_06676_amd import workloads as W
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(t):
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def _run_full(w):
+    dev = torch.device("cuda:0")
+    ctx = lkv.Context(0)
+    Ts = [int(t) for t in W.seq_lengths(w)]
+    Ks, Vs = [], []
+    for s, T in enumerate(Ts):
+        k, v = W.device_kv(w, T, s, dev)
+        Ks.append(k); Vs.append(v)
+    cache = lkv.Cache(Ks, Vs, w.Hq)
+    sc = W.draw_scorer(w)
+    scorer = G.scorer_to_gpu(sc)
+    budgets = [W.draw_budgets(w, T, s) for s, T in enumerate(Ts)]
+    flat = np.concatenate([b.reshape(-1) for b in budgets]).astype(np.int32)
+    total = int(flat.sum())
+    scores = [torch.empty((w.L, w.H, T), dtype=torch.float32, device=dev) for T in Ts]
+    idx = torch.empty((total,), dtype=torch.int32, device=dev)
+    offsets = torch.empty((cache.n_segments + 1,), dtype=torch.int32, device=dev)
+    kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
+    vp = torch.empty_like(kp)
+    qbits = [W.draw_q(w, s) for s in range(w.n_seq)]
+    q = torch.stack([G.bits_to_bf16_gpu(x) for x in qbits]).contiguous()
+    out = torch.full((w.n_seq, w.L, w.Hq, w.d), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((w.n_seq, w.L, w.Hq), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.empty((lkv.lkv_decode_workspace_bytes(cache.n_segments, total, w.Hq, w.H),), dtype=torch.uint8, device=dev)
+    lkv.lkv_score(ctx, cache, scorer, scores)
+    lkv.lkv_select(ctx, cache, scores, flat, idx, offsets)
+    lkv.lkv_compact(ctx, cache, idx, offsets, total, kp, vp)
+    lkv.lkv_decode_attn(ctx, w.n_seq, w.L, w.H, w.Hq, w.d, q, kp, vp, offsets, total, G.SCALE, out, lse, ws)
+    torch.cuda.synchronize()
+    return dict(w=w, Ts=Ts, Ks=Ks, Vs=Vs, sc=sc, budgets=budgets, flat=flat, total=total, scores=scores, idx=idx,
+                offsets=offsets, kp=kp, vp=vp, qbits=qbits, out=out, lse=lse, ctx=ctx)
+
+
+def _check_global_properties(r):
+    w = r["w"]
+    off = r["offsets"].cpu().numpy().astype(np.int64)
+    assert np.array_equal(off, np.concatenate([[0], np.cumsum(r["flat"].astype(np.int64))]))
+    idx = r["idx"]
+    # indices inside every segment are strictly ascending and inside [0, T)
+    seg_T = np.repeat(np.asarray(r["Ts"]), w.L * w.H)
+    assert int(idx.min()) >= 0
+    d = (idx[1:] - idx[:-1]).cpu().numpy()
+    starts = off[1:-1]
+    inner = np.ones(d.size, dtype=bool)
+    inner[starts[(starts > 0) & (starts < idx.numel())] - 1] = False
+    assert np.all(d[inner] > 0)
+    last = idx.cpu().numpy()[np.maximum(off[1:] - 1, 0)]
+    assert np.all((last < seg_T) | (r["flat"] == 0))
+    assert bool(torch.isfinite(r["out"]).all())
+    assert bool(torch.isfinite(r["lse"]).all()) or (r["flat"] == 0).any()
+    assert r["total"] / sum(w.L * w.H * T for T in r["Ts"]) <= w.R
+
+
+def _check_sampled_heads(r, seq, heads):
+    w = r["w"]
+    T = r["Ts"][seq]
+    off = r["offsets"].cpu().numpy().astype(np.int64)
+    sc_o = G.scorer_to_oracle(r["sc"])
+    Hs = r["sc"]["w1"].shape[1]
+    worst_s = worst_d = 0.0
+    for (l, h) in heads:
+        seg = (seq * w.L + l) * w.H + h
+        Kb = _bits(r["Ks"][seq][l, h])[None, None]          # [1, 1, T, d]
+        Vb = _bits(r["Vs"][seq][l, h])[None, None]
+        hs = h if Hs == w.H else 0
+        one = {"kind": sc_o["kind"], "act": sc_o["act"], "w1": sc_o["w1"][l:l + 1, hs:hs + 1],
+               "b1": sc_o["b1"][l:l + 1, hs:hs + 1],
+               "w2": None if sc_o["w2"] is None else sc_o["w2"][l:l + 1, hs:hs + 1],
+               "b2": None if sc_o["b2"] is None else sc_o["b2"][l:l + 1, hs:hs + 1]}
+        u_ref = O.score(O.bf16_bits_to_f64(Kb), O.bf16_bits_to_f64(Vb), one)[0, 0]
+        u_gpu = r["scores"][seq][l, h].cpu().numpy()
+        worst_s = max(worst_s, G.assert_scores_close(u_gpu[None], u_ref[None], f"seq {seq} layer {l} head {h}"))
+        b = int(r["budgets"][seq][l, h])
+        idx_ref = O.select(u_gpu, b)
+        lo, hi = int(off[seg]), int(off[seg + 1])
+        assert hi - lo == b
+        assert np.array_equal(r["idx"][lo:hi].cpu().numpy(), idx_ref), f"indices of segment {seg}"
+        Kp_ref, Vp_ref = O.compact(Kb, Vb, idx_ref, np.array([0, b]))
+        assert np.array_equal(_bits(r["kp"][lo:hi]), Kp_ref), f"packed K of segment {seg}"
+        assert np.array_equal(_bits(r["vp"][lo:hi]), Vp_ref), f"packed V of segment {seg}"
+        g = w.g
+        qh = O.bf16_bits_to_f64(r["qbits"][seq][l, h * g:(h + 1) * g])[None]      # [1, g, d]
+        o_ref, lse_ref = O.decode_attn(qh, O.bf16_bits_to_f64(Kp_ref), O.bf16_bits_to_f64(Vp_ref),
+                                       np.array([0, b]), 1, G.SCALE)
+        o_gpu = r["out"][seq, l, h * g:(h + 1) * g].cpu().numpy()
+        lse_gpu = r["lse"][seq, l, h * g:(h + 1) * g].cpu().numpy()
+        worst_d = max(worst_d, G.assert_decode_close(o_gpu, lse_gpu, o_ref[0], lse_ref[0], f"decode of segment {seg}"))
+    return worst_s, worst_d
+
+
+def _sample(r, seq, n_layers_sample=2):
+    w = r["w"]
+    b = r["budgets"][seq]
+    heads = {(0, h) for h in range(w.H)} | {(w.L - 1, h) for h in range(w.H)}
+    lmin, hmin = np.unravel_index(np.argmin(b), b.shape)
+    lmax, hmax = np.unravel_index(np.argmax(b), b.shape)
+    heads |= {(int(lmin), int(hmin)), (int(lmax), int(hmax)), (w.L // 2, 0)}
+    return sorted(heads)
+
+
+@pytest.mark.parametrize("cid", [1, 2])
+def test_full_size_single_sequence(cid):
+    w = W.CONFIGS[cid]
+    r = _run_full(w)
+    _check_global_properties(r)
+    ws, wd = _check_sampled_heads(r, 0, _sample(r, 0))
+    print(f"cfg{cid}: kept {r['total']}, worst score error {ws:.3g} x tol, worst decode error {wd:.3g} x tol")
+    r["ctx"].close()
+
+
+def test_full_size_batched_heterogeneous():
+    w = W.CONFIGS[3]
+    r = _run_full(w)
+    _check_global_properties(r)
+    for seq in (0, w.n_seq - 1, int(np.argmin(r["Ts"])), int(np.argmax(r["Ts"]))):
+        b = r["budgets"][seq]
+        lmax, hmax = np.unravel_index(np.argmax(b), b.shape)
+        _check_sampled_heads(r, seq, [(0, 0), (w.L - 1, w.H - 1), (int(lmax), int(hmax))])
+    r["ctx"].close()
+
+
+def test_full_size_group7_shared_budgets():
+    w = W.CONFIGS[4]
+    r = _run_full(w)
+    _check_global_properties(r)
+    b = r["budgets"][0]
+    assert int(b.max()) == w.T      # at least one head keeps everything: the b = T path at full size
+    lmax, hmax = np.unravel_index(np.argmax(b), b.shape)
+    lmin, hmin = np.unravel_index(np.argmin(b), b.shape)
+    for seq in (0, w.n_seq - 1):
+        _check_sampled_heads(r, seq, [(0, 0), (int(lmax), int(hmax)), (int(lmin), int(hmin)), (w.L - 1, w.H - 1)])
+    r["ctx"].close()
