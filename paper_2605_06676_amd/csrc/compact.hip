@@ -27,28 +27,28 @@ compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __r
   const int c = threadIdx.x & 15;
 #pragma unroll 1
   for (int it = 0; it < kCompactRowsPerBlock / 16; it += kCompactUnroll) {
+    // Loads are unconditional (a row past the end re-reads the last packed row) so that the
+    // staged rows stay in registers; only the stores are predicated.
     uint4 kk[kCompactUnroll], vv[kCompactUnroll];
     bool live[kCompactUnroll];
 #pragma unroll
     for (int u = 0; u < kCompactUnroll; ++u) {
-      const int64_t p = p0 + (it + u) * 16 + rslot;
-      live[u] = false;
-      if (p < total_kept) {
-        int s = s0;
-        while ((int64_t)offsets[s + 1] <= p) ++s;     // skips empty segments too; p < offsets[n_segments]
-        const int seq = s / heads_per_seq;
-        const int lh = s - seq * heads_per_seq;
-        const int sl = seq - seq_lo;                  // this launch describes sequences seq_lo .. seq_lo + tab.n - 1
-        if (sl >= 0 && sl < tab.n) {
-          // a token index outside [0, T) cannot come from lkv_select; it is clamped, never followed
-          const int T = tab.T[sl];
-          const int tok = min(max(idx[p], 0), T - 1);
-          const size_t src = ((size_t)lh * (size_t)T + (size_t)tok) * kChunksPerRow + c;
-          kk[u] = reinterpret_cast<const uint4*>(tab.k[sl])[src];
-          vv[u] = reinterpret_cast<const uint4*>(tab.v[sl])[src];
-          live[u] = true;
-        }
-      }
+      int64_t p = p0 + (it + u) * 16 + rslot;
+      live[u] = p < total_kept;
+      p = live[u] ? p : total_kept - 1;
+      int s = s0;
+      while ((int64_t)offsets[s + 1] <= p) ++s;     // skips empty segments too; p < offsets[n_segments]
+      const int seq = s / heads_per_seq;
+      const int lh = s - seq * heads_per_seq;
+      int sl = seq - seq_lo;                        // this launch describes sequences seq_lo .. seq_lo + tab.n - 1
+      live[u] = live[u] && sl >= 0 && sl < tab.n;
+      sl = min(max(sl, 0), tab.n - 1);
+      // a token index outside [0, T) cannot come from lkv_select; it is clamped, never followed
+      const int T = tab.T[sl];
+      const int tok = min(max(idx[p], 0), T - 1);
+      const size_t src = ((size_t)lh * (size_t)T + (size_t)tok) * kChunksPerRow + c;
+      kk[u] = reinterpret_cast<const uint4*>(tab.k[sl])[src];
+      vv[u] = reinterpret_cast<const uint4*>(tab.v[sl])[src];
     }
 #pragma unroll
     for (int u = 0; u < kCompactUnroll; ++u) {
