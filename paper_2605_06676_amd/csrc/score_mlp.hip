@@ -15,8 +15,8 @@
 //  * The accumulator layout leaves each lane with 4 hidden units of one token
 //    per M tile, so bias (as the initial accumulator), activation and the dot
 //    with w2 are per-lane work, finished by two cross-lane adds.
-// The next 16 tokens are prefetched into registers while the current 16 are
-// multiplied.
+// The next two 16-token tiles are prefetched into registers while the current
+// one is multiplied; b1 and w2 are read from LDS.
 #include "lkv_common.h"
 
 namespace lkv {
@@ -34,13 +34,31 @@ constexpr int kMlpKSteps = 8;                         // 256 features / 32 per M
 constexpr int kActSilu = 0;
 constexpr int kActGelu = 1;
 
+// Exact-form GELU, 0.5 z (1 + erf(z / sqrt 2)), branch free.  erf uses the five-term rational
+// approximation 7.1.26 of Abramowitz & Stegun, erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),
+// t = 1 / (1 + p x) for x >= 0, absolute error below 1.5e-7 (plus fp32 rounding).  Written as
+// max(z, 0) - |z|/2 * poly(t) * exp(-z^2/2), which has no cancellation for negative z.  The
+// library erff costs several times more issue slots (and branches), which made the kernel
+// VALU-bound instead of HBM-bound.
+__device__ __forceinline__ float gelu_erf(float z) {
+  const float az = fabsf(z);
+  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, az, 1.0f));
+  float p = fmaf(1.061405429f, t, -1.453152027f);
+  p = fmaf(p, t, 1.421413741f);
+  p = fmaf(p, t, -0.284496736f);
+  p = fmaf(p, t, 0.254829592f);
+  p *= t;
+  const float e = __builtin_amdgcn_exp2f((z * z) * (-0.5f * 1.4426950408889634f));   // exp(-z^2 / 2)
+  return fmaf(-0.5f * az, p * e, fmaxf(z, 0.f));
+}
+
 template <int kAct>
 __device__ __forceinline__ float activation(float z) {
   if (kAct == kActSilu) {
     // z * sigmoid(z); exp2 overflow for very negative z gives rcp(inf) = 0
     return z * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
   } else {
-    return 0.5f * z * (1.f + erff(z * 0.70710678118654752f));
+    return gelu_erf(z);
   }
 }
 
@@ -80,57 +98,60 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
       for (int ks = 0; ks < kMlpKSteps; ++ks)
         wfrag[mt][ks] = as_bf16x8(wbase[(size_t)(mt * 16 + c) * 32 + ks * 4 + r]);
   }
-  // accumulator rows of this lane: hidden units 16 mt + 4 r + e
-  float bias1[MT][4], wout[MT][4];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      bias1[mt][e] = b1[(size_t)scorer * HID + mt * 16 + 4 * r + e];
-      wout[mt][e] = w2[(size_t)scorer * HID + mt * 16 + 4 * r + e];
-    }
+  // b1 and w2 live in LDS (block-shared): lane (r, c) needs hidden units 16 mt + 4 r + e, which
+  // are 16-byte groups, so each is one broadcast LDS read per M tile.  Keeping them out of the
+  // register file leaves room for a second prefetch buffer.
+  float* par_lds = reinterpret_cast<float*>(smem + kMlpWaves * kMlpWaveLds);   // b1[HID] then w2[HID]
+  for (int i = threadIdx.x; i < 2 * HID; i += kMlpThreads)
+    par_lds[i] = i < HID ? b1[(size_t)scorer * HID + i] : w2[(size_t)scorer * HID + i - HID];
   const float bias2 = b2 != nullptr ? b2[scorer] : 0.f;
+  __syncthreads();
 
   const size_t head_row0 = (size_t)lh * (size_t)T;
   const uint4* Kh = reinterpret_cast<const uint4*>(tab.k[seq]) + head_row0 * kChunksPerRow;
   const uint4* Vh = reinterpret_cast<const uint4*>(tab.v[seq]) + head_row0 * kChunksPerRow;
   float* out = tab.scores[seq] + head_row0;
 
-  const int rows_per_wave = rows_per_block / kMlpWaves;          // a multiple of 16
-  const int wave_row0 = tile * rows_per_block + wave * rows_per_wave;
-  const int wave_row1 = min(T, wave_row0 + rows_per_wave);
-  if (wave_row0 >= wave_row1) return;
+  // The four waves of a block interleave 16-row tiles: tile i of wave w covers rows
+  // block_row0 + 64 i + 16 w, so that the block as a whole reads 16 KB of K and 16 KB of V
+  // contiguously at a time (DRAM pages are used better than with four distant 4 KB streams).
+  constexpr int kStep = kMlpWaves * kMlpTokTile;                 // 64 rows between a wave's tiles
+  const int wave_row0 = tile * rows_per_block + wave * kMlpTokTile;
+  const int wave_row1 = min(T, tile * rows_per_block + rows_per_block);
+  if (wave_row0 >= wave_row1) return;   // after the only block barrier
 
-  uint4 kk[4], vv[4];
-  auto load_tile = [&](int row0) {
+  // Two register buffers of 16 rows each: while one tile is multiplied, the loads of the next
+  // two are in flight (16 KB per wave), which is what it takes to keep HBM busy at two waves
+  // per SIMD.
+  uint4 ka[4], va[4], kb[4], vb[4];
+  auto load_tile = [&](uint4 (&kk)[4], uint4 (&vv)[4], int row0) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int row = row0 + 4 * j + r;
-      row = row < T ? row : T - 1;
+      row = row < T ? row : T - 1;   // ragged tail: re-read the last row, result unused
       kk[j] = load_stream16(Kh + (size_t)row * kChunksPerRow + c);
       vv[j] = load_stream16(Vh + (size_t)row * kChunksPerRow + c);
     }
   };
-  load_tile(wave_row0);
-
-#pragma unroll 1
-  for (int row0 = wave_row0; row0 < wave_row1; row0 += kMlpTokTile) {
-    // stage the 16 rows: row 4j + r, key piece c at byte 16c, value piece c at byte 256 + 16c
+  auto stage_tile = [&](const uint4 (&kk)[4], const uint4 (&vv)[4]) {
+    // row 4j + r, key piece c at byte 16c, value piece c at byte 256 + 16c
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       unsigned char* rowp = tile_lds + (4 * j + r) * kMlpRowStride + c * 16;
       *reinterpret_cast<uint4*>(rowp) = kk[j];
       *reinterpret_cast<uint4*>(rowp + 256) = vv[j];
     }
-    if (row0 + kMlpTokTile < wave_row1) load_tile(row0 + kMlpTokTile);   // prefetch
-    // the tile is private to this wave: order the LDS writes before the reads
+  };
+  auto wave_lds_sync = [&]() {   // the tile is private to this wave: order its LDS accesses, no barrier
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
     __builtin_amdgcn_wave_barrier();
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
+  };
+  auto multiply_tile = [&](int row0) {
+    wave_lds_sync();
     f32x4_t acc[MT];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4_t{bias1[mt][0], bias1[mt][1], bias1[mt][2], bias1[mt][3]};
+    for (int mt = 0; mt < MT; ++mt) acc[mt] = *reinterpret_cast<const f32x4_t*>(par_lds + mt * 16 + 4 * r);   // bias
 #pragma unroll
     for (int ks = 0; ks < kMlpKSteps; ++ks) {
       // B fragment: token c, features 32 ks + 8 r .. +7  = bytes 64 ks + 16 r of the staged row
@@ -142,23 +163,39 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
     }
     float part = 0.f;
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+      const f32x4_t wo = *reinterpret_cast<const f32x4_t*>(par_lds + HID + mt * 16 + 4 * r);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) part = fmaf(wout[mt][e], activation<kAct>(acc[mt][e]), part);
+      for (int e = 0; e < 4; ++e) part = fmaf(wo[e], activation<kAct>(acc[mt][e]), part);
+    }
     // sum the four feature-block lanes of each token: lanes c, c+16, c+32, c+48
     part += __shfl_xor(part, 16, 64);
     part += __shfl_xor(part, 32, 64);
     const int row = row0 + c;
     if (r == 0 && row < T) out[row] = part + bias2;
-    // the next iteration overwrites the tile: order these reads before those writes
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    wave_lds_sync();   // the next staging overwrites the tile
+  };
+
+  load_tile(ka, va, wave_row0);
+  if (wave_row0 + kStep < wave_row1) load_tile(kb, vb, wave_row0 + kStep);
+#pragma unroll 1
+  for (int row0 = wave_row0; row0 < wave_row1; row0 += 2 * kStep) {
+    stage_tile(ka, va);
+    if (row0 + 2 * kStep < wave_row1) load_tile(ka, va, row0 + 2 * kStep);
+    multiply_tile(row0);
+    if (row0 + kStep < wave_row1) {
+      stage_tile(kb, vb);
+      if (row0 + 3 * kStep < wave_row1) load_tile(kb, vb, row0 + 3 * kStep);
+      multiply_tile(row0 + kStep);
+    }
   }
 }
 
 int score_mlp_rows_per_block(int T) {
   // large tiles amortise the 32 KB of W1 each wave loads; small heads keep more blocks
+#ifdef LKV_MLP_ROWS
+  if (T >= 16384) return LKV_MLP_ROWS;
+#endif
   if (T >= 16384) return 2048;
   if (T >= 4096) return 1024;
   return 256;
@@ -171,7 +208,7 @@ static void launch_mt(const SeqTable& tab, const uint16_t* w1, const float* b1, 
                       const float* b2, int act, int heads_per_scorer_row, int rows_per_block,
                       hipStream_t stream) {
   const int blocks = tab.first[tab.n];
-  const size_t lds = (size_t)kMlpWaves * kMlpWaveLds;
+  const size_t lds = (size_t)kMlpWaves * kMlpWaveLds + 2 * MT * 16 * sizeof(float);
   if (act == kActSilu)
     hipLaunchKernelGGL((score_mlp_kernel<MT, kActSilu>), dim3(blocks), dim3(kMlpThreads), lds, stream, tab,
                        w1, b1, w2, b2, heads_per_scorer_row, rows_per_block);

@@ -3,8 +3,6 @@
 //
 // One workgroup of 1024 threads per segment (sequence, layer, head).
 //   1. Scores are mapped to order-preserving uint32 keys (NaN -> -inf first).
-//      If the head fits, the keys are cached in LDS and every later pass reads
-//      LDS; otherwise the passes re-read the fp32 scores from L2 / memory.
 //   2. The key of the b-th largest score is found by a radix descent over the
 //      key bits in three levels of 11, 11 and 10 bits: an LDS histogram of the
 //      keys that still match the prefix, then a block-wide scan from the top
@@ -13,10 +11,22 @@
 //   3. Emission in ascending token order: a token is kept if key > thr, or if
 //      key == thr and fewer than `need` tokens with that key precede it.  Each
 //      wave owns a contiguous range of tokens; per-wave counts are scanned once
-//      across the block, then every wave writes its range using ballot prefix
-//      counts.  The lower-index tie rule and the ascending output order both
-//      fall out of this ordered scan; no atomics decide placement, so the
-//      result is unique and reproducible bit for bit.
+//      across the block, then every wave writes its range using prefix counts.
+//      The lower-index tie rule and the ascending output order both fall out of
+//      this ordered scan; no atomic decides a position, so the result is unique
+//      and reproducible bit for bit.
+// Where the keys live depends on the head length T:
+//   * T <= 36864: the keys are cached in LDS (144 KB) by one batched read of the
+//     scores; every later pass reads LDS.
+//   * T <= 589824: too long for LDS.  The three histogram passes re-read the
+//     scores (they sit in L2 / the memory-side cache right after scoring) with
+//     batched 16-byte loads; a fourth pass classifies every token against `thr`
+//     into two LDS bitmaps (greater / equal), and the ordered emission runs on
+//     the bitmaps, 2048 tokens per wave step.
+//   * longer heads: as above but the emission re-reads the scores in order.
+// All global reads are issued eight at a time per thread before any is used:
+// the kernel is latency-bound, not bandwidth-bound, so what counts is how few
+// dependent round trips each pass makes.
 #include "lkv_common.h"
 
 namespace lkv {
@@ -24,7 +34,10 @@ namespace lkv {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelBins = 2048;
-constexpr int kSelMaxCachedKeys = 36864;   // 144 KB of keys; with histogram and scan scratch < 160 KB LDS
+constexpr int kSelMaxCachedKeys = 36864;                    // 144 KB of keys
+constexpr int kSelMaxBitmapWords = kSelMaxCachedKeys / 2;   // two bitmaps in the same 144 KB
+constexpr int kSelMaxBitmapT = kSelMaxBitmapWords * 32;     // 589824 tokens
+constexpr int kSelBatch = 8;                                // loads in flight per thread
 
 __device__ __forceinline__ uint32_t order_key(float u) {
   uint32_t bits = __float_as_uint(u);
@@ -51,61 +64,94 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane) {
   return x;
 }
 
-template <bool kCached>
-__device__ __forceinline__ uint32_t key_at(const uint32_t* keys_lds, const float* u, int i) {
-  if (kCached) return keys_lds[i];
-  return order_key(u[i]);
+// Calls f(key, token) for every token of the head, in no particular order, reading the fp32
+// scores from global memory with kSelBatch loads in flight per thread (16-byte loads when the
+// head is 16-byte aligned and its length a multiple of four).
+template <typename F>
+__device__ __forceinline__ void for_each_global_key(const float* __restrict__ u, int T, F f) {
+  const int tid = threadIdx.x;
+  if ((T & 3) == 0 && (reinterpret_cast<uintptr_t>(u) & 15u) == 0) {
+    const float4* u4 = reinterpret_cast<const float4*>(u);
+    const int n4 = T >> 2;
+    for (int base = tid; base < n4; base += kSelThreads * kSelBatch) {
+      float4 v[kSelBatch];
+#pragma unroll
+      for (int k = 0; k < kSelBatch; ++k) {
+        const int i = base + k * kSelThreads;
+        v[k] = u4[i < n4 ? i : base];
+      }
+#pragma unroll
+      for (int k = 0; k < kSelBatch; ++k) {
+        const int i = base + k * kSelThreads;
+        if (i < n4) {
+          f(order_key(v[k].x), 4 * i);
+          f(order_key(v[k].y), 4 * i + 1);
+          f(order_key(v[k].z), 4 * i + 2);
+          f(order_key(v[k].w), 4 * i + 3);
+        }
+      }
+    }
+  } else {
+    for (int base = tid; base < T; base += kSelThreads * kSelBatch) {
+      float v[kSelBatch];
+#pragma unroll
+      for (int k = 0; k < kSelBatch; ++k) {
+        const int i = base + k * kSelThreads;
+        v[k] = u[i < T ? i : base];
+      }
+#pragma unroll
+      for (int k = 0; k < kSelBatch; ++k) {
+        const int i = base + k * kSelThreads;
+        if (i < T) f(order_key(v[k]), i);
+      }
+    }
+  }
 }
 
-template <bool kCached>
-__device__ void select_body(const float* __restrict__ u, int T, int budget, int32_t* __restrict__ out,
-                            SelShared& sh, uint32_t* keys_lds) {
+// One level of the radix descent.  `count(fn)` must call fn(key) for every key of the head.
+// On return prefix / prefix_mask / need are advanced by this level's digit.
+template <typename Count>
+__device__ __forceinline__ void descend_level(SelShared& sh, int level, uint32_t& prefix, uint32_t& prefix_mask,
+                                              uint32_t& need, Count count) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
+  const int shift = level == 0 ? 21 : (level == 1 ? 10 : 0);
+  const int nbins = level == 2 ? 1024 : 2048;
+  for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
+  __syncthreads();   // also orders an LDS key cache fill before its first use
+  const uint32_t pfx = prefix, msk = prefix_mask;
+  count([&](uint32_t key) {
+    if ((key & msk) == pfx) atomicAdd(&sh.hist[(key >> shift) & (nbins - 1)], 1u);
+  });
+  __syncthreads();
+  // scan the bins from the top: thread t owns bins nbins-1-2t and nbins-2-2t
+  uint32_t c0 = 0, c1 = 0;
+  const int top = nbins - 1 - 2 * tid;
+  if (top >= 0) c0 = sh.hist[top];
+  if (top - 1 >= 0) c1 = sh.hist[top - 1];
+  const uint32_t incl = wave_inclusive_scan(c0 + c1, lane);
+  if (lane == 63) sh.wave_tot[wave] = incl;
+  __syncthreads();
+  uint32_t before = 0;
+  for (int w = 0; w < wave; ++w) before += sh.wave_tot[w];
+  const uint32_t excl = before + incl - (c0 + c1);   // keys in bins above this thread's pair
+  // exactly one bin satisfies: above < need <= above + count
+  if (c0 && excl < need && need <= excl + c0) { sh.found_bin = (uint32_t)top; sh.found_above = excl; }
+  if (c1 && excl + c0 < need && need <= excl + c0 + c1) { sh.found_bin = (uint32_t)(top - 1); sh.found_above = excl + c0; }
+  __syncthreads();
+  prefix |= sh.found_bin << shift;
+  prefix_mask |= (uint32_t)(nbins - 1) << shift;
+  need -= sh.found_above;
+  __syncthreads();   // found_* and hist are rewritten at the next level
+}
 
-  if (kCached) {
-    for (int i = tid; i < T; i += kSelThreads) keys_lds[i] = order_key(u[i]);
-  }
-
-  // ---- radix descent for the threshold key ---------------------------------
-  uint32_t prefix = 0;        // bits of the threshold key decided so far
-  uint32_t prefix_mask = 0;   // which bits those are
-  uint32_t need = (uint32_t)budget;   // rank of the threshold among keys that match the prefix (1-based)
-#pragma unroll 1
-  for (int level = 0; level < 3; ++level) {
-    const int shift = level == 0 ? 21 : (level == 1 ? 10 : 0);
-    const int nbins = level == 2 ? 1024 : 2048;
-    for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
-    __syncthreads();   // also orders the key cache fill before its first use
-    for (int i = tid; i < T; i += kSelThreads) {
-      const uint32_t key = key_at<kCached>(keys_lds, u, i);
-      if ((key & prefix_mask) == prefix) atomicAdd(&sh.hist[(key >> shift) & (nbins - 1)], 1u);
-    }
-    __syncthreads();
-    // scan the bins from the top: thread t owns bins nbins-1-2t and nbins-2-2t
-    uint32_t c0 = 0, c1 = 0;
-    const int top = nbins - 1 - 2 * tid;
-    if (top >= 0) c0 = sh.hist[top];
-    if (top - 1 >= 0) c1 = sh.hist[top - 1];
-    const uint32_t incl = wave_inclusive_scan(c0 + c1, lane);
-    if (lane == 63) sh.wave_tot[wave] = incl;
-    __syncthreads();
-    uint32_t before = 0;
-    for (int w = 0; w < wave; ++w) before += sh.wave_tot[w];
-    const uint32_t excl = before + incl - (c0 + c1);   // keys in bins above this thread's pair
-    // exactly one bin satisfies: above < need <= above + count
-    if (c0 && excl < need && need <= excl + c0) { sh.found_bin = (uint32_t)top; sh.found_above = excl; }
-    if (c1 && excl + c0 < need && need <= excl + c0 + c1) { sh.found_bin = (uint32_t)(top - 1); sh.found_above = excl + c0; }
-    __syncthreads();
-    prefix |= sh.found_bin << shift;
-    prefix_mask |= (uint32_t)(nbins - 1) << shift;
-    need -= sh.found_above;
-    __syncthreads();   // found_* and hist are rewritten at the next level
-  }
-  const uint32_t thr = prefix;   // full 32-bit key of the budget-th largest score; keep `need` of its copies
-
-  // ---- ordered emission ------------------------------------------------------
+// Ordered emission from a per-token key source `key_of(i)` (LDS key cache, or global scores).
+template <typename KeyOf>
+__device__ __forceinline__ void emit_from_keys(SelShared& sh, int T, uint32_t thr, uint32_t need,
+                                               int32_t* __restrict__ out, KeyOf key_of) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
   // wave w owns tokens [w*per, (w+1)*per), per a multiple of 64
   const int per = ((T + kSelWaves - 1) / kSelWaves + 63) & ~63;
   const int lo = wave * per;
@@ -114,7 +160,7 @@ __device__ void select_body(const float* __restrict__ u, int T, int budget, int3
   for (int base = lo; base < hi; base += 64) {
     const int i = base + lane;
     const bool in = i < hi;
-    const uint32_t key = in ? key_at<kCached>(keys_lds, u, i) : 0u;
+    const uint32_t key = in ? key_of(i) : 0u;
     n_gt += __popcll(__ballot(in && key > thr));
     n_eq += __popcll(__ballot(in && key == thr));
   }
@@ -127,7 +173,7 @@ __device__ void select_body(const float* __restrict__ u, int T, int budget, int3
   for (int base = lo; base < hi; base += 64) {
     const int i = base + lane;
     const bool in = i < hi;
-    const uint32_t key = in ? key_at<kCached>(keys_lds, u, i) : 0u;
+    const uint32_t key = in ? key_of(i) : 0u;
     const bool is_eq = in && key == thr;
     const unsigned long long eq_mask = __ballot(is_eq);
     const unsigned long long below = (1ull << lane) - 1ull;
@@ -140,13 +186,72 @@ __device__ void select_body(const float* __restrict__ u, int T, int budget, int3
   }
 }
 
+// The `k` lowest set bits of x (k <= popcount(x)); a fixed five-step search, no lane divergence.
+__device__ __forceinline__ uint32_t lowest_set_bits(uint32_t x, uint32_t k) {
+  if (k >= (uint32_t)__popc(x)) return x;
+  // smallest m in [0, 31] with popcount(x & ((1 << m) - 1)) >= k  (m = 0 when k = 0)
+  int lo = -1, hi = 31;   // invariant: the prefix of length hi holds >= k bits, that of length lo (if >= 0) fewer
+#pragma unroll
+  for (int it = 0; it < 5; ++it) {
+    const int mid = (lo + hi + 1) >> 1;
+    if ((uint32_t)__popc(x & ((1u << mid) - 1u)) >= k) hi = mid; else lo = mid;
+  }
+  return x & ((1u << hi) - 1u);
+}
+
+// Ordered emission from the two LDS bitmaps (bit i of gt: key_i > thr; of eq: key_i == thr).
+__device__ __forceinline__ void emit_from_bitmaps(SelShared& sh, int T, uint32_t need, int32_t* __restrict__ out,
+                                                  const uint32_t* gt_map, const uint32_t* eq_map) {
+  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6;
+  const int n_words = (T + 31) >> 5;
+  const int per = ((n_words + kSelWaves - 1) / kSelWaves + 63) & ~63;   // words per wave, a multiple of 64
+  const int lo = wave * per;
+  const int hi = min(n_words, lo + per);
+  uint32_t n_gt = 0, n_eq = 0;
+  for (int w = lo + lane; w < hi; w += 64) { n_gt += __popc(gt_map[w]); n_eq += __popc(eq_map[w]); }
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) { n_gt += __shfl_xor(n_gt, d, 64); n_eq += __shfl_xor(n_eq, d, 64); }
+  if (lane == 0) { sh.wave_gt[wave] = n_gt; sh.wave_eq[wave] = n_eq; }
+  __syncthreads();
+  uint32_t gt_before = 0, eq_before = 0;
+  for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
+  uint32_t eq_seen = eq_before;
+  uint32_t pos = gt_before + min(eq_before, need);
+  for (int base = lo; base < hi; base += 64) {
+    const int w = base + lane;
+    const bool in = w < hi;
+    const uint32_t gtw = in ? gt_map[w] : 0u;
+    const uint32_t eqw = in ? eq_map[w] : 0u;
+    // copies of thr before this lane's word, and how many of this word's copies are still kept
+    const uint32_t eq_cnt = __popc(eqw);
+    const uint32_t eq_incl = wave_inclusive_scan(eq_cnt, lane);
+    const uint32_t eq_rank = eq_seen + eq_incl - eq_cnt;
+    const uint32_t take = eq_rank < need ? min(eq_cnt, need - eq_rank) : 0u;
+    const uint32_t keptw = gtw | lowest_set_bits(eqw, take);
+    const uint32_t cnt = __popc(keptw);
+    const uint32_t incl = wave_inclusive_scan(cnt, lane);
+    uint32_t p = pos + incl - cnt;
+    // every cross-lane exchange of this step happens before the lanes diverge in the write loop
+    pos += __shfl(incl, 63, 64);
+    eq_seen += __shfl(eq_incl, 63, 64);
+    uint32_t bits = keptw;
+    while (bits) {
+      out[p++] = (w << 5) + __builtin_ctz(bits);
+      bits &= bits - 1;
+    }
+  }
+}
+
 __global__ void __launch_bounds__(kSelThreads)
 select_kernel(SeqTable tab, const int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
-              int seg_base, int cached_limit /* heads of at most this many tokens use the LDS key cache */) {
+              int seg_base, int cached_limit /* heads of at most this many tokens use the LDS key cache */,
+              int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */) {
   extern __shared__ __align__(16) unsigned char smem[];
   SelShared& sh = *reinterpret_cast<SelShared*>(smem);
-  uint32_t* keys_lds = reinterpret_cast<uint32_t*>(smem + sizeof(SelShared));
+  uint32_t* region = reinterpret_cast<uint32_t*>(smem + sizeof(SelShared));
 
+  const int tid = threadIdx.x;
   const int local_seg = blockIdx.x;
   const int seq = seq_of_unit(tab, local_seg);
   const int lh = local_seg - tab.first[seq];
@@ -158,11 +263,44 @@ select_kernel(SeqTable tab, const int32_t* __restrict__ offsets, int32_t* __rest
   int32_t* out = idx + off;
   if (budget <= 0) return;
   if (budget >= T) {   // everything is kept
-    for (int i = threadIdx.x; i < T; i += kSelThreads) out[i] = i;
+    for (int i = tid; i < T; i += kSelThreads) out[i] = i;
     return;
   }
-  if (T <= cached_limit) select_body<true>(u, T, budget, out, sh, keys_lds);
-  else select_body<false>(u, T, budget, out, sh, keys_lds);
+
+  uint32_t prefix = 0;        // bits of the threshold key decided so far
+  uint32_t prefix_mask = 0;   // which bits those are
+  uint32_t need = (uint32_t)budget;   // rank of the threshold among keys that match the prefix (1-based)
+
+  if (T <= cached_limit) {
+    uint32_t* keys = region;
+    for_each_global_key(u, T, [&](uint32_t key, int i) { keys[i] = key; });
+    auto count = [&](auto fn) { for (int i = tid; i < T; i += kSelThreads) fn(keys[i]); };
+#pragma unroll 1
+    for (int level = 0; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
+    emit_from_keys(sh, T, prefix, need, out, [&](int i) { return keys[i]; });
+    return;
+  }
+
+  auto count = [&](auto fn) { for_each_global_key(u, T, [&](uint32_t key, int) { fn(key); }); };
+#pragma unroll 1
+  for (int level = 0; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
+  const uint32_t thr = prefix;   // full 32-bit key of the budget-th largest score; keep `need` of its copies
+
+  if (T <= bitmap_limit) {
+    const int n_words = (T + 31) >> 5;
+    uint32_t* gt_map = region;
+    uint32_t* eq_map = region + n_words;
+    for (int i = tid; i < 2 * n_words; i += kSelThreads) region[i] = 0;
+    __syncthreads();
+    for_each_global_key(u, T, [&](uint32_t key, int i) {
+      if (key > thr) atomicOr(&gt_map[i >> 5], 1u << (i & 31));
+      else if (key == thr) atomicOr(&eq_map[i >> 5], 1u << (i & 31));
+    });
+    __syncthreads();
+    emit_from_bitmaps(sh, T, need, out, gt_map, eq_map);
+  } else {
+    emit_from_keys(sh, T, thr, need, out, [&](int i) { return order_key(u[i]); });
+  }
 }
 
 hipError_t select_prepare() {
@@ -175,13 +313,18 @@ void launch_select(const SeqTable& tab, const int32_t* offsets, int32_t* idx, in
                    hipStream_t stream) {
   const int segs = tab.first[tab.n];
   if (segs <= 0) return;
-  // the LDS key cache is sized for the longest sequence of this launch that fits it
-  int cached_limit = 0;
-  for (int i = 0; i < tab.n; ++i)
-    if (tab.T[i] <= kSelMaxCachedKeys && tab.T[i] > cached_limit) cached_limit = tab.T[i];
-  const size_t lds = sizeof(SelShared) + (size_t)cached_limit * sizeof(uint32_t);
-  hipLaunchKernelGGL(select_kernel, dim3(segs), dim3(kSelThreads), lds, stream, tab, offsets, idx, seg_base,
-                     cached_limit);
+  // the LDS region is sized for the longest sequence of this launch that can use it
+  int cached_limit = 0, bitmap_limit = 0;
+  for (int i = 0; i < tab.n; ++i) {
+    const int T = tab.T[i];
+    if (T <= kSelMaxCachedKeys) { if (T > cached_limit) cached_limit = T; }
+    else if (T <= kSelMaxBitmapT) { if (T > bitmap_limit) bitmap_limit = T; }
+  }
+  size_t region = (size_t)cached_limit * sizeof(uint32_t);
+  const size_t maps = 2 * (size_t)((bitmap_limit + 31) / 32) * sizeof(uint32_t);
+  if (maps > region) region = maps;
+  hipLaunchKernelGGL(select_kernel, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab, offsets,
+                     idx, seg_base, cached_limit, bitmap_limit);
 }
 
 }  // namespace lkv

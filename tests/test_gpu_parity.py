@@ -100,25 +100,55 @@ def test_all_scores_equal_keeps_the_first_tokens(ctx):
     G.check_against_oracle(run, K, V, Q, sc, B, "ties")
 
 
-def test_select_on_crafted_scores(ctx):
-    # NaN, infinities, signed zeros, duplicates; the head is longer than the LDS key cache allows
-    rng = np.random.default_rng(0)
-    for T in (4000, 40000):
-        w = W.scaled(W.CONFIGS[0], L=1, H=3, Hq=3, T=T)
-        K, V, Q, sc, B = _inputs(w, [T])
-        u = rng.standard_normal((1, 3, T)).astype(np.float32)
-        u[0, 0, ::7] = np.nan; u[0, 0, 5] = -np.inf; u[0, 0, 11] = np.inf
-        u[0, 1] = np.round(u[0, 1] * 4) / 4                      # heavy ties
-        u[0, 1, ::2] *= 0.0                                      # +0.0 and -0.0
-        u[0, 2] = 1.0; u[0, 2, T // 2:] = 1.0 + 2 ** -23          # two values one ulp apart
-        budgets = np.array([[T - T // 7 + 3, T // 2, T // 2 + 10]], dtype=np.int32)
-        run = G.GpuRun(ctx, K, V, Q, sc, [budgets], w.Hq)
-        run.scores[0].copy_(torch.from_numpy(u))
-        run.select()
-        torch.cuda.synchronize()
-        idx_ref, off_ref = O.select_all(u, budgets)
-        assert np.array_equal(run.offsets.cpu().numpy(), off_ref)
-        assert np.array_equal(run.idx.cpu().numpy()[:off_ref[-1]], idx_ref)
+@pytest.mark.parametrize("T", [4000, 4001, 36864, 36865, 40000, 40003, 131072, 600001])
+def test_select_on_crafted_scores(ctx, T):
+    # NaN, infinities, signed zeros, duplicates, values one ulp apart; head lengths on both sides of
+    # every storage mode of the kernel (LDS key cache, LDS bitmaps, streaming) and off the 16-byte grid
+    rng = np.random.default_rng(T)
+    H = 4
+    k = torch.empty((1, H, T, 128), dtype=torch.bfloat16, device="cuda")   # contents unused by lkv_select
+    cache = lkv.Cache([k], [k], H)
+    u = rng.standard_normal((1, H, T)).astype(np.float32)
+    u[0, 0, ::7] = np.nan; u[0, 0, 5] = -np.inf; u[0, 0, 11] = np.inf
+    u[0, 1] = np.round(u[0, 1] * 4) / 4                      # heavy ties
+    u[0, 1, ::2] *= 0.0                                      # +0.0 and -0.0
+    u[0, 2] = 1.0; u[0, 2, T // 2:] = 1.0 + 2 ** -23          # two values one ulp apart
+    u[0, 3] = 0.5                                            # all equal
+    budgets = np.array([[T - T // 7 + 3, T // 2, T // 2 + 10, T // 3]], dtype=np.int32)
+    scores = [torch.from_numpy(u).cuda()]
+    total = int(budgets.sum())
+    idx = torch.full((total,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((H + 1,), -1, dtype=torch.int32, device="cuda")
+    lkv.lkv_select(ctx, cache, scores, budgets, idx, offsets)
+    torch.cuda.synchronize()
+    idx_ref, off_ref = O.select_all(u, budgets)
+    assert np.array_equal(offsets.cpu().numpy(), off_ref)
+    got = idx.cpu().numpy()
+    for h in range(H):
+        assert np.array_equal(got[off_ref[h]:off_ref[h + 1]], idx_ref[off_ref[h]:off_ref[h + 1]]), f"head {h}"
+
+
+def test_select_mixed_lengths_in_one_launch(ctx):
+    # sequences whose heads use different storage modes share one launch (and one LDS size)
+    rng = np.random.default_rng(5)
+    Ts = [3000, 50000, 36864, 70001]
+    H = 2
+    ks = [torch.empty((1, H, T, 128), dtype=torch.bfloat16, device="cuda") for T in Ts]
+    cache = lkv.Cache(ks, ks, H)
+    us = [rng.standard_normal((1, H, T)).astype(np.float32) for T in Ts]
+    budgets = np.array([[T // 5, T // 9] for T in Ts], dtype=np.int32)
+    total = int(budgets.sum())
+    idx = torch.full((total,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((len(Ts) * H + 1,), -1, dtype=torch.int32, device="cuda")
+    lkv.lkv_select(ctx, cache, [torch.from_numpy(u).cuda() for u in us], budgets.reshape(-1), idx, offsets)
+    torch.cuda.synchronize()
+    got = idx.cpu().numpy()
+    off = offsets.cpu().numpy()
+    assert np.array_equal(off, np.concatenate([[0], np.cumsum(budgets.reshape(-1))]))
+    for s, T in enumerate(Ts):
+        for h in range(H):
+            seg = s * H + h
+            assert np.array_equal(got[off[seg]:off[seg + 1]], O.select(us[s][0, h], int(budgets[s, h]))), (s, h)
 
 
 def test_results_are_reproducible(ctx):
