@@ -217,23 +217,32 @@ lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* 
   if (total > 0 && idx == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "idx is NULL");
   hipStream_t st = as_stream(stream);
 
-  // offsets: computed on the host (budgets are host data), uploaded through a pinned slot
-  const int slot = ctx->stage_next;
-  ctx->stage_next = (slot + 1) % kStageSlots;
-  if (ctx->stage_used[slot]) {
-    if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
+  // offsets: computed on the host (budgets are host data).  Few segments: they ride in the kernel
+  // arguments and the kernel publishes them.  Many: uploaded through a pinned slot of the ring.
+  const bool inline_offsets = n_seg < lkv::select_inline_capacity() && cache->n_seq <= lkv::kMaxSeqPerLaunch;
+  int32_t inline_buf[1024];
+  int32_t* host_off = inline_buf;
+  int slot = -1;
+  if (!inline_offsets) {
+    slot = ctx->stage_next;
+    ctx->stage_next = (slot + 1) % kStageSlots;
+    if (ctx->stage_used[slot]) {
+      if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
+    }
+    host_off = static_cast<int32_t*>(ctx->stage[slot]);
   }
-  int32_t* host_off = static_cast<int32_t*>(ctx->stage[slot]);
   int32_t run = 0;
   for (int64_t i = 0; i < n_seg; ++i) {
     host_off[i] = run;
     run += budgets[i];
   }
   host_off[n_seg] = run;
-  if (hipError_t e = hipMemcpyAsync(offsets, host_off, (size_t)(n_seg + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st))
-    return hip_fail(ctx, e, "offsets upload");
-  if (hipError_t e = hipEventRecord(ctx->stage_done[slot], st)) return hip_fail(ctx, e, "staging event");
-  ctx->stage_used[slot] = true;
+  if (!inline_offsets) {
+    if (hipError_t e = hipMemcpyAsync(offsets, host_off, (size_t)(n_seg + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st))
+      return hip_fail(ctx, e, "offsets upload");
+    if (hipError_t e = hipEventRecord(ctx->stage_done[slot], st)) return hip_fail(ctx, e, "staging event");
+    ctx->stage_used[slot] = true;
+  }
 
   for (int s0 = 0; s0 < cache->n_seq; s0 += lkv::kMaxSeqPerLaunch) {
     lkv::SeqTable tab;
@@ -246,7 +255,7 @@ lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* 
     }
     tab.first[n] = n * heads;
     tab.n = n;
-    lkv::launch_select(tab, offsets, idx, s0 * heads, st);
+    lkv::launch_select(tab, inline_offsets ? host_off : nullptr, (int)n_seg, offsets, idx, s0 * heads, st);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_select launch");
   }
   return LKV_OK;

@@ -19,8 +19,9 @@ int score_mlp_rows_per_block(int T);
 
 // select.hip
 hipError_t select_prepare();
-void launch_select(const SeqTable& tab, const int32_t* offsets, int32_t* idx, int seg_base,
-                   hipStream_t stream);
+int select_inline_capacity();
+void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
+                   int32_t* idx, int seg_base, hipStream_t stream);
 
 // compact.hip
 void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,

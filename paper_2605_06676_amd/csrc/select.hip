@@ -16,14 +16,18 @@
 //      this ordered scan; no atomic decides a position, so the result is unique
 //      and reproducible bit for bit.
 // Where the keys live depends on the head length T:
-//   * T <= 36864: the keys are cached in LDS (144 KB) by one batched read of the
-//     scores; every later pass reads LDS.
-//   * T <= 589824: too long for LDS.  The three histogram passes re-read the
-//     scores (they sit in L2 / the memory-side cache right after scoring) with
-//     batched 16-byte loads; a fourth pass classifies every token against `thr`
-//     into two LDS bitmaps (greater / equal), and the ordered emission runs on
-//     the bitmaps, 2048 tokens per wave step.
-//   * longer heads: as above but the emission re-reads the scores in order.
+//   * T <= 34304: the keys are cached in LDS by one batched read of the scores;
+//     the histogram passes and the classification read LDS.
+//   * T <= 589824: too long for LDS.  The three histogram passes and the
+//     classification pass re-read the scores (they sit in L2 / the memory-side
+//     cache right after scoring) with batched 16-byte loads.
+//   In both cases every token is classified against `thr` into two LDS bitmaps
+//   (greater / equal) and the ordered emission runs on the bitmaps, 1024 tokens
+//   per wave step: every lane expands its 16 bits into the wave's LDS staging
+//   buffer at the position given by a prefix count, then the wave copies the
+//   staged indices out with fully coalesced stores.
+//   * T <= 327680 is the limit for this; longer heads re-read the scores in
+//     order during emission, 64 tokens a step.
 // All global reads are issued eight at a time per thread before any is used:
 // the kernel is latency-bound, not bandwidth-bound, so what counts is how few
 // dependent round trips each pass makes.
@@ -34,16 +38,24 @@ namespace lkv {
 constexpr int kSelThreads = 1024;
 constexpr int kSelWaves = kSelThreads / 64;
 constexpr int kSelBins = 2048;
-constexpr int kSelMaxCachedKeys = 36864;                    // 144 KB of keys
-constexpr int kSelMaxBitmapWords = kSelMaxCachedKeys / 2;   // two bitmaps in the same 144 KB
-constexpr int kSelMaxBitmapT = kSelMaxBitmapWords * 32;     // 589824 tokens
+constexpr int kSelRegionBytes = 144 * 1024;                 // LDS after the histogram: key cache and/or bitmaps
+constexpr int kSelMaxCachedKeys = 34304;                    // 134 KB of keys + 8.4 KB of bitmaps fit the region
+constexpr int kSelStageWords = 1024;                        // staged indices per wave and step (one per token of the step)
+constexpr int kSelStageBytes = kSelWaves * kSelStageWords * 4;   // 64 KB
+constexpr int kSelMaxBitmapT = (kSelRegionBytes - kSelStageBytes) / 8 * 32;   // 327680 tokens: two bitmaps + staging
+static_assert(kSelMaxCachedKeys * 4 + 2 * ((kSelMaxCachedKeys + 31) / 32) * 4 <= kSelRegionBytes, "key cache + bitmaps");
 constexpr int kSelBatch = 8;                                // loads in flight per thread
+constexpr int kSelInlineOffsets = 640;                      // offsets that fit the kernel arguments next to the launch table
 
 __device__ __forceinline__ uint32_t order_key(float u) {
   uint32_t bits = __float_as_uint(u);
   if ((bits & 0x7fffffffu) > 0x7f800000u) bits = 0xff800000u;   // NaN ranks as -inf
   return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
 }
+
+struct InlineOffsets {
+  int32_t v[kSelInlineOffsets];
+};
 
 struct SelShared {
   uint32_t hist[kSelBins];
@@ -199,13 +211,25 @@ __device__ __forceinline__ uint32_t lowest_set_bits(uint32_t x, uint32_t k) {
   return x & ((1u << hi) - 1u);
 }
 
+__device__ __forceinline__ void wave_lds_sync() {
+  // orders this wave's LDS writes and reads of its private staging; no block barrier needed
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Ordered emission from the two LDS bitmaps (bit i of gt: key_i > thr; of eq: key_i == thr).
+// Each wave owns a contiguous range of bitmap words and handles 32 words (1024 tokens) per step,
+// one 16-bit half word per lane.  Loops whose trip count could differ between lanes are avoided
+// (the expansion loop runs a fixed 16 times), and every cross-lane exchange of a step comes
+// before the staging traffic.
 __device__ __forceinline__ void emit_from_bitmaps(SelShared& sh, int T, uint32_t need, int32_t* __restrict__ out,
-                                                  const uint32_t* gt_map, const uint32_t* eq_map) {
+                                                  const uint32_t* gt_map, const uint32_t* eq_map, uint32_t* stage_all) {
   const int lane = threadIdx.x & 63;
   const int wave = threadIdx.x >> 6;
+  uint32_t* stage = stage_all + wave * kSelStageWords;
   const int n_words = (T + 31) >> 5;
-  const int per = ((n_words + kSelWaves - 1) / kSelWaves + 63) & ~63;   // words per wave, a multiple of 64
+  const int per = ((n_words + kSelWaves - 1) / kSelWaves + 31) & ~31;   // words per wave, a multiple of 32
   const int lo = wave * per;
   const int hi = min(n_words, lo + per);
   uint32_t n_gt = 0, n_eq = 0;
@@ -218,35 +242,50 @@ __device__ __forceinline__ void emit_from_bitmaps(SelShared& sh, int T, uint32_t
   for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
   uint32_t eq_seen = eq_before;
   uint32_t pos = gt_before + min(eq_before, need);
-  for (int base = lo; base < hi; base += 64) {
-    const int w = base + lane;
+  const int half = lane & 1;
+  for (int base = lo; base < hi; base += 32) {
+    const int w = base + (lane >> 1);
     const bool in = w < hi;
-    const uint32_t gtw = in ? gt_map[w] : 0u;
-    const uint32_t eqw = in ? eq_map[w] : 0u;
-    // copies of thr before this lane's word, and how many of this word's copies are still kept
-    const uint32_t eq_cnt = __popc(eqw);
+    const uint32_t gth = in ? (gt_map[w] >> (16 * half)) & 0xffffu : 0u;
+    const uint32_t eqh = in ? (eq_map[w] >> (16 * half)) & 0xffffu : 0u;
+    // copies of thr before this lane's half word, and how many of its own copies are still kept
+    const uint32_t eq_cnt = __popc(eqh);
     const uint32_t eq_incl = wave_inclusive_scan(eq_cnt, lane);
     const uint32_t eq_rank = eq_seen + eq_incl - eq_cnt;
     const uint32_t take = eq_rank < need ? min(eq_cnt, need - eq_rank) : 0u;
-    const uint32_t keptw = gtw | lowest_set_bits(eqw, take);
-    const uint32_t cnt = __popc(keptw);
+    uint32_t bits = gth | lowest_set_bits(eqh, take);
+    const uint32_t cnt = __popc(bits);
     const uint32_t incl = wave_inclusive_scan(cnt, lane);
-    uint32_t p = pos + incl - cnt;
-    // every cross-lane exchange of this step happens before the lanes diverge in the write loop
-    pos += __shfl(incl, 63, 64);
+    const uint32_t total = (uint32_t)__builtin_amdgcn_readfirstlane((int)__shfl(incl, 63, 64));
     eq_seen += __shfl(eq_incl, 63, 64);
-    uint32_t bits = keptw;
-    while (bits) {
-      out[p++] = (w << 5) + __builtin_ctz(bits);
-      bits &= bits - 1;
+    uint32_t p = incl - cnt;
+    const uint32_t tok0 = ((uint32_t)w << 5) + 16u * half;
+#pragma unroll
+    for (int it = 0; it < 16; ++it) {
+      if (bits) {
+        stage[p++] = tok0 + __builtin_ctz(bits);
+        bits &= bits - 1;
+      }
     }
+    wave_lds_sync();
+    for (uint32_t j0 = 0; j0 < total; j0 += 64) {   // uniform trip count
+      const uint32_t j = j0 + lane;
+      if (j < total) out[pos + j] = stage[j];
+    }
+    pos += total;
+    wave_lds_sync();   // the staging buffer is rewritten by the next step
   }
 }
 
+// Up to kSelInlineOffsets segment offsets travel in the kernel arguments instead of through a
+// host-to-device copy (which costs an extra dependent transfer before the kernel can start);
+// the blocks then also publish them to the device array that the later calls read.
+template <bool kInline>
 __global__ void __launch_bounds__(kSelThreads)
-select_kernel(SeqTable tab, const int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
+select_kernel(SeqTable tab, InlineOffsets inl, int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
               int seg_base, int cached_limit /* heads of at most this many tokens use the LDS key cache */,
-              int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */) {
+              int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */,
+              int cached_stage_off, int bitmap_stage_off /* word offsets of the staging buffer in the region */) {
   extern __shared__ __align__(16) unsigned char smem[];
   SelShared& sh = *reinterpret_cast<SelShared*>(smem);
   uint32_t* region = reinterpret_cast<uint32_t*>(smem + sizeof(SelShared));
@@ -258,8 +297,12 @@ select_kernel(SeqTable tab, const int32_t* __restrict__ offsets, int32_t* __rest
   const int T = tab.T[seq];
   const float* u = tab.scores[seq] + (size_t)lh * (size_t)T;
   const int seg = seg_base + local_seg;
-  const int off = offsets[seg];
-  const int budget = offsets[seg + 1] - off;
+  const int off = kInline ? inl.v[seg] : offsets[seg];
+  const int budget = (kInline ? inl.v[seg + 1] : offsets[seg + 1]) - off;
+  if (kInline && tid == 0) {
+    offsets[seg] = off;
+    if (local_seg == (int)gridDim.x - 1) offsets[seg + 1] = off + budget;   // the total, by the launch's last block
+  }
   int32_t* out = idx + off;
   if (budget <= 0) return;
   if (budget >= T) {   // everything is kept
@@ -273,11 +316,30 @@ select_kernel(SeqTable tab, const int32_t* __restrict__ offsets, int32_t* __rest
 
   if (T <= cached_limit) {
     uint32_t* keys = region;
+    const int n_words = (T + 31) >> 5;
+    uint32_t* gt_map = region + cached_limit;   // after the key cache of the launch's longest cached head
+    uint32_t* eq_map = gt_map + n_words;
     for_each_global_key(u, T, [&](uint32_t key, int i) { keys[i] = key; });
     auto count = [&](auto fn) { for (int i = tid; i < T; i += kSelThreads) fn(keys[i]); };
 #pragma unroll 1
     for (int level = 0; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
-    emit_from_keys(sh, T, prefix, need, out, [&](int i) { return keys[i]; });
+    const uint32_t thr = prefix;
+    // classification: a wave covers 64 consecutive tokens, so a ballot is two finished bitmap words
+    const int lane = tid & 63;
+    for (int base = (tid >> 6) * 64; base < T; base += kSelThreads) {
+      const int i = base + lane;
+      const uint32_t key = i < T ? keys[i] : 0u;
+      const unsigned long long m_gt = __ballot(i < T && key > thr);
+      const unsigned long long m_eq = __ballot(i < T && key == thr);
+      if (lane == 0) {
+        const int w = base >> 5;
+        gt_map[w] = (uint32_t)m_gt;
+        eq_map[w] = (uint32_t)m_eq;
+        if (w + 1 < n_words) { gt_map[w + 1] = (uint32_t)(m_gt >> 32); eq_map[w + 1] = (uint32_t)(m_eq >> 32); }
+      }
+    }
+    __syncthreads();
+    emit_from_bitmaps(sh, T, need, out, gt_map, eq_map, region + cached_stage_off);   // the key cache is dead by now
     return;
   }
 
@@ -297,20 +359,28 @@ select_kernel(SeqTable tab, const int32_t* __restrict__ offsets, int32_t* __rest
       else if (key == thr) atomicOr(&eq_map[i >> 5], 1u << (i & 31));
     });
     __syncthreads();
-    emit_from_bitmaps(sh, T, need, out, gt_map, eq_map);
+    emit_from_bitmaps(sh, T, need, out, gt_map, eq_map, region + bitmap_stage_off);
   } else {
     emit_from_keys(sh, T, thr, need, out, [&](int i) { return order_key(u[i]); });
   }
 }
 
 hipError_t select_prepare() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel),
-                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                             (int)(sizeof(SelShared) + (size_t)kSelMaxCachedKeys * 4));
+  const int lds = (int)(sizeof(SelShared) + (size_t)kSelRegionBytes);
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<true>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
 }
 
-void launch_select(const SeqTable& tab, const int32_t* offsets, int32_t* idx, int seg_base,
-                   hipStream_t stream) {
+int select_inline_capacity() { return kSelInlineOffsets; }
+
+// `host_offsets` non-null: all n_total_segments + 1 offsets are passed in the kernel arguments
+// (n_total_segments < kSelInlineOffsets) and the kernel writes the device array; null: the
+// device array has already been filled.
+void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
+                   int32_t* idx, int seg_base, hipStream_t stream) {
   const int segs = tab.first[tab.n];
   if (segs <= 0) return;
   // the LDS region is sized for the longest sequence of this launch that can use it
@@ -320,11 +390,27 @@ void launch_select(const SeqTable& tab, const int32_t* offsets, int32_t* idx, in
     if (T <= kSelMaxCachedKeys) { if (T > cached_limit) cached_limit = T; }
     else if (T <= kSelMaxBitmapT) { if (T > bitmap_limit) bitmap_limit = T; }
   }
-  size_t region = (size_t)cached_limit * sizeof(uint32_t);
-  const size_t maps = 2 * (size_t)((bitmap_limit + 31) / 32) * sizeof(uint32_t);
-  if (maps > region) region = maps;
-  hipLaunchKernelGGL(select_kernel, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab, offsets,
-                     idx, seg_base, cached_limit, bitmap_limit);
+  // Region layout.  Cached heads: key cache of the longest one, then two bitmaps; the staging
+  // buffer of the emission overlays the (by then dead) key cache when that is large enough,
+  // else it follows the bitmaps.  Longer heads: two bitmaps, then the staging buffer.
+  const size_t cached_words = cached_limit > 0 ? (size_t)cached_limit + 2 * (size_t)((cached_limit + 31) / 32) : 0;
+  const bool overlay = (size_t)cached_limit * 4 >= (size_t)kSelStageBytes;
+  const size_t cached_stage_off = overlay ? 0 : cached_words;
+  size_t region = cached_limit > 0 ? (overlay ? cached_words * 4 : cached_words * 4 + kSelStageBytes) : 0;
+  const size_t bitmap_stage_off = 2 * (size_t)((bitmap_limit + 31) / 32);
+  if (bitmap_limit > 0 && bitmap_stage_off * 4 + kSelStageBytes > region) region = bitmap_stage_off * 4 + kSelStageBytes;
+  InlineOffsets inl;
+  if (host_offsets != nullptr) {
+    for (int i = 0; i <= n_total_segments; ++i) inl.v[i] = host_offsets[i];
+    hipLaunchKernelGGL(select_kernel<true>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
+                       inl, offsets, idx, seg_base, cached_limit, bitmap_limit, (int)cached_stage_off,
+                       (int)bitmap_stage_off);
+  } else {
+    inl.v[0] = 0;
+    hipLaunchKernelGGL(select_kernel<false>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
+                       inl, offsets, idx, seg_base, cached_limit, bitmap_limit, (int)cached_stage_off,
+                       (int)bitmap_stage_off);
+  }
 }
 
 }  // namespace lkv

@@ -100,7 +100,7 @@ def test_all_scores_equal_keeps_the_first_tokens(ctx):
     G.check_against_oracle(run, K, V, Q, sc, B, "ties")
 
 
-@pytest.mark.parametrize("T", [4000, 4001, 36864, 36865, 40000, 40003, 131072, 600001])
+@pytest.mark.parametrize("T", [12, 63, 4000, 4001, 16383, 16384, 32768, 34304, 34305, 40000, 40003, 131072, 327680, 327681])
 def test_select_on_crafted_scores(ctx, T):
     # NaN, infinities, signed zeros, duplicates, values one ulp apart; head lengths on both sides of
     # every storage mode of the kernel (LDS key cache, LDS bitmaps, streaming) and off the 16-byte grid
@@ -114,15 +114,18 @@ def test_select_on_crafted_scores(ctx, T):
     u[0, 1, ::2] *= 0.0                                      # +0.0 and -0.0
     u[0, 2] = 1.0; u[0, 2, T // 2:] = 1.0 + 2 ** -23          # two values one ulp apart
     u[0, 3] = 0.5                                            # all equal
-    budgets = np.array([[T - T // 7 + 3, T // 2, T // 2 + 10, T // 3]], dtype=np.int32)
+    budgets = np.minimum(np.array([[T - T // 7 + 3, T // 2, T // 2 + 10, T // 3]], dtype=np.int32), T)
     scores = [torch.from_numpy(u).cuda()]
     total = int(budgets.sum())
-    idx = torch.full((total,), -1, dtype=torch.int32, device="cuda")
+    # the index buffer sits inside a larger one so that a kernel writing past its end is caught, not harmful
+    buf = torch.full((total + 4 * T + 64,), -1, dtype=torch.int32, device="cuda")
+    idx = buf[:total]
     offsets = torch.full((H + 1,), -1, dtype=torch.int32, device="cuda")
     lkv.lkv_select(ctx, cache, scores, budgets, idx, offsets)
     torch.cuda.synchronize()
     idx_ref, off_ref = O.select_all(u, budgets)
     assert np.array_equal(offsets.cpu().numpy(), off_ref)
+    assert bool((buf[total:] == -1).all()), "writes past the end of idx"
     got = idx.cpu().numpy()
     for h in range(H):
         assert np.array_equal(got[off_ref[h]:off_ref[h + 1]], idx_ref[off_ref[h]:off_ref[h + 1]]), f"head {h}"
@@ -131,7 +134,7 @@ def test_select_on_crafted_scores(ctx, T):
 def test_select_mixed_lengths_in_one_launch(ctx):
     # sequences whose heads use different storage modes share one launch (and one LDS size)
     rng = np.random.default_rng(5)
-    Ts = [3000, 50000, 36864, 70001]
+    Ts = [3000, 50000, 34304, 70001]
     H = 2
     ks = [torch.empty((1, H, T, 128), dtype=torch.bfloat16, device="cuda") for T in Ts]
     cache = lkv.Cache(ks, ks, H)
