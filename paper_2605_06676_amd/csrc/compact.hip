@@ -47,15 +47,15 @@ compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __r
       const int T = tab.T[sl];
       const int tok = min(max(idx[p], 0), T - 1);
       const size_t src = ((size_t)lh * (size_t)T + (size_t)tok) * kChunksPerRow + c;
-      kk[u] = reinterpret_cast<const uint4*>(tab.k[sl])[src];
-      vv[u] = reinterpret_cast<const uint4*>(tab.v[sl])[src];
+      kk[u] = load_stream16(reinterpret_cast<const uint4*>(tab.k[sl]) + src);
+      vv[u] = load_stream16(reinterpret_cast<const uint4*>(tab.v[sl]) + src);
     }
 #pragma unroll
     for (int u = 0; u < kCompactUnroll; ++u) {
       const int64_t p = p0 + (it + u) * 16 + rslot;
       if (live[u]) {
-        kp[p * kChunksPerRow + c] = kk[u];
-        vp[p * kChunksPerRow + c] = vv[u];
+        store_stream16(kp + p * kChunksPerRow + c, kk[u]);
+        store_stream16(vp + p * kChunksPerRow + c, vv[u]);
       }
     }
   }

@@ -15,7 +15,7 @@ namespace lkv {
 constexpr int kScoreBlockThreads = 256;
 constexpr int kScoreRowsPerWave = 64;
 constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * (kScoreBlockThreads / 64);   // 256
-constexpr int kScoreUnroll = 8;   // row groups whose loads are in flight together
+constexpr int kScoreUnroll = 4;   // row groups whose loads are in flight together (8 loads per lane)
 
 __global__ void __launch_bounds__(kScoreBlockThreads)
 score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
