@@ -25,6 +25,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the score kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
+# by what the counter reads for a plain 1 GiB copy (profiles/hbm_traffic_counters__cfg1_L32_H8_T32768_linear.md).
+# Hardware counters cannot be read from inside this script, so the figure is carried per workload; None = not measured.
+MEASURED_SCORE_TRAFFIC_BYTES = {1: 4328786289}
 
 
 def parse():
@@ -153,7 +157,8 @@ def main():
                    "frac_of_peak": decode_bytes / (t_decode * 1e6) / HBM_PEAK_GBS},
         "roofline": {"kernel": "score_linear_kernel" if w.scorer == "linear" else "score_mlp_kernel",
                      "bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS,
+                     "traffic": MEASURED_SCORE_TRAFFIC_BYTES.get(args.config),
                      "launches_per_step": 1 if w.n_seq <= 32 else math.ceil(w.n_seq / 32),
                      "bytes_per_launch": score_bytes},
     }
