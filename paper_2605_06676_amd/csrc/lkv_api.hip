@@ -136,8 +136,6 @@ lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* sco
     if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
     if (scorer->hidden < 16 || scorer->hidden > 128 || scorer->hidden % 16 != 0)
       return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must be a multiple of 16 in [16, 128]", scorer->hidden);
-    if (scorer->hidden > 64)
-      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d: widths above 64 are not built yet", scorer->hidden);
   }
   const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
   for (int s = 0; s < cache->n_seq; ++s) {

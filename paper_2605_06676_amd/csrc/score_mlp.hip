@@ -1,5 +1,5 @@
 // LKV-T token scoring with the two-layer MLP of Sec. 3.4 / Table 5 of the
-// paper: u = w2 . act(W1 [k ; v] + b1) (+ b2), hidden width up to 64 here.
+// paper: u = w2 . act(W1 [k ; v] + b1) (+ b2), hidden width 16..128.
 //
 // The hidden layer is the one dense contraction of the eviction path
 // ([tokens x 256] x [256 x hidden], about 64 flop per byte streamed for
@@ -66,8 +66,10 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& p) {
   return __builtin_bit_cast(bf16x8_t, p);
 }
 
+// Hidden widths up to 64 keep W1 in 128 registers and run two waves per SIMD; widths up to 128
+// (the paper's 256 -> 128 -> 1) need 256 registers for W1 alone and run one wave per SIMD.
 template <int MT, int kAct>
-__global__ void __launch_bounds__(kMlpThreads, 2)
+__global__ void __launch_bounds__(kMlpThreads, (MT <= 4 ? 2 : 1))
 score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
                  const float* __restrict__ w2, const float* __restrict__ b2, int heads_per_scorer_row,
                  int rows_per_block) {
@@ -227,6 +229,10 @@ void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, 
     case 2: launch_mt<2>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
     case 3: launch_mt<3>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
     case 4: launch_mt<4>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 5: launch_mt<5>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 6: launch_mt<6>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 7: launch_mt<7>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 8: launch_mt<8>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
     default: break;
   }
 }

@@ -64,6 +64,7 @@ class Workload:
     outliers: Optional[str] = None      # None, 'x10', 'student_t'
     shared_budgets: bool = False        # one budget table for all sequences
     per_head: bool = False
+    out_bias: bool = True               # False: the paper's arrangement (Table 5: no output bias)
     d: int = D_HEAD
 
     @property
@@ -80,6 +81,11 @@ CONFIGS = (
              0.15, 0.5, 32),
     Workload(4, "cfg4-8seq-L28-H4-g7-T65536-mlp64gelu", 8, 28, 4, 28, 65536, "mlp", 64, "gelu", 0.05, 0.1, 32,
              outliers="student_t", shared_budgets=True),
+    # not one of the five benchmark configurations: the scorer exactly as the paper builds it
+    # (Sec. 3.4 / Table 5: one 256 -> 128 -> 1 SiLU network per (layer, head), no output bias)
+    # on the Llama-3.1-8B cache shape of its App. C.1
+    Workload(5, "paper-L32-H8-T32768-mlp128silu-per-head", 1, 32, 8, 32, 32768, "mlp", 128, "silu", 0.15, 0.5, 64,
+             per_head=True, out_bias=False),
 )
 
 
@@ -186,7 +192,7 @@ def draw_scorer(w: Workload, seed: int = 0) -> dict:
     w1 = rng.normal(0.0, std, size=(w.L, Hs, w.hidden, 2 * w.d)).astype(np.float32)
     b1 = rng.normal(0.0, std, size=(w.L, Hs, w.hidden)).astype(np.float32)
     w2 = rng.normal(0.0, std, size=(w.L, Hs, w.hidden)).astype(np.float32)
-    b2 = rng.normal(0.0, std, size=(w.L, Hs)).astype(np.float32)
+    b2 = rng.normal(0.0, std, size=(w.L, Hs)).astype(np.float32) if w.out_bias else None
     return {"kind": "mlp", "act": w.act, "hidden": w.hidden, "per_head": w.per_head,
             "w1": f32_to_bf16_bits(w1), "b1": b1, "w2": w2, "b2": b2}
 

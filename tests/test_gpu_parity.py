@@ -66,7 +66,9 @@ def test_gqa_group_sizes(ctx, g):
     _run_and_check(ctx, w, [1500], seed=g, what=f"g={g}")
 
 
-@pytest.mark.parametrize("hidden,act,per_head", [(64, "gelu", False), (32, "silu", True), (16, "gelu", True), (48, "silu", False)])
+@pytest.mark.parametrize("hidden,act,per_head", [(64, "gelu", False), (32, "silu", True), (16, "gelu", True), (48, "silu", False),
+                                                 (128, "silu", True), (80, "gelu", False), (96, "silu", False), (112, "gelu", True),
+                                                 (128, "gelu", False)])
 def test_mlp_scorer(ctx, hidden, act, per_head):
     w = W.scaled(W.CONFIGS[2], L=2, H=2, Hq=8, T=3000, b_min=16, hidden=hidden, act=act, per_head=per_head)
     ws, wd = _run_and_check(ctx, w, [3000], what=f"mlp{hidden}{act}")
@@ -80,6 +82,16 @@ def test_mlp_without_output_bias_and_heavy_tails(ctx):
     run = G.GpuRun(ctx, K, V, Q, sc, B, w.Hq)
     run.run_all()
     G.check_against_oracle(run, K, V, Q, sc, B, "cfg4-like")
+
+
+def test_paper_scorer_shape(ctx):
+    # Sec. 3.4 / Table 5: one 256 -> 128 -> 1 SiLU network per (layer, head), hidden bias, no output bias
+    w = W.scaled(W.CONFIGS[5], L=2, H=3, Hq=12, T=2100, b_min=16)
+    K, V, Q, sc, B = _inputs(w, [2100])
+    assert sc["b2"] is None and sc["w1"].shape == (2, 3, 128, 256)
+    run = G.GpuRun(ctx, K, V, Q, sc, B, w.Hq)
+    run.run_all()
+    G.check_against_oracle(run, K, V, Q, sc, B, "paper scorer")
 
 
 def test_per_head_linear_scorer(ctx):

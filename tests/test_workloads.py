@@ -45,6 +45,8 @@ def test_config_table_shapes():
     Ts = W.seq_lengths(w3)
     assert Ts.size == 16 and Ts.min() >= 4096 and Ts.max() <= 16384
     assert W.CONFIGS[4].g == 7 and W.CONFIGS[1].g == 4
+    paper = W.draw_scorer(W.scaled(W.CONFIGS[5], L=2))
+    assert paper["w1"].shape == (2, 8, 128, 256) and paper["b2"] is None and paper["act"] == "silu"
     sc = W.draw_scorer(W.CONFIGS[2])
     assert sc["w1"].shape == (32, 1, 64, 256) and sc["w1"].dtype == np.uint16
     assert abs(W.bf16_bits_to_f32(sc["w1"]).std() - 0.02) < 1e-3
