@@ -99,6 +99,39 @@ def test_per_head_linear_scorer(ctx):
     _run_and_check(ctx, w, [2048], what="per-head linear")
 
 
+@pytest.mark.parametrize("seed", range(24))
+def test_random_shapes(ctx, seed):
+    # shapes, scorer kinds and budgets drawn at random: several sequences, empty and full heads,
+    # lengths off every tile size, GQA groups up to 16
+    rng = np.random.default_rng(1000 + seed)
+    L, H = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+    g = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 12, 16]))
+    n_seq = int(rng.integers(1, 4))
+    Ts = [int(rng.integers(1, 2600)) for _ in range(n_seq)]
+    kind = str(rng.choice(["linear", "mlp"]))
+    w = W.scaled(W.CONFIGS[0], L=L, H=H, Hq=H * g, n_seq=n_seq, scorer=kind,
+                 hidden=int(rng.choice([16, 32, 64, 80, 128])) if kind == "mlp" else 0,
+                 act=str(rng.choice(["silu", "gelu"])), per_head=bool(rng.integers(0, 2)),
+                 out_bias=bool(rng.integers(0, 2)))
+    budgets = []
+    for T in Ts:
+        b = rng.integers(0, T + 1, size=(L, H))
+        b[rng.random((L, H)) < 0.15] = 0
+        b[rng.random((L, H)) < 0.1] = T
+        budgets.append(b.astype(np.int32))
+    _run_and_check(ctx, w, Ts, seed=seed, budgets=budgets, what=f"random {seed}")
+
+
+def test_group_size_limit(ctx):
+    w = W.scaled(W.CONFIGS[0], L=1, H=1, Hq=17, T=64, b_min=4)
+    K, V, Q, sc, B = _inputs(w, [64])
+    run = G.GpuRun(ctx, K, V, Q, sc, B, 16)
+    with pytest.raises(lkv.LkvError) as e:
+        lkv.lkv_decode_attn(ctx, 1, 1, 1, 17, 128, run.q, run.kp, run.vp, run.offsets, run.total, G.SCALE,
+                            run.out, run.lse, run.ws)
+    assert e.value.status == 2
+
+
 def test_all_scores_equal_keeps_the_first_tokens(ctx):
     w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=8, T=5000)
     K, V, Q, sc, B = _inputs(w, [5000])
