@@ -155,7 +155,8 @@ def main():
                   "context_tokens_per_s": sum(Ts) / (t_evict * 1e-3)},
         "decode": {"bytes": decode_bytes, "GBps": decode_bytes / (t_decode * 1e6),
                    "frac_of_peak": decode_bytes / (t_decode * 1e6) / HBM_PEAK_GBS},
-        "roofline": {"kernel": "score_linear_kernel" if w.scorer == "linear" else "score_mlp_kernel",
+        "roofline": {"kernel": "score_linear_kernel" if w.scorer == "linear"
+                     else ("score_mlp_kernel" if w.hidden <= 64 else "score_mlp_wide_kernel"),
                      "bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS,
                      "traffic": MEASURED_SCORE_TRAFFIC_BYTES.get(args.config),

@@ -66,10 +66,9 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& p) {
   return __builtin_bit_cast(bf16x8_t, p);
 }
 
-// Hidden widths up to 64 keep W1 in 128 registers and run two waves per SIMD; widths up to 128
-// (the paper's 256 -> 128 -> 1) need 256 registers for W1 alone and run one wave per SIMD.
+// Hidden widths up to 64: one wave multiplies a tile by the whole W1 (128 registers), two waves per SIMD.
 template <int MT, int kAct>
-__global__ void __launch_bounds__(kMlpThreads, (MT <= 4 ? 2 : 1))
+__global__ void __launch_bounds__(kMlpThreads, 2)
 score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
                  const float* __restrict__ w2, const float* __restrict__ b2, int heads_per_scorer_row,
                  int rows_per_block) {
@@ -193,6 +192,164 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
   }
 }
 
+// Hidden widths 80..128 (the paper's network is 256 -> 128 -> 1): W1 no longer fits the registers of
+// one wave at two waves per SIMD, so the hidden units are split over a pair of waves, and a block is
+// one pair.  Wave `half` keeps the fragments of M tiles [half * MTW, half * MTW + MTW) and both
+// multiply the same staged 16-token tile; the two partial sums of a token meet in LDS.  Staging is
+// split evenly: wave 0 brings the key halves of the rows, wave 1 the value halves, each two tiles
+// ahead in registers.  The tile and the partial-sum slots are double buffered and one barrier per
+// tile orders everything: a wave that stages tile i + 1 has passed barrier i, so its partner has
+// finished reading tile i - 1.  Inside a wave the matrix products of tile i are issued ahead of the
+// activation arithmetic of tile i - 1, so the matrix and vector pipes overlap.
+constexpr int kWideThreads = 128;
+
+template <int MTW, int kAct>
+__global__ void __launch_bounds__(kWideThreads, 2)
+score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
+                      const float* __restrict__ w2, const float* __restrict__ b2, int hidden,
+                      int heads_per_scorer_row, int rows_per_block) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  constexpr int HW = MTW * 16;                      // hidden units per wave (zero padded past `hidden`)
+  const int MT = hidden / 16;
+
+  const int seq = seq_of_unit(tab, blockIdx.x);
+  const int local = blockIdx.x - tab.first[seq];
+  const int T = tab.T[seq];
+  const int tiles = (T + rows_per_block - 1) / rows_per_block;
+  const int lh = local / tiles;
+  const int tile = local - lh * tiles;
+  const int scorer = lh / heads_per_scorer_row;
+
+  const int lane = threadIdx.x & 63;
+  const int half = threadIdx.x >> 6;
+  const int r = lane >> 4;
+  const int c = lane & 15;
+  // LDS: two staged tiles, then [buffer][16] partial sums, then b1 / w2 (zero padded)
+  unsigned char* x_lds = smem;
+  float* sum_lds = reinterpret_cast<float*>(smem + 2 * kMlpWaveLds);
+  float* par_lds = sum_lds + 32;   // b1[2 HW] then w2[2 HW]
+
+  bf16x8_t wfrag[MTW][kMlpKSteps];
+  {
+    const uint4* wbase = reinterpret_cast<const uint4*>(w1 + (size_t)scorer * hidden * 256);
+#pragma unroll
+    for (int mw = 0; mw < MTW; ++mw) {
+      const int mt = half * MTW + mw;
+#pragma unroll
+      for (int ks = 0; ks < kMlpKSteps; ++ks) {
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (mt < MT) v = wbase[(size_t)(mt * 16 + c) * 32 + ks * 4 + r];
+        wfrag[mw][ks] = as_bf16x8(v);
+      }
+    }
+  }
+  for (int i = threadIdx.x; i < 4 * HW; i += kWideThreads) {
+    const int j = i < 2 * HW ? i : i - 2 * HW;
+    const float* src = i < 2 * HW ? b1 : w2;
+    par_lds[i] = j < hidden ? src[(size_t)scorer * hidden + j] : 0.f;
+  }
+  const float bias2 = b2 != nullptr ? b2[scorer] : 0.f;
+
+  const size_t head_row0 = (size_t)lh * (size_t)T;
+  // this wave's half of the rows: keys for wave 0, values for wave 1
+  const uint4* Xh = reinterpret_cast<const uint4*>(half == 0 ? tab.k[seq] : tab.v[seq]) + head_row0 * kChunksPerRow;
+  float* out = tab.scores[seq] + head_row0;
+
+  // tile i covers rows block_row0 + 16 i; rows past the end are clamped on load and not stored
+  const int block_row0 = tile * rows_per_block;
+  const int block_rows = min(T - block_row0, rows_per_block);
+  const int n_tiles = (block_rows + 15) >> 4;
+
+  uint4 xa[4], xb[4];   // this wave's halves of an even and of an odd tile on their way to LDS
+  auto load_half = [&](uint4 (&xx)[4], int i) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int row = block_row0 + 16 * i + 4 * j + r;
+      row = row < T ? row : T - 1;
+      xx[j] = load_stream16(Xh + (size_t)row * kChunksPerRow + c);
+    }
+  };
+  auto stage_half = [&](const uint4 (&xx)[4], int buf) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      *reinterpret_cast<uint4*>(x_lds + buf * kMlpWaveLds + (4 * j + r) * kMlpRowStride + half * 256 + c * 16) = xx[j];
+  };
+  auto issue_products = [&](f32x4_t (&acc)[MTW], int buf) {
+#pragma unroll
+    for (int mw = 0; mw < MTW; ++mw)
+      acc[mw] = *reinterpret_cast<const f32x4_t*>(par_lds + half * HW + mw * 16 + 4 * r);   // bias
+    const unsigned char* xt = x_lds + buf * kMlpWaveLds;
+#pragma unroll
+    for (int ks = 0; ks < kMlpKSteps; ++ks) {
+      const uint4 x = *reinterpret_cast<const uint4*>(xt + c * kMlpRowStride + ks * 64 + r * 16);
+      const bf16x8_t xv = as_bf16x8(x);
+#pragma unroll
+      for (int mw = 0; mw < MTW; ++mw)
+        acc[mw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfrag[mw][ks], xv, acc[mw], 0, 0, 0);
+    }
+  };
+  float held_prev = 0.f, held = 0.f;   // wave 0: its own partial sums of the two latest finished tiles
+  auto finish_tile = [&](const f32x4_t (&acc)[MTW], int t) {   // activation and output layer of tile t
+    float part = 0.f;
+#pragma unroll
+    for (int mw = 0; mw < MTW; ++mw) {
+      const f32x4_t wo = *reinterpret_cast<const f32x4_t*>(par_lds + 2 * HW + half * HW + mw * 16 + 4 * r);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) part = fmaf(wo[e], activation<kAct>(acc[mw][e]), part);
+    }
+    part += __shfl_xor(part, 16, 64);
+    part += __shfl_xor(part, 32, 64);
+    if (half == 1) {
+      if (r == 0) sum_lds[(t & 1) * 16 + c] = part;
+    } else {
+      held_prev = held;
+      held = part;
+    }
+  };
+  auto store_tile = [&](int t, float mine) {   // wave 0: add the partner's partial sum of tile t and store
+    const int row = block_row0 + 16 * t + c;
+    if (half == 0 && r == 0 && row < T) out[row] = mine + sum_lds[(t & 1) * 16 + c] + bias2;
+  };
+
+  // Barrier i makes tile i visible; it also means both waves have finished reading tile i - 1 and
+  // have written the partial sums of tile i - 2.  One step: products of tile i, epilogue of tile
+  // i - 1, store of tile i - 2, staging of tile i + 1 (fetching tile i + 3 behind it), barrier i + 1.
+  f32x4_t acc_a[MTW], acc_b[MTW];
+  auto step = [&](f32x4_t (&acc_new)[MTW], const f32x4_t (&acc_old)[MTW], uint4 (&x_next)[4], int i) {
+    issue_products(acc_new, i & 1);
+    finish_tile(acc_old, i - 1);
+    if (i >= 2) store_tile(i - 2, held_prev);
+    if (i + 1 < n_tiles) {
+      stage_half(x_next, (i + 1) & 1);
+      if (i + 3 < n_tiles) load_half(x_next, i + 3);
+    }
+    __syncthreads();
+  };
+  load_half(xa, 0);
+  if (1 < n_tiles) load_half(xb, 1);
+  stage_half(xa, 0);
+  if (2 < n_tiles) load_half(xa, 2);
+  __syncthreads();   // tile 0 and b1 / w2 are in LDS
+  issue_products(acc_a, 0);
+  if (1 < n_tiles) {
+    stage_half(xb, 1);
+    if (3 < n_tiles) load_half(xb, 3);
+  }
+  __syncthreads();
+#pragma unroll 1
+  for (int i = 1; i < n_tiles; i += 2) {
+    step(acc_b, acc_a, xa, i);                               // stages the even tile i + 1
+    if (i + 1 < n_tiles) step(acc_a, acc_b, xb, i + 1);      // uniform condition around the barrier
+  }
+  // drain: the last tile's epilogue, one more barrier for its partial sums, then the last two stores
+  const int last = n_tiles - 1;
+  if (last & 1) finish_tile(acc_b, last);
+  else finish_tile(acc_a, last);
+  __syncthreads();
+  if (last >= 1) store_tile(last - 1, held_prev);
+  store_tile(last, held);
+}
+
 int score_mlp_rows_per_block(int T) {
   // large tiles amortise the 32 KB of W1 each wave loads; small heads keep more blocks
 #ifdef LKV_MLP_ROWS
@@ -219,6 +376,20 @@ static void launch_mt(const SeqTable& tab, const uint16_t* w1, const float* b1, 
                        w1, b1, w2, b2, heads_per_scorer_row, rows_per_block);
 }
 
+template <int MTW>
+static void launch_wide(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
+                        const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
+                        hipStream_t stream) {
+  const int blocks = tab.first[tab.n];
+  const size_t lds = (size_t)2 * kMlpWaveLds + 32 * sizeof(float) + 4 * MTW * 16 * sizeof(float);
+  if (act == kActSilu)
+    hipLaunchKernelGGL((score_mlp_wide_kernel<MTW, kActSilu>), dim3(blocks), dim3(kWideThreads), lds, stream, tab,
+                       w1, b1, w2, b2, hidden, heads_per_scorer_row, rows_per_block);
+  else
+    hipLaunchKernelGGL((score_mlp_wide_kernel<MTW, kActGelu>), dim3(blocks), dim3(kWideThreads), lds, stream, tab,
+                       w1, b1, w2, b2, hidden, heads_per_scorer_row, rows_per_block);
+}
+
 // All sequences of one launch must share rows_per_block (the host groups them so).
 void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
                       const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
@@ -229,10 +400,8 @@ void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, 
     case 2: launch_mt<2>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
     case 3: launch_mt<3>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
     case 4: launch_mt<4>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 5: launch_mt<5>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 6: launch_mt<6>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 7: launch_mt<7>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 8: launch_mt<8>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 5: case 6: launch_wide<3>(tab, w1, b1, w2, b2, hidden, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 7: case 8: launch_wide<4>(tab, w1, b1, w2, b2, hidden, act, heads_per_scorer_row, rows_per_block, stream); break;
     default: break;
   }
 }
