@@ -43,7 +43,7 @@ import numpy as np
 
 D_HEAD = 128
 
-_TAGS = {"kv": 1, "q": 2, "scorer": 3, "budget": 4, "seqlen": 5, "chan": 6, "noise": 7}
+_TAGS = {"kv": 1, "q": 2, "scorer": 3, "budget": 4, "seqlen": 5, "chan": 6, "noise": 7, "headpred": 8}
 
 
 @dataclasses.dataclass(frozen=True)
@@ -195,6 +195,24 @@ def draw_scorer(w: Workload, seed: int = 0) -> dict:
     b2 = rng.normal(0.0, std, size=(w.L, Hs)).astype(np.float32) if w.out_bias else None
     return {"kind": "mlp", "act": w.act, "hidden": w.hidden, "per_head": w.per_head,
             "w1": f32_to_bf16_bits(w1), "b1": b1, "w2": w2, "b2": b2}
+
+
+def draw_head_predictor(w: Workload, seed: int = 0, d_e: int = 128, hidden: int = 64,
+                        out_bias: bool = False, spread: float = 1.0):
+    """LKV-H inputs: head embeddings fp32 [L * H, d_e] and the shared predictor
+    (w1 fp32 [hidden, d_e], b1 fp32 [hidden], w2 fp32 [hidden], b2 float or None).
+
+    No trained embeddings exist here, so the draw is shaped to give what trained ones give in
+    the paper's figures: head scores a few units apart, so ratios from a few percent to near one.
+    """
+    rng = _rng(seed, w.cid, "headpred")
+    n = w.L * w.H
+    emb = rng.standard_normal(size=(n, d_e)).astype(np.float32)
+    w1 = (rng.standard_normal(size=(hidden, d_e)) / np.sqrt(d_e)).astype(np.float32)
+    b1 = rng.normal(0.0, 0.1, size=hidden).astype(np.float32)
+    w2 = (rng.standard_normal(size=hidden) * (spread * 4.0 / np.sqrt(hidden))).astype(np.float32)
+    b2 = float(np.float32(rng.normal(0.0, 0.1))) if out_bias else None
+    return emb, {"w1": w1, "b1": b1, "w2": w2, "b2": b2, "d_e": d_e, "hidden": hidden}
 
 
 def draw_kv_layer(w: Workload, T: int, seq: int, layer: int, seed: int = 0,
