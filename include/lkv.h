@@ -151,6 +151,45 @@ lkv_status lkv_decode_attn(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_
                            float scale, float *out, float *lse, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
+
+/* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):
+ *   y_i = f(x_i / tau - lambda),  f(z) = (1 + sgn(z)(1 - e^{-|z|})) / 2,  sum_i y_i = k.
+ * fp64 arithmetic, sums carried as logarithms (any tau > 0 is safe).  One workgroup sorts the
+ * input in LDS, hence the size limit lkv_soft_topk_max_n (32768 for fp32 input, 16384 for fp64).
+ * x    : DEVICE fp32 [n] (x_is_f64 = 0) or fp64 [n] (x_is_f64 = 1); finite values
+ * k    : target sum, in the open interval (0, n)
+ * tau  : temperature, > 0
+ * y    : DEVICE fp64 [n]; may be the same buffer as an fp64 x
+ * info : DEVICE fp64 [2] or NULL: info[0] = lambda (in units of x / tau), info[1] = split index m
+ * Errors: LKV_ERR_INVALID_ARG for k, tau or n out of range, LKV_ERR_UNSUPPORTED beyond the size limit. */
+int32_t lkv_soft_topk_max_n(int32_t x_is_f64);
+lkv_status lkv_soft_topk(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t n, double k, double tau,
+                         double *y, double *info, void *stream);
+
+/* Shared head predictor of LKV-H (Sec. 3.3; Table 5: 128 -> 64 -> 1, SiLU, hidden bias, no
+ * output bias).  All pointers DEVICE fp32; b2 may be NULL. */
+typedef struct lkv_head_predictor {
+  int32_t d_e;       /* embedding width */
+  int32_t hidden;    /* hidden units, <= 4096 */
+  const float *w1;   /* [hidden, d_e] */
+  const float *b1;   /* [hidden] */
+  const float *w2;   /* [hidden] */
+  const float *b2;   /* [1] or NULL */
+} lkv_head_predictor;
+
+/* Retention ratios and integer budgets of all heads (Sec. 3.3):
+ *   s_i = MLP_head(e_i),  r = ST_{R n}(s) at tau = 1,  b_i = floor(r_i * t).
+ * fp64 arithmetic.  The ratios depend only on static parameters: compute once, keep.
+ * emb : DEVICE fp32 [n_heads, d_e], heads flattened layer-major (l * H + h)
+ * R   : global retention ratio in (0, 1)
+ * t   : context length the budgets are for (ignored when b is NULL)
+ * r   : DEVICE fp64 [n_heads], every value in (0, 1), sum = R * n_heads
+ * b   : DEVICE int32 [n_heads] or NULL; sum <= floor(R * n_heads * t)
+ * Budgets reach lkv_select through host memory: copy b back after the stream has finished. */
+lkv_status lkv_head_budgets(lkv_ctx *ctx, const float *emb, const lkv_head_predictor *predictor,
+                            int32_t n_heads, double R, int32_t t, double *r, int32_t *b, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -3,6 +3,7 @@
 // Every check runs before anything is enqueued.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -97,7 +98,7 @@ lkv_status lkv_create(lkv_ctx** out, int device) {
     }
   }
   if (lkv::select_prepare() != hipSuccess || lkv::decode_prepare() != hipSuccess ||
-      lkv::score_mlp_prepare() != hipSuccess) {
+      lkv::score_mlp_prepare() != hipSuccess || lkv::lkv_h_prepare() != hipSuccess) {
     lkv_destroy(ctx);
     return LKV_ERR_HIP;
   }
@@ -320,6 +321,51 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
   if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, (int)n_seg, total_kept, scale, out, lse,
                                         static_cast<float*>(workspace), as_stream(stream)))
     return hip_fail(ctx, e, "lkv_decode_attn launch");
+  return LKV_OK;
+}
+
+int32_t lkv_soft_topk_max_n(int32_t x_is_f64) { return lkv::soft_topk_max_n(x_is_f64 != 0); }
+
+lkv_status lkv_soft_topk(lkv_ctx* ctx, const void* x, int32_t x_is_f64, int32_t n, double k, double tau, double* y,
+                         double* info, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (x == nullptr || y == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "x or y is NULL");
+  if (n < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n = %d must be >= 1", n);
+  if (!(k > 0.0) || !(k < (double)n)) return fail(ctx, LKV_ERR_INVALID_ARG, "k = %g must lie in the open interval (0, %d)", k, n);
+  if (!(tau > 0.0) || std::isinf(tau)) return fail(ctx, LKV_ERR_INVALID_ARG, "tau = %g must be positive and finite", tau);
+  if (n > lkv::soft_topk_max_n(x_is_f64 != 0))
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "n = %d exceeds the single-workgroup limit %d for this input type", n,
+                lkv::soft_topk_max_n(x_is_f64 != 0));
+  if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, LKV_ERR_HIP, "hipSetDevice failed");
+  lkv::launch_soft_topk(x, x_is_f64 != 0, n, k, tau, y, info, nullptr, 0.0, as_stream(stream));
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e, "soft top-k launch");
+  return LKV_OK;
+}
+
+lkv_status lkv_head_budgets(lkv_ctx* ctx, const float* emb, const lkv_head_predictor* p, int32_t n_heads, double R,
+                            int32_t t, double* r, int32_t* b, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (emb == nullptr || p == nullptr || r == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "emb, predictor or r is NULL");
+  if (p->w1 == nullptr || p->b1 == nullptr || p->w2 == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "predictor w1, b1 or w2 is NULL");
+  if (n_heads < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n_heads = %d must be >= 1", n_heads);
+  if (p->d_e < 1 || p->hidden < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "d_e and hidden must be >= 1");
+  if (p->hidden > lkv::head_scores_max_hidden())
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d exceeds %d", p->hidden, lkv::head_scores_max_hidden());
+  if (n_heads > lkv::soft_topk_max_n(true))
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "n_heads = %d exceeds %d", n_heads, lkv::soft_topk_max_n(true));
+  // k = R L H must stay inside (0, n): the operator is undefined at the ends (App. A.1)
+  const double k = R * (double)n_heads;
+  if (!(k > 0.0) || !(k < (double)n_heads)) return fail(ctx, LKV_ERR_INVALID_ARG, "R = %g must lie in the open interval (0, 1)", R);
+  if (b != nullptr && t < 0) return fail(ctx, LKV_ERR_INVALID_ARG, "t = %d must be >= 0", t);
+  if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, LKV_ERR_HIP, "hipSetDevice failed");
+  lkv::launch_head_scores(emb, p->w1, p->b1, p->w2, p->b2, n_heads, p->d_e, p->hidden, r, as_stream(stream));
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e, "head score launch");
+  lkv::launch_soft_topk(r, true, n_heads, k, 1.0, r, nullptr, b, (double)t, as_stream(stream));
+  e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e, "soft top-k launch");
   return LKV_OK;
 }
 

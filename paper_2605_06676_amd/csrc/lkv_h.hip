@@ -1,0 +1,256 @@
+// LKV-H at inference time (Sec. 3.3) and the forward Soft-TopK operator ST_k (Sec. 3.2, Eq. 2,
+// App. A.1), in fp64.  Both are tiny next to the cache kernels (L * H <= a few hundred heads,
+// computed once and frozen), so one workgroup does the whole operator and the arithmetic is
+// double precision throughout: the ratios decide integer budgets floor(r t).
+//
+// ST_k(x)_i = f(x_i / tau - lambda), f the Laplace CDF, lambda such that the outputs sum to k.
+// With the inputs in descending order and m = #{i : x_i / tau >= lambda}, App. A.1 gives lambda in
+// closed form from S1 = sum_{i <= m} e^{-x_i}, S2 = sum_{i > m} e^{x_i}.  The split index is found
+// without trying every m: g(v) = sum_i f(x_i - v) - k decreases in v, so x_j >= lambda exactly
+// when g(x_j) <= 0, and g at the element of rank j needs only the prefix sum S1(j) and the suffix
+// sum S2(j).  All sums are carried as logarithms so that x / tau with a tiny tau cannot overflow.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+
+#include "lkv_kernels.h"
+
+namespace lkv {
+
+namespace {
+
+constexpr int kStThreads = 1024;
+constexpr int kStKeyBytes = 128 * 1024;   // LDS given to the sort keys
+constexpr int kStLocal = 32;              // elements per thread chunk at the largest n
+
+__device__ inline double log_add_exp(double a, double b) {   // log(e^a + e^b); -inf means an empty sum
+  const double hi = fmax(a, b);
+  const double lo = fmin(a, b);
+  if (lo == -INFINITY) return hi;
+  return hi + log1p(exp(lo - hi));
+}
+
+// keys whose unsigned order is the numeric order of the values
+__device__ inline uint32_t to_key(float x) {
+  const uint32_t u = __float_as_uint(x);
+  return (u >> 31) ? ~u : (u | 0x80000000u);
+}
+__device__ inline uint64_t to_key(double x) {
+  const uint64_t u = (uint64_t)__double_as_longlong(x);
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ull);
+}
+__device__ inline double from_key(uint32_t k) {
+  const uint32_t u = (k >> 31) ? (k & 0x7fffffffu) : ~k;
+  return (double)__uint_as_float(u);
+}
+__device__ inline double from_key(uint64_t k) {
+  const uint64_t u = (k >> 63) ? (k & 0x7fffffffffffffffull) : ~k;
+  return __longlong_as_double((long long)u);
+}
+
+// log( sqrt(d^2 + e^L) + d ) for d >= 0
+__device__ inline double log_root_plus(double d, double L) {
+  const double h = 0.5 * L;
+  if (d == 0.0) return h;
+  if (h > 300.0) return h + asinh(d * exp(-h));
+  return log(hypot(d, exp(h)) + d);
+}
+
+// value of sum_i f(x_i - v) - k at the element v of rank j (1-based, descending), given
+// log S1(j) = log sum_{i <= j} e^{-x_i} and log S2(j) = log sum_{i > j} e^{x_i}
+__device__ inline double constraint_at(double v, int j, double log_s1, double log_s2, double k) {
+  return ((double)j - k) - 0.5 * exp(v + log_s1) + 0.5 * exp(log_s2 - v);
+}
+
+struct StShared {
+  double lambda;
+  int m;
+  int pad;
+};
+
+template <typename X, typename Key>
+__global__ void __launch_bounds__(kStThreads)
+soft_topk_kernel(const X* __restrict__ x, int n, int P, double k, double tau, double* __restrict__ y,
+                 double* __restrict__ info, int32_t* __restrict__ budgets, double t) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  Key* keys = reinterpret_cast<Key*>(smem);                                  // [P]
+  double* pre = reinterpret_cast<double*>(smem + (size_t)P * sizeof(Key));  // [1024] prefix of log S1
+  double* suf = pre + kStThreads;                                            // [1024] suffix of log S2
+  double* loc = suf + kStThreads;                                            // [kStLocal]
+  StShared* sh = reinterpret_cast<StShared*>(loc + kStLocal);
+  const int tid = threadIdx.x;
+
+  for (int i = tid; i < P; i += kStThreads) keys[i] = i < n ? to_key(x[i]) : (Key)0;
+  __syncthreads();
+
+  // bitonic sort, descending
+  for (int span = 2; span <= P; span <<= 1) {
+    for (int j = span >> 1; j > 0; j >>= 1) {
+      for (int i = tid; i < (P >> 1); i += kStThreads) {
+        const int a = ((i & ~(j - 1)) << 1) | (i & (j - 1));
+        const int b = a | j;
+        const Key ka = keys[a], kb = keys[b];
+        const bool descending = (a & span) == 0;
+        if (descending ? (ka < kb) : (ka > kb)) {
+          keys[a] = kb;
+          keys[b] = ka;
+        }
+      }
+      __syncthreads();
+    }
+  }
+
+  // per-thread chunk of the sorted values
+  const int c = (n + kStThreads - 1) / kStThreads;
+  const int start = min(n, tid * c);
+  const int end = min(n, start + c);
+  double a_loc = -INFINITY, b_loc = -INFINITY;
+  for (int i = start; i < end; ++i) {
+    const double v = from_key(keys[i]) / tau;
+    a_loc = log_add_exp(a_loc, -v);
+    b_loc = log_add_exp(b_loc, v);
+  }
+  pre[tid] = a_loc;
+  suf[tid] = b_loc;
+  __syncthreads();
+  for (int off = 1; off < kStThreads; off <<= 1) {
+    const double pa = tid >= off ? pre[tid - off] : -INFINITY;
+    const double sb = tid + off < kStThreads ? suf[tid + off] : -INFINITY;
+    __syncthreads();
+    pre[tid] = log_add_exp(pre[tid], pa);
+    suf[tid] = log_add_exp(suf[tid], sb);
+    __syncthreads();
+  }
+  const double before = tid > 0 ? pre[tid - 1] : -INFINITY;               // log S1 of everything ahead of the chunk
+  const double after = tid + 1 < kStThreads ? suf[tid + 1] : -INFINITY;   // log S2 of everything behind it
+
+  // chunks whose last element is still at or above the threshold are wholly in the head
+  bool whole = false;
+  if (end > start) {
+    const double v = from_key(keys[end - 1]) / tau;
+    whole = constraint_at(v, end, pre[tid], after, k) <= 0.0;
+  }
+  const int full_chunks = __syncthreads_count(whole);
+  const int used_chunks = (n + c - 1) / c;
+
+  if (tid == min(full_chunks, kStThreads - 1)) {
+    int m;
+    double log_s1, log_s2;
+    if (full_chunks >= used_chunks) {   // every element is at or above the threshold
+      m = n;
+      log_s1 = pre[kStThreads - 1];
+      log_s2 = -INFINITY;
+    } else {
+      // the split lies in this thread's chunk: suffix sums inside the chunk, then a forward walk
+      const int cnt = end - start;
+      double run = -INFINITY;
+      for (int i = cnt - 1; i >= 0; --i) {
+        loc[i] = run;   // log sum of e^{x} over the chunk elements behind element i
+        run = log_add_exp(run, from_key(keys[start + i]) / tau);
+      }
+      m = start;
+      log_s1 = before;
+      log_s2 = log_add_exp(run, after);
+      double s1 = before;
+      for (int i = 0; i < cnt; ++i) {
+        const double v = from_key(keys[start + i]) / tau;
+        s1 = log_add_exp(s1, -v);
+        const double s2 = log_add_exp(loc[i], after);
+        if (constraint_at(v, start + i + 1, s1, s2, k) > 0.0) break;
+        m = start + i + 1;
+        log_s1 = s1;
+        log_s2 = s2;
+      }
+    }
+    // closed form of App. A.1 for y = e^lambda: S1 y^2 + 2 (k - m) y - S2 = 0, positive root,
+    // written so that neither a difference of close numbers nor an overflow occurs
+    const double d = k - (double)m;
+    double lambda;
+    if (m == 0) lambda = log_s2 - log(2.0 * k);
+    else if (m == n) lambda = log(2.0 * ((double)n - k)) - log_s1;
+    else if (d >= 0.0) lambda = log_s2 - log_root_plus(d, log_s1 + log_s2);
+    else lambda = log_root_plus(-d, log_s1 + log_s2) - log_s1;
+    sh->lambda = lambda;
+    sh->m = m;
+  }
+  __syncthreads();
+  const double lambda = sh->lambda;
+  if (tid == 0 && info != nullptr) {
+    info[0] = lambda;
+    info[1] = (double)sh->m;
+  }
+  for (int i = tid; i < n; i += kStThreads) {
+    const double z = (double)x[i] / tau - lambda;
+    const double r = z >= 0.0 ? 1.0 - 0.5 * exp(-z) : 0.5 * exp(z);
+    if (y != nullptr) y[i] = r;
+    if (budgets != nullptr) budgets[i] = (int32_t)floor(r * t);
+  }
+}
+
+// s = w2 . SiLU(W1 e + b1) (+ b2) for one head per block
+__global__ void __launch_bounds__(256)
+head_scores_kernel(const float* __restrict__ emb, const float* __restrict__ w1, const float* __restrict__ b1,
+                   const float* __restrict__ w2, const float* __restrict__ b2, int d_e, int hidden,
+                   double* __restrict__ s) {
+  extern __shared__ __align__(16) unsigned char smem[];
+  double* part = reinterpret_cast<double*>(smem);   // [hidden]
+  const float* e = emb + (size_t)blockIdx.x * d_e;
+  for (int j = threadIdx.x; j < hidden; j += blockDim.x) {
+    const float* w = w1 + (size_t)j * d_e;
+    double z = 0.0;
+    for (int q = 0; q < d_e; ++q) z = fma((double)w[q], (double)e[q], z);
+    z += (double)b1[j];
+    part[j] = (double)w2[j] * (z / (1.0 + exp(-z)));
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double acc = 0.0;
+    for (int j = 0; j < hidden; ++j) acc += part[j];
+    if (b2 != nullptr) acc += (double)b2[0];
+    s[blockIdx.x] = acc;
+  }
+}
+
+int padded_size(int n) {
+  int P = 2;
+  while (P < n) P <<= 1;
+  return P;
+}
+
+size_t soft_topk_lds(int P, size_t key_bytes) {
+  return (size_t)P * key_bytes + (size_t)(2 * kStThreads + kStLocal) * sizeof(double) + sizeof(StShared);
+}
+
+}  // namespace
+
+int soft_topk_max_n(bool is_f64) { return kStKeyBytes / (int)(is_f64 ? sizeof(uint64_t) : sizeof(uint32_t)); }
+int head_scores_max_hidden() { return 4096; }
+
+hipError_t lkv_h_prepare() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(soft_topk_kernel<float, uint32_t>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize,
+                                     (int)soft_topk_lds(kStKeyBytes / 4, 4));
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(soft_topk_kernel<double, uint64_t>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, (int)soft_topk_lds(kStKeyBytes / 8, 8));
+}
+
+// y, info and budgets may each be null; y may alias x when x is fp64
+void launch_soft_topk(const void* x, bool is_f64, int n, double k, double tau, double* y, double* info,
+                      int32_t* budgets, double t, hipStream_t stream) {
+  const int P = padded_size(n);
+  if (is_f64)
+    hipLaunchKernelGGL((soft_topk_kernel<double, uint64_t>), dim3(1), dim3(kStThreads), soft_topk_lds(P, 8), stream,
+                       static_cast<const double*>(x), n, P, k, tau, y, info, budgets, t);
+  else
+    hipLaunchKernelGGL((soft_topk_kernel<float, uint32_t>), dim3(1), dim3(kStThreads), soft_topk_lds(P, 4), stream,
+                       static_cast<const float*>(x), n, P, k, tau, y, info, budgets, t);
+}
+
+void launch_head_scores(const float* emb, const float* w1, const float* b1, const float* w2, const float* b2,
+                        int n_heads, int d_e, int hidden, double* s, hipStream_t stream) {
+  hipLaunchKernelGGL(head_scores_kernel, dim3(n_heads), dim3(256), (size_t)hidden * sizeof(double), stream, emb, w1,
+                     b1, w2, b2, d_e, hidden, s);
+}
+
+}  // namespace lkv

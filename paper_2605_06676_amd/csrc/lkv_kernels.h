@@ -36,4 +36,13 @@ hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, c
                          int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
                          hipStream_t stream);
 
+// lkv_h.hip
+hipError_t lkv_h_prepare();
+int soft_topk_max_n(bool is_f64);
+int head_scores_max_hidden();
+void launch_soft_topk(const void* x, bool is_f64, int n, double k, double tau, double* y, double* info,
+                      int32_t* budgets, double t, hipStream_t stream);
+void launch_head_scores(const float* emb, const float* w1, const float* b1, const float* w2, const float* b2,
+                        int n_heads, int d_e, int hidden, double* s, hipStream_t stream);
+
 }  // namespace lkv

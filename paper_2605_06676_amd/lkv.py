@@ -20,7 +20,8 @@ ACT_SILU, ACT_GELU_ERF = 0, 1
 _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "LKV_ERR_WORKSPACE", 4: "LKV_ERR_HIP"}
 
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
-           "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn")
+           "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
+           "lkv_soft_topk", "lkv_head_budgets")
 
 
 class LkvError(RuntimeError):
@@ -38,6 +39,11 @@ class _Cache(C.Structure):
 class _Scorer(C.Structure):
     _fields_ = [("kind", C.c_int32), ("act", C.c_int32), ("hidden", C.c_int32), ("per_head", C.c_int32),
                 ("w1", C.c_void_p), ("b1", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p)]
+
+
+class _HeadPredictor(C.Structure):
+    _fields_ = [("d_e", C.c_int32), ("hidden", C.c_int32), ("w1", C.c_void_p), ("b1", C.c_void_p),
+                ("w2", C.c_void_p), ("b2", C.c_void_p)]
 
 
 _lib = None
@@ -73,6 +79,14 @@ def load_library() -> C.CDLL:
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lkv_decode_attn.restype = C.c_int
+    lib.lkv_soft_topk_max_n.argtypes = [C.c_int32]
+    lib.lkv_soft_topk_max_n.restype = C.c_int32
+    lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
+                                  C.c_void_p, C.c_void_p]
+    lib.lkv_soft_topk.restype = C.c_int
+    lib.lkv_head_budgets.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_HeadPredictor), C.c_int32, C.c_double,
+                                     C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.lkv_head_budgets.restype = C.c_int
     _lib = lib
     return lib
 
@@ -175,3 +189,36 @@ def lkv_decode_attn(ctx: Context, n_seq: int, L: int, H: int, Hq: int, d: int, q
     ctx._check(ctx.lib.lkv_decode_attn(ctx.h, n_seq, L, H, Hq, d, _ptr(q), _ptr(kp), _ptr(vp), _ptr(offsets),
                                        int(total_kept), float(scale), _ptr(out), _ptr(lse), _ptr(workspace),
                                        ws_bytes, _stream_ptr(stream)))
+
+
+def lkv_soft_topk_max_n(x_is_f64: bool) -> int:
+    return int(load_library().lkv_soft_topk_max_n(1 if x_is_f64 else 0))
+
+
+def lkv_soft_topk(ctx: Context, x, k: float, tau: float, y, info=None, stream=None) -> None:
+    """x: GPU fp32 or fp64 [n]; y: GPU fp64 [n]; info: GPU fp64 [2] or None."""
+    import torch
+
+    assert x.dtype in (torch.float32, torch.float64) and x.is_contiguous()
+    assert y.dtype == torch.float64 and y.numel() == x.numel() and y.is_contiguous()
+    assert info is None or (info.dtype == torch.float64 and info.numel() >= 2)
+    ctx._check(ctx.lib.lkv_soft_topk(ctx.h, _ptr(x), 1 if x.dtype == torch.float64 else 0, int(x.numel()), float(k),
+                                     float(tau), _ptr(y), _ptr(info), _stream_ptr(stream)))
+
+
+def lkv_head_budgets(ctx: Context, emb, predictor: dict, R: float, t: int, r, b=None, stream=None) -> None:
+    """emb: GPU fp32 [n_heads, d_e]; predictor: dict of GPU fp32 tensors w1 [hidden, d_e], b1, w2 and
+    b2 ([1]) or None; r: GPU fp64 [n_heads]; b: GPU int32 [n_heads] or None."""
+    import torch
+
+    n_heads, d_e = emb.shape
+    hidden = predictor["w1"].shape[0]
+    for name in ("w1", "b1", "w2"):
+        assert predictor[name].dtype == torch.float32 and predictor[name].is_contiguous()
+    assert emb.dtype == torch.float32 and emb.is_contiguous() and predictor["w1"].shape[1] == d_e
+    assert r.dtype == torch.float64 and r.numel() == n_heads
+    assert b is None or (b.dtype == torch.int32 and b.numel() == n_heads)
+    p = _HeadPredictor(d_e, hidden, _ptr(predictor["w1"]), _ptr(predictor["b1"]), _ptr(predictor["w2"]),
+                       _ptr(predictor.get("b2")))
+    ctx._check(ctx.lib.lkv_head_budgets(ctx.h, _ptr(emb), C.byref(p), n_heads, float(R), int(t), _ptr(r), _ptr(b),
+                                        _stream_ptr(stream)))

@@ -198,7 +198,7 @@ def draw_scorer(w: Workload, seed: int = 0) -> dict:
 
 
 def draw_head_predictor(w: Workload, seed: int = 0, d_e: int = 128, hidden: int = 64,
-                        out_bias: bool = False, spread: float = 1.0):
+                        out_bias: bool = False, spread: float = 0.5):
     """LKV-H inputs: head embeddings fp32 [L * H, d_e] and the shared predictor
     (w1 fp32 [hidden, d_e], b1 fp32 [hidden], w2 fp32 [hidden], b2 float or None).
 
