@@ -36,7 +36,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="workload 0..4 (1 = the Llama-3-8B-shaped 32k cache)")
+    ap.add_argument("--config", type=int, default=1, help="workload 0..5 (1 = the Llama-3-8B-shaped 32k cache)")
+    ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
+                    help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (a kernel of known "
@@ -84,7 +86,30 @@ def main():
     scorer = {"kind": sc_host["kind"], "act": sc_host["act"], "hidden": sc_host["hidden"],
               "per_head": sc_host["per_head"], "w1": to_dev(sc_host["w1"], True), "b1": to_dev(sc_host["b1"]),
               "w2": to_dev(sc_host["w2"]), "b2": to_dev(sc_host["b2"])}
-    budgets = [W.draw_budgets(w, T, s) for s, T in enumerate(Ts)]
+    # LKV-H (Sec. 3.3): ratios are computed once from static parameters; timed apart from the step
+    emb_h, mlp_h = W.draw_head_predictor(w)
+    emb_d = to_dev(emb_h)
+    pred_d = {k: to_dev(mlp_h[k]) for k in ("w1", "b1", "w2")}
+    pred_d["b2"] = None
+    r_d = torch.empty((w.L * w.H,), dtype=torch.float64, device=dev)
+    b_d = torch.empty((w.L * w.H,), dtype=torch.int32, device=dev)
+    lkv.lkv_head_budgets(ctx, emb_d, pred_d, w.R, Ts[0], r_d, b_d)
+    torch.cuda.synchronize()
+    eh = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    eh[0].record()
+    for _ in range(20):
+        lkv.lkv_head_budgets(ctx, emb_d, pred_d, w.R, Ts[0], r_d, b_d)
+    eh[1].record()
+    torch.cuda.synchronize()
+    lkv_h_us = eh[0].elapsed_time(eh[1]) * 1e3 / 20
+    if args.budgets == "lkvh":
+        budgets = []
+        for T in Ts:
+            lkv.lkv_head_budgets(ctx, emb_d, pred_d, w.R, T, r_d, b_d)
+            torch.cuda.synchronize()
+            budgets.append(b_d.cpu().numpy().reshape(w.L, w.H).astype(np.int32))
+    else:
+        budgets = [W.draw_budgets(w, T, s) for s, T in enumerate(Ts)]
     budgets_flat = np.concatenate([b.reshape(-1) for b in budgets]).astype(np.int32)
     total = int(budgets_flat.sum())
     N = sum(w.L * w.H * T for T in Ts)
@@ -164,6 +189,9 @@ def main():
                      "bytes_per_launch": score_bytes},
     }
 
+    result["config"]["budgets"] = "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe"
+    result["lkv_h"] = {"n_heads": w.L * w.H, "us_per_call": lkv_h_us, "dtype": "f64",
+                       "note": "head scores + Soft-TopK + floor(r t); computed once, outside the step"}
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
     print(json.dumps(result))
