@@ -151,6 +151,35 @@ lkv_status lkv_decode_attn(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_
                            float scale, float *out, float *lse, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* ---- Layer-by-layer eviction during prefill (Sec. 1: each layer's cache is evicted as soon as
+ * the prefill has produced it, so the full cache of all layers never exists) ---------------- */
+
+/* The packed layout follows from the budgets alone (they are static, Sec. 3.3), so it can be
+ * fixed before any layer exists: offsets[s] = sum of the budgets of the segments before s.
+ * budgets    : HOST int32 [n_segments], each >= 0, sum < 2^31
+ * offsets    : DEVICE int32 [n_segments + 1]
+ * total_kept : HOST out, may be NULL
+ * The upload is asynchronous on `stream` (pinned staging owned by the context). */
+lkv_status lkv_plan_offsets(lkv_ctx *ctx, int64_t n_segments, const int32_t *budgets, int32_t *offsets,
+                            int64_t *total_kept, void *stream);
+
+/* Score, select and compact ONE layer into its final rows of the packed cache; the result is bit
+ * for bit what lkv_score + lkv_select + lkv_compact over the whole cache write for that layer.
+ * All work is enqueued on `stream`, so it can overlap the prefill of the next layer on another
+ * stream; the layer's K/V may be released once the stream has passed this call.
+ * layer       : a cache description with n_layers = 1 whose k[s], v[s] point at bf16 [H, T_s, d] of
+ *               this layer; at most 32 sequences
+ * layer_index : which layer of the model this is, in [0, n_layers)
+ * scorer      : the whole model's scorer (parameters of all layers), as for lkv_score
+ * budgets     : HOST int32 [n_seq, n_layers, H], the same table lkv_plan_offsets was given
+ * offsets     : DEVICE int32 [n_seq * n_layers * H + 1] written by lkv_plan_offsets
+ * scores      : HOST [n_seq] of DEVICE fp32 [H, T_s]: scratch, overwritten
+ * idx         : DEVICE int32 [total_kept], the global index buffer (this layer's part is written)
+ * kp, vp      : DEVICE bf16 [total_kept, d], the global packed cache (this layer's rows are written) */
+lkv_status lkv_evict_layer(lkv_ctx *ctx, const lkv_cache *layer, int32_t layer_index, int32_t n_layers,
+                           const lkv_scorer *scorer, const int32_t *budgets, const int32_t *offsets,
+                           float *const *scores, int32_t *idx, void *kp, void *vp, void *stream);
+
 /* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
 
 /* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):

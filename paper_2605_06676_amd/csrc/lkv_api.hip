@@ -152,13 +152,13 @@ lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* sco
     lkv::SeqTable tab;
     memset(&tab, 0, sizeof(tab));
     int64_t blocks = 0;
-    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s]) : 0;
+    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s], (int)heads) : 0;
     int n = 0;
     while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
       const int T = cache->seq_len[s];
       int64_t per_head;
       if (scorer->kind == LKV_SCORER_MLP) {
-        if (lkv::score_mlp_rows_per_block(T) != rpb0) break;
+        if (lkv::score_mlp_rows_per_block(T, (int)heads) != rpb0) break;
         per_head = (T + rpb0 - 1) / rpb0;
       } else {
         per_head = lkv::score_linear_blocks_per_head(T);
@@ -254,7 +254,7 @@ lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* 
     }
     tab.first[n] = n * heads;
     tab.n = n;
-    lkv::launch_select(tab, inline_offsets ? host_off : nullptr, (int)n_seg, offsets, idx, s0 * heads, st);
+    lkv::launch_select(tab, inline_offsets ? host_off : nullptr, (int)n_seg, offsets, idx, s0 * heads, heads, st);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_select launch");
   }
   return LKV_OK;
@@ -283,7 +283,7 @@ lkv_status lkv_compact(lkv_ctx* ctx, const lkv_cache* cache, const int32_t* idx,
       tab.T[i] = cache->seq_len[s0 + i];
     }
     tab.n = n;
-    lkv::launch_compact(tab, idx, offsets, n_seg, heads, s0, total_kept, kp, vp, st);
+    lkv::launch_compact(tab, idx, offsets, n_seg, heads, s0, 0, heads, 0, total_kept, kp, vp, st);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_compact launch");
   }
   return LKV_OK;
@@ -321,6 +321,125 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
   if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, (int)n_seg, total_kept, scale, out, lse,
                                         static_cast<float*>(workspace), as_stream(stream)))
     return hip_fail(ctx, e, "lkv_decode_attn launch");
+  return LKV_OK;
+}
+
+lkv_status lkv_plan_offsets(lkv_ctx* ctx, int64_t n_segments, const int32_t* budgets, int32_t* offsets,
+                            int64_t* total_kept, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (budgets == nullptr || offsets == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "budgets or offsets is NULL");
+  if (n_segments < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n_segments = %lld must be >= 1", (long long)n_segments);
+  if (n_segments > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "%lld segments exceed the staging capacity", (long long)n_segments);
+  int64_t total = 0;
+  for (int64_t i = 0; i < n_segments; ++i) {
+    if (budgets[i] < 0) return fail(ctx, LKV_ERR_INVALID_ARG, "budget %d of segment %lld is negative", budgets[i], (long long)i);
+    total += budgets[i];
+  }
+  if (total >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "sum of budgets %lld >= 2^31", (long long)total);
+  hipStream_t st = as_stream(stream);
+  const int slot = ctx->stage_next;
+  ctx->stage_next = (slot + 1) % kStageSlots;
+  if (ctx->stage_used[slot]) {
+    if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
+  }
+  int32_t* host_off = static_cast<int32_t*>(ctx->stage[slot]);
+  int32_t run = 0;
+  for (int64_t i = 0; i < n_segments; ++i) {
+    host_off[i] = run;
+    run += budgets[i];
+  }
+  host_off[n_segments] = run;
+  if (hipError_t e = hipMemcpyAsync(offsets, host_off, (size_t)(n_segments + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st))
+    return hip_fail(ctx, e, "offsets upload");
+  if (hipError_t e = hipEventRecord(ctx->stage_done[slot], st)) return hip_fail(ctx, e, "staging event");
+  ctx->stage_used[slot] = true;
+  if (total_kept != nullptr) *total_kept = total;
+  return LKV_OK;
+}
+
+lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_index, int32_t n_layers,
+                           const lkv_scorer* scorer, const int32_t* budgets, const int32_t* offsets,
+                           float* const* scores, int32_t* idx, void* kp, void* vp, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, layer, true)) return st;
+  if (layer->n_layers != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "the layer view must have n_layers = 1, got %d", layer->n_layers);
+  if (n_layers < 1 || layer_index < 0 || layer_index >= n_layers)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "layer_index %d is outside [0, %d)", layer_index, n_layers);
+  if (scorer == nullptr || budgets == nullptr || offsets == nullptr || scores == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "scorer, budgets, offsets or scores is NULL");
+  const int H = layer->n_kv_heads;
+  const int heads_all = n_layers * H;
+  const int64_t n_seg = (int64_t)heads_all * layer->n_seq;
+  if (n_seg > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+
+  // row ranges of this layer's segments in the packed cache, from the same prefix sums the plan uploaded
+  int64_t run = 0, layer_rows = 0;
+  int64_t row_lo[lkv::kMaxSeqPerLaunch], row_hi[lkv::kMaxSeqPerLaunch];
+  if (layer->n_seq > lkv::kMaxSeqPerLaunch)
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "a layer view holds at most %d sequences, got %d", lkv::kMaxSeqPerLaunch, layer->n_seq);
+  for (int s = 0; s < layer->n_seq; ++s) {
+    const int T = layer->seq_len[s];
+    for (int j = 0; j < heads_all; ++j) {
+      const int32_t b = budgets[(size_t)s * heads_all + j];
+      if (b < 0 || b > T)
+        return fail(ctx, LKV_ERR_INVALID_ARG, "budget %d of segment %lld is outside [0, %d]", b, (long long)s * heads_all + j, T);
+      if (j == layer_index * H) row_lo[s] = run;
+      run += b;
+      if (j == layer_index * H + H - 1) row_hi[s] = run;
+    }
+    layer_rows += row_hi[s] - row_lo[s];
+  }
+  if (run >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "sum of budgets %lld >= 2^31", (long long)run);
+  if (layer_rows > 0 && (idx == nullptr || kp == nullptr || vp == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "idx, kp or vp is NULL");
+  if (!aligned16(kp) || !aligned16(vp)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is not 16-byte aligned");
+
+  // score: the scorer parameters of this layer
+  if (scorer->kind != LKV_SCORER_LINEAR && scorer->kind != LKV_SCORER_MLP)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", scorer->kind);
+  if (scorer->w1 == nullptr || scorer->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
+  if (scorer->per_head != 0 && scorer->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
+  lkv_scorer sl = *scorer;
+  const size_t rows = (size_t)layer_index * (scorer->per_head ? H : 1);   // scorer rows ahead of this layer
+  if (scorer->kind == LKV_SCORER_LINEAR) {
+    sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * 2 * lkv::kHeadDim;
+    sl.b1 = scorer->b1 + rows;
+  } else {
+    if (scorer->hidden < 16 || scorer->hidden > 128 || scorer->hidden % 16 != 0)
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must be a multiple of 16 in [16, 128]", scorer->hidden);
+    if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
+    sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * (size_t)scorer->hidden * 2 * lkv::kHeadDim;
+    sl.b1 = scorer->b1 + rows * scorer->hidden;
+    sl.w2 = scorer->w2 + rows * scorer->hidden;
+    sl.b2 = scorer->b2 != nullptr ? scorer->b2 + rows : nullptr;
+  }
+  if (lkv_status st = lkv_score(ctx, layer, &sl, scores, stream)) return st;
+
+  hipStream_t st = as_stream(stream);
+  lkv::SeqTable tab;
+  memset(&tab, 0, sizeof(tab));
+  for (int i = 0; i < layer->n_seq; ++i) {
+    tab.k[i] = static_cast<const uint16_t*>(layer->k[i]);
+    tab.v[i] = static_cast<const uint16_t*>(layer->v[i]);
+    tab.scores[i] = scores[i];
+    tab.T[i] = layer->seq_len[i];
+    tab.first[i] = i * H;
+  }
+  tab.first[layer->n_seq] = layer->n_seq * H;
+  tab.n = layer->n_seq;
+  // select: segment of (sequence i, head h) is (i * n_layers + layer_index) * H + h, offsets already on the device
+  lkv::launch_select(tab, nullptr, (int)n_seg, const_cast<int32_t*>(offsets), idx, layer_index * H, heads_all, st);
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer select launch");
+  // compact: one contiguous row range per sequence
+  for (int i = 0; i < layer->n_seq; ++i) {
+    lkv::SeqTable one;
+    memset(&one, 0, sizeof(one));
+    one.k[0] = tab.k[i];
+    one.v[0] = tab.v[i];
+    one.T[0] = tab.T[i];
+    one.n = 1;
+    lkv::launch_compact(one, idx, offsets, (int)n_seg, heads_all, i, layer_index * H, H, row_lo[i], row_hi[i], kp, vp, st);
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer compact launch");
+  }
   return LKV_OK;
 }
 

@@ -15,18 +15,18 @@ hipError_t score_mlp_prepare();
 void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
                       const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
                       hipStream_t stream);
-int score_mlp_rows_per_block(int T);
+int score_mlp_rows_per_block(int T, int heads);
 
 // select.hip
 hipError_t select_prepare();
 int select_inline_capacity();
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
-                   int32_t* idx, int seg_base, hipStream_t stream);
+                   int32_t* idx, int seg_base, int seg_stride, hipStream_t stream);
 
 // compact.hip
 void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
-                    int heads_per_seq, int seq_lo, int64_t total_kept, void* kp, void* vp,
-                    hipStream_t stream);
+                    int heads_per_seq, int seq_lo, int head_lo, int n_heads_view, int64_t row_lo, int64_t row_hi,
+                    void* kp, void* vp, hipStream_t stream);
 
 // decode.hip
 constexpr int kDecodeMaxGroup = 16;

@@ -350,14 +350,15 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   store_tile(last, held);
 }
 
-int score_mlp_rows_per_block(int T) {
-  // large tiles amortise the 32 KB of W1 each wave loads; small heads keep more blocks
+int score_mlp_rows_per_block(int T, int heads) {
+  // large tiles amortise the 32 KB of W1 each wave loads; short heads, and launches over few
+  // heads (one layer at a time), take smaller tiles so that the grid still covers the chip
 #ifdef LKV_MLP_ROWS
   if (T >= 16384) return LKV_MLP_ROWS;
 #endif
-  if (T >= 16384) return 2048;
-  if (T >= 4096) return 1024;
-  return 256;
+  int rows = T >= 16384 ? 2048 : (T >= 4096 ? 1024 : 256);
+  while (rows > 256 && (int64_t)heads * ((T + rows - 1) / rows) < 1024) rows >>= 1;
+  return rows;
 }
 
 hipError_t score_mlp_prepare() { return hipSuccess; }

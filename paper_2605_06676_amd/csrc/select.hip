@@ -283,7 +283,8 @@ __device__ __forceinline__ void emit_from_bitmaps(SelShared& sh, int T, uint32_t
 template <bool kInline>
 __global__ void __launch_bounds__(kSelThreads)
 select_kernel(SeqTable tab, InlineOffsets inl, int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
-              int seg_base, int cached_limit /* heads of at most this many tokens use the LDS key cache */,
+              int seg_base, int seg_stride /* global segment = seg_base + sequence * seg_stride + head */,
+              int cached_limit /* heads of at most this many tokens use the LDS key cache */,
               int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */,
               int cached_stage_off, int bitmap_stage_off /* word offsets of the staging buffer in the region */) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -296,7 +297,7 @@ select_kernel(SeqTable tab, InlineOffsets inl, int32_t* __restrict__ offsets, in
   const int lh = local_seg - tab.first[seq];
   const int T = tab.T[seq];
   const float* u = tab.scores[seq] + (size_t)lh * (size_t)T;
-  const int seg = seg_base + local_seg;
+  const int seg = seg_base + seq * seg_stride + lh;
   const int off = kInline ? inl.v[seg] : offsets[seg];
   const int budget = (kInline ? inl.v[seg + 1] : offsets[seg + 1]) - off;
   if (kInline && tid == 0) {
@@ -380,7 +381,7 @@ int select_inline_capacity() { return kSelInlineOffsets; }
 // (n_total_segments < kSelInlineOffsets) and the kernel writes the device array; null: the
 // device array has already been filled.
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
-                   int32_t* idx, int seg_base, hipStream_t stream) {
+                   int32_t* idx, int seg_base, int seg_stride, hipStream_t stream) {
   const int segs = tab.first[tab.n];
   if (segs <= 0) return;
   // the LDS region is sized for the longest sequence of this launch that can use it
@@ -403,12 +404,12 @@ void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total
   if (host_offsets != nullptr) {
     for (int i = 0; i <= n_total_segments; ++i) inl.v[i] = host_offsets[i];
     hipLaunchKernelGGL(select_kernel<true>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
-                       inl, offsets, idx, seg_base, cached_limit, bitmap_limit, (int)cached_stage_off,
+                       inl, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
                        (int)bitmap_stage_off);
   } else {
     inl.v[0] = 0;
     hipLaunchKernelGGL(select_kernel<false>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
-                       inl, offsets, idx, seg_base, cached_limit, bitmap_limit, (int)cached_stage_off,
+                       inl, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
                        (int)bitmap_stage_off);
   }
 }

@@ -21,7 +21,7 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
-           "lkv_soft_topk", "lkv_head_budgets")
+           "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer")
 
 
 class LkvError(RuntimeError):
@@ -79,6 +79,13 @@ def load_library() -> C.CDLL:
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lkv_decode_attn.restype = C.c_int
+    lib.lkv_plan_offsets.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_void_p, C.POINTER(C.c_int64),
+                                     C.c_void_p]
+    lib.lkv_plan_offsets.restype = C.c_int
+    lib.lkv_evict_layer.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_int32, C.c_int32, C.POINTER(_Scorer),
+                                    C.POINTER(C.c_int32), C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_void_p]
+    lib.lkv_evict_layer.restype = C.c_int
     lib.lkv_soft_topk_max_n.argtypes = [C.c_int32]
     lib.lkv_soft_topk_max_n.restype = C.c_int32
     lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
@@ -152,13 +159,17 @@ class Context:
             raise LkvError(st, self.lib.lkv_last_error(self.h).decode())
 
 
+def _scorer_struct(scorer: dict) -> _Scorer:
+    kind = SCORER_LINEAR if scorer["kind"] == "linear" else SCORER_MLP
+    act = ACT_SILU if scorer.get("act", "silu") == "silu" else ACT_GELU_ERF
+    return _Scorer(kind, act, int(scorer.get("hidden", 0)), int(bool(scorer.get("per_head", False))),
+                   _ptr(scorer["w1"]), _ptr(scorer["b1"]), _ptr(scorer.get("w2")), _ptr(scorer.get("b2")))
+
+
 def lkv_score(ctx: Context, cache: Cache, scorer: dict, scores: Sequence, stream=None) -> None:
     """scorer: dict(kind, act, hidden, per_head, w1, b1, w2, b2) of GPU tensors (w1 bf16, others fp32).
     scores: per-sequence fp32 [L, H, T_s] GPU tensors, written in place."""
-    kind = SCORER_LINEAR if scorer["kind"] == "linear" else SCORER_MLP
-    act = ACT_SILU if scorer.get("act", "silu") == "silu" else ACT_GELU_ERF
-    sc = _Scorer(kind, act, int(scorer.get("hidden", 0)), int(bool(scorer.get("per_head", False))),
-                 _ptr(scorer["w1"]), _ptr(scorer["b1"]), _ptr(scorer.get("w2")), _ptr(scorer.get("b2")))
+    sc = _scorer_struct(scorer)
     sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
     ctx._check(ctx.lib.lkv_score(ctx.h, C.byref(cache.c), C.byref(sc), sp, _stream_ptr(stream)))
 
@@ -222,3 +233,30 @@ def lkv_head_budgets(ctx: Context, emb, predictor: dict, R: float, t: int, r, b=
                        _ptr(predictor.get("b2")))
     ctx._check(ctx.lib.lkv_head_budgets(ctx.h, _ptr(emb), C.byref(p), n_heads, float(R), int(t), _ptr(r), _ptr(b),
                                         _stream_ptr(stream)))
+
+
+def lkv_plan_offsets(ctx: Context, budgets, offsets, stream=None) -> int:
+    """budgets: host int32 [n_segments]; offsets: GPU int32 [n_segments + 1].  Returns the total kept."""
+    import numpy as np
+
+    b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
+    assert offsets.numel() >= b.size + 1
+    total = C.c_int64(0)
+    ctx._check(ctx.lib.lkv_plan_offsets(ctx.h, b.size, b.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(offsets),
+                                        C.byref(total), _stream_ptr(stream)))
+    return int(total.value)
+
+
+def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int, scorer: dict, budgets, offsets,
+                    scores: Sequence, idx, kp, vp, stream=None) -> None:
+    """layer: a Cache built from per-sequence tensors [1, H, T_s, 128]; budgets: host int32
+    [n_seq * n_layers * H]; scores: per-sequence GPU fp32 [H, T_s] scratch."""
+    import numpy as np
+
+    b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
+    assert b.size == layer.n_seq * n_layers * layer.H
+    sc = _scorer_struct(scorer)
+    sp = (C.c_void_p * layer.n_seq)(*[s.data_ptr() for s in scores])
+    ctx._check(ctx.lib.lkv_evict_layer(ctx.h, C.byref(layer.c), layer_index, n_layers, C.byref(sc),
+                                       b.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(offsets), sp, _ptr(idx), _ptr(kp),
+                                       _ptr(vp), _stream_ptr(stream)))
