@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
                     help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-layerwise", action="store_true", help="skip the layer-by-layer eviction measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (a kernel of known "
                          "traffic for scaling hardware byte counters under rocprofv3 --pmc)")
@@ -66,14 +67,8 @@ def main():
     torch.cuda.set_device(dev)
     w = W.CONFIGS[args.config]
     ctx = lkv.Context(0)
+    layerwise_result = None
 
-    # ---- inputs, resident in HBM before the timed region --------------------------------
-    Ts = [int(t) for t in W.seq_lengths(w)]
-    Ks, Vs = [], []
-    for s, T in enumerate(Ts):
-        k, v = W.device_kv(w, T, s, dev)
-        Ks.append(k); Vs.append(v)
-    cache = lkv.Cache(Ks, Vs, w.Hq)
     sc_host = W.draw_scorer(w)
 
     def to_dev(a, bf16=False):
@@ -86,6 +81,18 @@ def main():
     scorer = {"kind": sc_host["kind"], "act": sc_host["act"], "hidden": sc_host["hidden"],
               "per_head": sc_host["per_head"], "w1": to_dev(sc_host["w1"], True), "b1": to_dev(sc_host["b1"]),
               "w2": to_dev(sc_host["w2"]), "b2": to_dev(sc_host["b2"])}
+    # ---- layer-by-layer mode first, while the whole cache does not exist yet ---------------
+    if not args.no_layerwise:
+        layerwise_result = layerwise(ctx, lkv, W, w, scorer, dev)
+        torch.cuda.empty_cache()
+
+    # ---- inputs, resident in HBM before the timed region --------------------------------
+    Ts = [int(t) for t in W.seq_lengths(w)]
+    Ks, Vs = [], []
+    for s, T in enumerate(Ts):
+        k, v = W.device_kv(w, T, s, dev)
+        Ks.append(k); Vs.append(v)
+    cache = lkv.Cache(Ks, Vs, w.Hq)
     # LKV-H (Sec. 3.3): ratios are computed once from static parameters; timed apart from the step
     emb_h, mlp_h = W.draw_head_predictor(w)
     emb_d = to_dev(emb_h)
@@ -192,9 +199,84 @@ def main():
     result["config"]["budgets"] = "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe"
     result["lkv_h"] = {"n_heads": w.L * w.H, "us_per_call": lkv_h_us, "dtype": "f64",
                        "note": "head scores + Soft-TopK + floor(r t); computed once, outside the step"}
+    if layerwise_result is not None:
+        result["layerwise"] = layerwise_result
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
     print(json.dumps(result))
+
+
+def layerwise(ctx, lkv, W, w, scorer, dev, reps=3):
+    """Layer-by-layer eviction during prefill (Sec. 1): a stand-in producer fills one layer's K/V on
+    one stream (it takes the place of the prefill compute), the eviction of the previous layer runs on
+    another; two layer buffers are alive at any time instead of L.  Reports time and peak memory."""
+    import torch
+
+    Ts = [int(t) for t in W.seq_lengths(w)]
+    if len(Ts) > 32:
+        return None
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    budgets = np.concatenate([W.draw_budgets(w, T, s).reshape(-1) for s, T in enumerate(Ts)]).astype(np.int32)
+    n_seg = budgets.size
+    total = int(budgets.sum())
+    ring = [([torch.empty((1, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts],
+             [torch.empty((1, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts]) for _ in range(2)]
+    views = [lkv.Cache(k, v, w.Hq) for k, v in ring]
+    scratch = [torch.empty((w.H, T), dtype=torch.float32, device=dev) for T in Ts]
+    idx = torch.empty((total,), dtype=torch.int32, device=dev)
+    offsets = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
+    kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
+    vp = torch.empty_like(kp)
+    s_fill, s_evict = torch.cuda.Stream(), torch.cuda.Stream()
+
+    def fill(slot):
+        for t in ring[slot][0] + ring[slot][1]:
+            t.normal_()
+
+    def run(evict=True, produce=True):
+        filled = [torch.cuda.Event() for _ in range(w.L)]
+        evicted = [torch.cuda.Event(enable_timing=True) for _ in range(w.L)]
+        started = [torch.cuda.Event(enable_timing=True) for _ in range(w.L)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if evict:
+            lkv.lkv_plan_offsets(ctx, budgets, offsets, stream=s_evict)
+        for l in range(w.L):
+            slot = l & 1
+            if produce:
+                with torch.cuda.stream(s_fill):
+                    if evict and l >= 2:
+                        s_fill.wait_event(evicted[l - 2])     # the buffer's previous layer has left it
+                    fill(slot)
+                    filled[l].record(s_fill)
+            if evict:
+                if produce:
+                    s_evict.wait_event(filled[l])
+                started[l].record(s_evict)
+                lkv.lkv_evict_layer(ctx, views[slot], l, w.L, scorer, budgets, offsets, scratch, idx, kp, vp,
+                                    stream=s_evict)
+                evicted[l].record(s_evict)
+        torch.cuda.synchronize()
+        wall = (time.perf_counter() - t0) * 1e3
+        per_layer = float(np.mean([started[l].elapsed_time(evicted[l]) for l in range(w.L)])) if evict else 0.0
+        return wall, per_layer
+
+    run()                                   # warm-up
+    both = min(run()[0] for _ in range(reps))
+    produce_only = min(run(evict=False)[0] for _ in range(reps))
+    fill(0); fill(1)
+    evict_only, per_layer = min(run(produce=False) for _ in range(reps))
+    peak = torch.cuda.max_memory_allocated() - base
+    layer_bytes = sum(2 * w.H * T * w.d * 2 for T in Ts)
+    N = sum(w.L * w.H * T for T in Ts)
+    return {"ms_producer_and_eviction": both, "ms_producer_alone": produce_only, "ms_eviction_alone": evict_only,
+            "ms_per_layer_eviction": per_layer,
+            "evict_GBps_eviction_alone": (N * 520 + total * 1032) / (evict_only * 1e6),
+            "peak_bytes": int(peak), "peak_bytes_whole_cache_path": int(w.L * layer_bytes + total * 1032 + N * 4),
+            "layer_buffers_alive": 2,
+            "note": "producer = in-place normal_() of one layer's K/V on a second stream, standing in for prefill"}
 
 
 def cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, cap_s):
