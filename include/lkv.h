@@ -180,6 +180,52 @@ lkv_status lkv_evict_layer(lkv_ctx *ctx, const lkv_cache *layer, int32_t layer_i
                            const lkv_scorer *scorer, const int32_t *budgets, const int32_t *offsets,
                            float *const *scores, int32_t *idx, void *kp, void *vp, void *stream);
 
+/* ---- Decode-time growth of the packed cache -----------------------------------------------
+ * The paper evicts during prefill (Sec. 1), lets step t attend every cached token up to t (Eq. 1)
+ * and sets the budget of a head at step t to floor(r t) (Sec. 3.3), but does not say how the
+ * compacted cache follows t.  The layout used here: every segment s owns the rows
+ * cap_offsets[s] .. cap_offsets[s+1] of kp / vp / up, of which the first lengths[s] are in use;
+ * `slack` spare rows per segment take the tokens generated after prefill, one per decode step.
+ * When the slack is used up the caller re-evicts (lkv_reevict) with the budgets of the new
+ * length.  `up` holds the LKV-T score of every row in use. */
+
+/* lkv_compact into a cache with `slack` spare rows behind every segment.
+ * Row j of segment s goes to row offsets[s] + slack * s + j; the score of that token goes to up.
+ * Also writes cap_offsets[s] = offsets[s] + slack * s (s = 0..n_segments) and lengths[s] = budget.
+ * scores      : HOST [n_seq] of DEVICE fp32 [L, H, T_s], the scores the selection used
+ * idx, offsets: DEVICE, as written by lkv_select
+ * kp, vp      : DEVICE bf16 [total_kept + n_segments * slack, d]
+ * up          : DEVICE fp32 [total_kept + n_segments * slack]
+ * cap_offsets : DEVICE int32 [n_segments + 1];  lengths : DEVICE int32 [n_segments]
+ * Spare rows are left as they are (never read). */
+lkv_status lkv_compact_grow(lkv_ctx *ctx, const lkv_cache *cache, const float *const *scores,
+                            const int32_t *idx, const int32_t *offsets, int64_t total_kept, int32_t slack,
+                            void *kp, void *vp, float *up, int32_t *cap_offsets, int32_t *lengths,
+                            void *stream);
+
+/* One generated token: its key, value and LKV-T score (Sec. 3.4, computed here from the token's
+ * own key and value with the given scorer) are written to the first spare row of every segment
+ * and lengths[s] grows by one.  A segment without a spare row is left untouched and *overflow is
+ * set to 1 (the caller keeps count of the appends since the last eviction and re-evicts in time;
+ * the flag is the safety net).
+ * k_new, v_new : DEVICE bf16 [n_seq, L, H, d]
+ * scorer       : as for lkv_score; the MLP hidden width may be any value in [1, 128] here
+ * overflow     : DEVICE int32 [1] or NULL; never cleared by this call */
+lkv_status lkv_append(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
+                      const lkv_scorer *scorer, const void *k_new, const void *v_new, void *kp, void *vp,
+                      float *up, const int32_t *cap_offsets, int32_t *lengths, int32_t *overflow,
+                      void *stream);
+
+/* lkv_decode_attn over the rows in use of a cache with slack: segment s is rows
+ * cap_offsets[s] .. cap_offsets[s] + lengths[s].  total_rows = cap_offsets[n_segments]; the
+ * workspace is sized by lkv_decode_workspace_bytes(n_segments, total_rows, ...).  Everything
+ * else as for lkv_decode_attn. */
+lkv_status lkv_decode_attn_grown(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads,
+                                 int32_t n_q_heads, int32_t head_dim, const void *q, const void *kp,
+                                 const void *vp, const int32_t *cap_offsets, const int32_t *lengths,
+                                 int64_t total_rows, float scale, float *out, float *lse,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
 
 /* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):

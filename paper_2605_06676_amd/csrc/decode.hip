@@ -75,8 +75,9 @@ __device__ __forceinline__ s16x4_t lds_read_tr16(const unsigned char* p) {
 
 __global__ void __launch_bounds__(kDecThreads, 2)
 decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ kp,
-                      const uint4* __restrict__ vp, const int32_t* __restrict__ offsets, int n_segments,
-                      int64_t total_kept, int chunk_rows, int G, float scale, float* __restrict__ out,
+                      const uint4* __restrict__ vp, const int32_t* __restrict__ offsets,
+                      const int32_t* __restrict__ lengths /* rows in use per segment, or null: all of them */,
+                      int n_segments, int64_t total_kept, int chunk_rows, int G, float scale, float* __restrict__ out,
                       float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_m,
                       float* __restrict__ ws_l) {
   extern __shared__ __align__(16) unsigned char smem[];
@@ -98,8 +99,10 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
 
 #pragma unroll 1
   for (int s = s_first; s < n_segments; ++s) {
-    const int64_t seg_lo = offsets[s], seg_hi = offsets[s + 1];
+    const int64_t seg_lo = offsets[s];
     if (seg_lo >= p1) break;
+    // rows behind the ones in use (spare rows for later tokens) are never read
+    const int64_t seg_hi = lengths != nullptr ? seg_lo + lengths[s] : (int64_t)offsets[s + 1];
     const int64_t a = max(p0, seg_lo), b = min(p1, seg_hi);
     if (b <= a) continue;   // empty segment (the merge kernel zeroes its output)
     const int n_rows = (int)(b - a);
@@ -262,14 +265,16 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
 // the partials of up to eight pieces are loaded together and folded in with a running maximum:
 // the chain is the offsets load plus one round per eight pieces.
 __global__ void __launch_bounds__(kDecThreads)
-decode_merge_kernel(const int32_t* __restrict__ offsets, int G, int blocks_per_segment, int chunk_rows,
+decode_merge_kernel(const int32_t* __restrict__ offsets, const int32_t* __restrict__ lengths, int G,
+                    int blocks_per_segment, int chunk_rows,
                     const float* __restrict__ ws_acc, const float* __restrict__ ws_m,
                     const float* __restrict__ ws_l, float* __restrict__ out, float* __restrict__ lse) {
   const int s = blockIdx.x / blocks_per_segment;
   const int o = (blockIdx.x - s * blocks_per_segment) * kDecThreads + threadIdx.x;
   if (o >= G * kHeadDim) return;
   const int h = o / kHeadDim, ch = o - h * kHeadDim;
-  const int64_t a = offsets[s], b = offsets[s + 1];
+  const int64_t a = offsets[s];
+  const int64_t b = lengths != nullptr ? a + lengths[s] : (int64_t)offsets[s + 1];
   const size_t row = (size_t)s * G + h;
   if (b <= a) {   // empty segment: zero output, lse = -inf
     out[row * kHeadDim + ch] = 0.f;
@@ -334,7 +339,7 @@ hipError_t decode_prepare() {
 }
 
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
-                         int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
+                         const int32_t* lengths, int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
                          hipStream_t stream) {
   if (G < 1 || G > kDecMaxGroup) return hipErrorInvalidValue;
   const size_t slots = decode_slots(n_segments, total_kept);
@@ -346,12 +351,12 @@ hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, c
   if (chunks > 0) {
     hipLaunchKernelGGL(decode_partial_kernel, dim3(chunks), dim3(kDecThreads), kDecWaves * kDecWaveLds, stream,
                        reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint4*>(kp),
-                       reinterpret_cast<const uint4*>(vp), offsets, n_segments, total_kept, chunk_rows, G, scale,
+                       reinterpret_cast<const uint4*>(vp), offsets, lengths, n_segments, total_kept, chunk_rows, G, scale,
                        out, lse, ws_acc, ws_m, ws_l);
   }
   const int blocks_per_segment = (G * kHeadDim + kDecThreads - 1) / kDecThreads;
   hipLaunchKernelGGL(decode_merge_kernel, dim3(n_segments * blocks_per_segment), dim3(kDecThreads), 0, stream,
-                     offsets, G, blocks_per_segment, chunk_rows, ws_acc, ws_m, ws_l, out, lse);
+                     offsets, lengths, G, blocks_per_segment, chunk_rows, ws_acc, ws_m, ws_l, out, lse);
   return hipGetLastError();
 }
 

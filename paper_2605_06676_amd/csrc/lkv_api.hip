@@ -318,7 +318,7 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
     return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
   if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
     return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace is not 256-byte aligned");
-  if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, (int)n_seg, total_kept, scale, out, lse,
+  if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, nullptr, (int)n_seg, total_kept, scale, out, lse,
                                         static_cast<float*>(workspace), as_stream(stream)))
     return hip_fail(ctx, e, "lkv_decode_attn launch");
   return LKV_OK;
@@ -440,6 +440,108 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
     lkv::launch_compact(one, idx, offsets, (int)n_seg, heads_all, i, layer_index * H, H, row_lo[i], row_hi[i], kp, vp, st);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer compact launch");
   }
+  return LKV_OK;
+}
+
+lkv_status lkv_compact_grow(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* idx,
+                            const int32_t* offsets, int64_t total_kept, int32_t slack, void* kp, void* vp, float* up,
+                            int32_t* cap_offsets, int32_t* lengths, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (scores == nullptr || offsets == nullptr || cap_offsets == nullptr || lengths == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "scores, offsets, cap_offsets or lengths is NULL");
+  if (slack < 0) return fail(ctx, LKV_ERR_INVALID_ARG, "slack = %d must be >= 0", slack);
+  const int heads = cache->n_layers * cache->n_kv_heads;
+  const int64_t n_seg = (int64_t)heads * cache->n_seq;
+  if (total_kept < 0 || total_kept + n_seg * slack >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "total_kept + n_segments * slack = %lld is outside [0, 2^31)",
+                (long long)(total_kept + n_seg * slack));
+  if (total_kept > 0 && (idx == nullptr || kp == nullptr || vp == nullptr || up == nullptr))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "idx, kp, vp or up is NULL");
+  if (!aligned16(kp) || !aligned16(vp)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is not 16-byte aligned");
+  for (int s = 0; s < cache->n_seq; ++s)
+    if (scores[s] == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL", s);
+  hipStream_t st = as_stream(stream);
+  lkv::launch_grown_layout(offsets, (int)n_seg, slack, cap_offsets, lengths, st);
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_compact_grow layout launch");
+  for (int s0 = 0; s0 < cache->n_seq; s0 += lkv::kMaxSeqPerLaunch) {
+    lkv::SeqTable tab;
+    memset(&tab, 0, sizeof(tab));
+    const int n = cache->n_seq - s0 < lkv::kMaxSeqPerLaunch ? cache->n_seq - s0 : lkv::kMaxSeqPerLaunch;
+    for (int i = 0; i < n; ++i) {
+      tab.k[i] = static_cast<const uint16_t*>(cache->k[s0 + i]);
+      tab.v[i] = static_cast<const uint16_t*>(cache->v[s0 + i]);
+      tab.scores[i] = const_cast<float*>(scores[s0 + i]);
+      tab.T[i] = cache->seq_len[s0 + i];
+    }
+    tab.n = n;
+    lkv::launch_compact_grow(tab, idx, offsets, (int)n_seg, heads, s0, total_kept, slack, kp, vp, up, st);
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_compact_grow launch");
+  }
+  return LKV_OK;
+}
+
+lkv_status lkv_append(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads, int32_t head_dim,
+                      const lkv_scorer* scorer, const void* k_new, const void* v_new, void* kp, void* vp, float* up,
+                      const int32_t* cap_offsets, int32_t* lengths, int32_t* overflow, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (n_seq < 1 || n_layers < 1 || n_kv_heads < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers and n_kv_heads must be >= 1");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  const int64_t n_seg = (int64_t)n_seq * n_layers * n_kv_heads;
+  if (n_seg > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  if (scorer == nullptr || k_new == nullptr || v_new == nullptr || kp == nullptr || vp == nullptr || up == nullptr ||
+      cap_offsets == nullptr || lengths == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "a required pointer is NULL");
+  if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(kp) || !aligned16(vp))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "k_new, v_new, kp or vp is not 16-byte aligned");
+  if (scorer->kind != LKV_SCORER_LINEAR && scorer->kind != LKV_SCORER_MLP)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", scorer->kind);
+  if (scorer->w1 == nullptr || scorer->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
+  if (!aligned16(scorer->w1)) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 is not 16-byte aligned");
+  if (scorer->per_head != 0 && scorer->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
+  if (scorer->kind == LKV_SCORER_MLP) {
+    if (scorer->act != LKV_ACT_SILU && scorer->act != LKV_ACT_GELU_ERF)
+      return fail(ctx, LKV_ERR_INVALID_ARG, "unknown activation %d", scorer->act);
+    if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
+    if (scorer->hidden < 1 || scorer->hidden > 128)
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must lie in [1, 128]", scorer->hidden);
+  }
+  lkv::launch_append((int)n_seg, n_layers * n_kv_heads, n_kv_heads, scorer->kind == LKV_SCORER_LINEAR ? 0 : 1,
+                     scorer->act == LKV_ACT_SILU ? 0 : 1, scorer->hidden, scorer->per_head,
+                     static_cast<const uint16_t*>(scorer->w1), scorer->b1, scorer->w2, scorer->b2, k_new, v_new, kp, vp,
+                     up, cap_offsets, lengths, overflow, as_stream(stream));
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_append launch");
+  return LKV_OK;
+}
+
+lkv_status lkv_decode_attn_grown(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads,
+                                 int32_t n_q_heads, int32_t head_dim, const void* q, const void* kp, const void* vp,
+                                 const int32_t* cap_offsets, const int32_t* lengths, int64_t total_rows, float scale,
+                                 float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (n_seq < 1 || n_layers < 1 || n_kv_heads < 1 || n_q_heads < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers, n_kv_heads and n_q_heads must be >= 1");
+  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  const int G = n_q_heads / n_kv_heads;
+  if (G > lkv::kDecodeMaxGroup) return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", G, lkv::kDecodeMaxGroup);
+  const int64_t n_seg = (int64_t)n_seq * n_layers * n_kv_heads;
+  if (n_seg > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  if (total_rows < 0 || total_rows >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "total_rows = %lld is outside [0, 2^31)", (long long)total_rows);
+  if (q == nullptr || cap_offsets == nullptr || lengths == nullptr || out == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, cap_offsets, lengths or out is NULL");
+  if (total_rows > 0 && (kp == nullptr || vp == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is NULL");
+  if (!aligned16(q) || !aligned16(kp) || !aligned16(vp) || !aligned16(out))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, kp, vp or out is not 16-byte aligned");
+  const size_t need = lkv::decode_workspace_bytes((int)n_seg, total_rows, G);
+  if (workspace == nullptr || workspace_bytes < need)
+    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace is not 256-byte aligned");
+  if (hipError_t e = lkv::launch_decode(G, q, kp, vp, cap_offsets, lengths, (int)n_seg, total_rows, scale, out, lse,
+                                        static_cast<float*>(workspace), as_stream(stream)))
+    return hip_fail(ctx, e, "lkv_decode_attn_grown launch");
   return LKV_OK;
 }
 

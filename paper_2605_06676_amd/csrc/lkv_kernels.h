@@ -28,12 +28,27 @@ void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offs
                     int heads_per_seq, int seq_lo, int head_lo, int n_heads_view, int64_t row_lo, int64_t row_hi,
                     void* kp, void* vp, hipStream_t stream);
 
+void launch_compact_grow(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
+                         int heads_per_seq, int seq_lo, int64_t total_kept, int slack, void* kp, void* vp, float* up,
+                         hipStream_t stream);
+void launch_compact_regrow(const int32_t* idx, const int32_t* offsets, int n_segments, int64_t total_kept, int slack,
+                           const void* kp_old, const void* vp_old, const float* up_old, const int32_t* cap_old,
+                           const int32_t* len_old, void* kp, void* vp, float* up, hipStream_t stream);
+void launch_grown_layout(const int32_t* offsets, int n_segments, int slack, int32_t* cap, int32_t* len,
+                         hipStream_t stream);
+
+// append.hip
+void launch_append(int n_segments, int heads_per_seq, int n_kv_heads, int scorer_kind, int act, int hidden,
+                   int per_head, const uint16_t* w1, const float* b1, const float* w2, const float* b2,
+                   const void* k_new, const void* v_new, void* kp, void* vp, float* up, const int32_t* cap,
+                   int32_t* len, int32_t* overflow, hipStream_t stream);
+
 // decode.hip
 constexpr int kDecodeMaxGroup = 16;
 hipError_t decode_prepare();
 size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G);
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
-                         int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
+                         const int32_t* lengths, int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
                          hipStream_t stream);
 
 // lkv_h.hip

@@ -17,6 +17,7 @@
 //    with w2 are per-lane work, finished by two cross-lane adds.
 // The next two 16-token tiles are prefetched into registers while the current
 // one is multiplied; b1 and w2 are read from LDS.
+#include "lkv_act.h"
 #include "lkv_common.h"
 
 namespace lkv {
@@ -30,37 +31,6 @@ constexpr int kMlpTokTile = 16;                       // tokens per MFMA N tile
 constexpr int kMlpRowStride = 2 * 256 + 16;           // bytes per staged [k ; v] row in LDS
 constexpr int kMlpWaveLds = kMlpTokTile * kMlpRowStride;
 constexpr int kMlpKSteps = 8;                         // 256 features / 32 per MFMA
-
-constexpr int kActSilu = 0;
-constexpr int kActGelu = 1;
-
-// Exact-form GELU, 0.5 z (1 + erf(z / sqrt 2)), branch free.  erf uses the five-term rational
-// approximation 7.1.26 of Abramowitz & Stegun, erf(x) = 1 - (a1 t + ... + a5 t^5) exp(-x^2),
-// t = 1 / (1 + p x) for x >= 0, absolute error below 1.5e-7 (plus fp32 rounding).  Written as
-// max(z, 0) - |z|/2 * poly(t) * exp(-z^2/2), which has no cancellation for negative z.  The
-// library erff costs several times more issue slots (and branches), which made the kernel
-// VALU-bound instead of HBM-bound.
-__device__ __forceinline__ float gelu_erf(float z) {
-  const float az = fabsf(z);
-  const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, az, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
-  p *= t;
-  const float e = __builtin_amdgcn_exp2f((z * z) * (-0.5f * 1.4426950408889634f));   // exp(-z^2 / 2)
-  return fmaf(-0.5f * az, p * e, fmaxf(z, 0.f));
-}
-
-template <int kAct>
-__device__ __forceinline__ float activation(float z) {
-  if (kAct == kActSilu) {
-    // z * sigmoid(z); exp2 overflow for very negative z gives rcp(inf) = 0
-    return z * __builtin_amdgcn_rcpf(1.f + __builtin_amdgcn_exp2f(-1.4426950408889634f * z));
-  } else {
-    return gelu_erf(z);
-  }
-}
 
 __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& p) {
   return __builtin_bit_cast(bf16x8_t, p);

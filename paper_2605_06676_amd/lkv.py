@@ -21,7 +21,8 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
-           "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer")
+           "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
+           "lkv_append", "lkv_decode_attn_grown")
 
 
 class LkvError(RuntimeError):
@@ -86,6 +87,18 @@ def load_library() -> C.CDLL:
                                     C.POINTER(C.c_int32), C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
                                     C.c_void_p, C.c_void_p]
     lib.lkv_evict_layer.restype = C.c_int
+    lib.lkv_compact_grow.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
+                                     C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p]
+    lib.lkv_compact_grow.restype = C.c_int
+    lib.lkv_append.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(_Scorer), C.c_void_p,
+                               C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                               C.c_void_p]
+    lib.lkv_append.restype = C.c_int
+    lib.lkv_decode_attn_grown.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
+                                          C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lkv_decode_attn_grown.restype = C.c_int
     lib.lkv_soft_topk_max_n.argtypes = [C.c_int32]
     lib.lkv_soft_topk_max_n.restype = C.c_int32
     lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
@@ -260,3 +273,29 @@ def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int,
     ctx._check(ctx.lib.lkv_evict_layer(ctx.h, C.byref(layer.c), layer_index, n_layers, C.byref(sc),
                                        b.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(offsets), sp, _ptr(idx), _ptr(kp),
                                        _ptr(vp), _stream_ptr(stream)))
+
+
+def lkv_compact_grow(ctx: Context, cache: Cache, scores: Sequence, idx, offsets, total_kept: int, slack: int, kp, vp,
+                     up, cap_offsets, lengths, stream=None) -> None:
+    """kp, vp: bf16 [total_kept + n_segments * slack, 128]; up: fp32 of as many rows; cap_offsets int32
+    [n_segments + 1] and lengths int32 [n_segments] are written."""
+    sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    ctx._check(ctx.lib.lkv_compact_grow(ctx.h, C.byref(cache.c), sp, _ptr(idx), _ptr(offsets), int(total_kept),
+                                        int(slack), _ptr(kp), _ptr(vp), _ptr(up), _ptr(cap_offsets), _ptr(lengths),
+                                        _stream_ptr(stream)))
+
+
+def lkv_append(ctx: Context, n_seq: int, L: int, H: int, d: int, scorer: dict, k_new, v_new, kp, vp, up, cap_offsets,
+               lengths, overflow=None, stream=None) -> None:
+    """k_new, v_new: bf16 [n_seq, L, H, 128]; overflow: int32 [1] GPU tensor or None."""
+    sc = _scorer_struct(scorer)
+    ctx._check(ctx.lib.lkv_append(ctx.h, n_seq, L, H, d, C.byref(sc), _ptr(k_new), _ptr(v_new), _ptr(kp), _ptr(vp),
+                                  _ptr(up), _ptr(cap_offsets), _ptr(lengths), _ptr(overflow), _stream_ptr(stream)))
+
+
+def lkv_decode_attn_grown(ctx: Context, n_seq: int, L: int, H: int, Hq: int, d: int, q, kp, vp, cap_offsets, lengths,
+                          total_rows: int, scale: float, out, lse, workspace, stream=None) -> None:
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ctx._check(ctx.lib.lkv_decode_attn_grown(ctx.h, n_seq, L, H, Hq, d, _ptr(q), _ptr(kp), _ptr(vp), _ptr(cap_offsets),
+                                             _ptr(lengths), int(total_rows), float(scale), _ptr(out), _ptr(lse),
+                                             _ptr(workspace), ws_bytes, _stream_ptr(stream)))
