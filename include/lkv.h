@@ -226,6 +226,27 @@ lkv_status lkv_decode_attn_grown(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, 
                                  int64_t total_rows, float scale, float *out, float *lse,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* Re-eviction of a cache with slack (the budgets floor(r t') of a longer context t', Sec. 3.3):
+ * every segment keeps the new_budgets[s] rows it holds with the largest stored scores (the hard
+ * top-k and tie rule of lkv_select, position = row inside the segment, which is time order) and
+ * the result is written, in that order, to a new cache with fresh slack.  Tokens evicted earlier
+ * do not return.
+ * kp, vp, up, cap_offsets, lengths : DEVICE, the cache to shrink (not modified)
+ * lengths_host  : HOST int32 [n_segments], the caller's count of the rows in use (budget at the
+ *                 last eviction + appends since); must equal the device array
+ * new_budgets   : HOST int32 [n_segments], 0 <= new_budgets[s] <= lengths_host[s]
+ * idx           : DEVICE int32 [sum of new_budgets]: scratch, receives the kept row positions
+ * offsets       : DEVICE int32 [n_segments + 1]: scratch, receives the prefix sums of new_budgets
+ * kp_new, vp_new: DEVICE bf16 [sum of new_budgets + n_segments * slack, d]; up_new fp32 of as many rows
+ * cap_offsets_new, lengths_new : DEVICE int32 [n_segments + 1] / [n_segments]
+ * total_kept    : HOST out (sum of new_budgets), may be NULL
+ * The new buffers must not overlap the old ones. */
+lkv_status lkv_reevict(lkv_ctx *ctx, int64_t n_segments, int32_t head_dim, const void *kp, const void *vp,
+                       const float *up, const int32_t *cap_offsets, const int32_t *lengths,
+                       const int32_t *lengths_host, const int32_t *new_budgets, int32_t slack,
+                       int32_t *idx, int32_t *offsets, void *kp_new, void *vp_new, float *up_new,
+                       int32_t *cap_offsets_new, int32_t *lengths_new, int64_t *total_kept, void *stream);
+
 /* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
 
 /* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):

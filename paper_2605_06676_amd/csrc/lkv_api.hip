@@ -545,6 +545,56 @@ lkv_status lkv_decode_attn_grown(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, 
   return LKV_OK;
 }
 
+lkv_status lkv_reevict(lkv_ctx* ctx, int64_t n_segments, int32_t head_dim, const void* kp, const void* vp,
+                       const float* up, const int32_t* cap_offsets, const int32_t* lengths,
+                       const int32_t* lengths_host, const int32_t* new_budgets, int32_t slack, int32_t* idx,
+                       int32_t* offsets, void* kp_new, void* vp_new, float* up_new, int32_t* cap_offsets_new,
+                       int32_t* lengths_new, int64_t* total_kept, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  if (n_segments < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n_segments = %lld must be >= 1", (long long)n_segments);
+  if (n_segments > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  if (cap_offsets == nullptr || lengths == nullptr || lengths_host == nullptr || new_budgets == nullptr ||
+      offsets == nullptr || cap_offsets_new == nullptr || lengths_new == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "a required pointer is NULL");
+  if (slack < 0) return fail(ctx, LKV_ERR_INVALID_ARG, "slack = %d must be >= 0", slack);
+  int64_t total = 0;
+  int max_len = 1;
+  for (int64_t i = 0; i < n_segments; ++i) {
+    if (lengths_host[i] < 0) return fail(ctx, LKV_ERR_INVALID_ARG, "length %d of segment %lld is negative", lengths_host[i], (long long)i);
+    if (new_budgets[i] < 0 || new_budgets[i] > lengths_host[i])
+      return fail(ctx, LKV_ERR_INVALID_ARG, "new budget %d of segment %lld is outside [0, %d]", new_budgets[i],
+                  (long long)i, lengths_host[i]);
+    total += new_budgets[i];
+    if (lengths_host[i] > max_len) max_len = lengths_host[i];
+  }
+  if (total + n_segments * slack >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "new cache of %lld rows >= 2^31", (long long)(total + n_segments * slack));
+  if (total > 0 && (kp == nullptr || vp == nullptr || up == nullptr || idx == nullptr || kp_new == nullptr ||
+                    vp_new == nullptr || up_new == nullptr))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "a cache, score or index buffer is NULL");
+  if (!aligned16(kp) || !aligned16(vp) || !aligned16(kp_new) || !aligned16(vp_new))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "kp, vp, kp_new or vp_new is not 16-byte aligned");
+  // tight offsets of the new budgets, the layout the selection writes its indices in
+  if (lkv_status st = lkv_plan_offsets(ctx, n_segments, new_budgets, offsets, nullptr, stream)) return st;
+  hipStream_t st = as_stream(stream);
+  lkv::SeqTable tab;
+  memset(&tab, 0, sizeof(tab));
+  tab.T[0] = max_len;          // upper bound of every segment's length: sizes the LDS region
+  tab.first[0] = 0;
+  tab.first[1] = (int32_t)n_segments;
+  tab.n = 1;
+  lkv::launch_select(tab, nullptr, (int)n_segments, offsets, idx, 0, 0, st, up, cap_offsets, lengths);
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_reevict select launch");
+  lkv::launch_compact_regrow(idx, offsets, (int)n_segments, total, slack, kp, vp, up, cap_offsets, lengths, kp_new, vp_new,
+                             up_new, st);
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_reevict compact launch");
+  lkv::launch_grown_layout(offsets, (int)n_segments, slack, cap_offsets_new, lengths_new, st);
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_reevict layout launch");
+  if (total_kept != nullptr) *total_kept = total;
+  return LKV_OK;
+}
+
 int32_t lkv_soft_topk_max_n(int32_t x_is_f64) { return lkv::soft_topk_max_n(x_is_f64 != 0); }
 
 lkv_status lkv_soft_topk(lkv_ctx* ctx, const void* x, int32_t x_is_f64, int32_t n, double k, double tau, double* y,

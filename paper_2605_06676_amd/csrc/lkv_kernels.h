@@ -21,7 +21,9 @@ int score_mlp_rows_per_block(int T, int heads);
 hipError_t select_prepare();
 int select_inline_capacity();
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
-                   int32_t* idx, int seg_base, int seg_stride, hipStream_t stream);
+                   int32_t* idx, int seg_base, int seg_stride, hipStream_t stream,
+                   const float* ragged_scores = nullptr, const int32_t* ragged_start = nullptr,
+                   const int32_t* ragged_len = nullptr);
 
 // compact.hip
 void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,

@@ -280,9 +280,17 @@ __device__ __forceinline__ void emit_from_bitmaps(SelShared& sh, int T, uint32_t
 // Up to kSelInlineOffsets segment offsets travel in the kernel arguments instead of through a
 // host-to-device copy (which costs an extra dependent transfer before the kernel can start);
 // the blocks then also publish them to the device array that the later calls read.
+// Segments that are not heads of a [L, H, T] score tensor but ragged pieces of one flat array
+// (re-eviction of a packed cache): segment s has len[s] scores starting at flat[start[s]].
+struct SelRagged {
+  const float* flat;      // null: the launch table describes the scores
+  const int32_t* start;
+  const int32_t* len;
+};
+
 template <bool kInline>
 __global__ void __launch_bounds__(kSelThreads)
-select_kernel(SeqTable tab, InlineOffsets inl, int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
+select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
               int seg_base, int seg_stride /* global segment = seg_base + sequence * seg_stride + head */,
               int cached_limit /* heads of at most this many tokens use the LDS key cache */,
               int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */,
@@ -295,9 +303,10 @@ select_kernel(SeqTable tab, InlineOffsets inl, int32_t* __restrict__ offsets, in
   const int local_seg = blockIdx.x;
   const int seq = seq_of_unit(tab, local_seg);
   const int lh = local_seg - tab.first[seq];
-  const int T = tab.T[seq];
-  const float* u = tab.scores[seq] + (size_t)lh * (size_t)T;
   const int seg = seg_base + seq * seg_stride + lh;
+  // a ragged segment can be no longer than the launch table says (the LDS region is sized by it)
+  const int T = ragged.flat != nullptr ? min(ragged.len[seg], tab.T[seq]) : tab.T[seq];
+  const float* u = ragged.flat != nullptr ? ragged.flat + ragged.start[seg] : tab.scores[seq] + (size_t)lh * (size_t)T;
   const int off = kInline ? inl.v[seg] : offsets[seg];
   const int budget = (kInline ? inl.v[seg + 1] : offsets[seg + 1]) - off;
   if (kInline && tid == 0) {
@@ -381,7 +390,8 @@ int select_inline_capacity() { return kSelInlineOffsets; }
 // (n_total_segments < kSelInlineOffsets) and the kernel writes the device array; null: the
 // device array has already been filled.
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
-                   int32_t* idx, int seg_base, int seg_stride, hipStream_t stream) {
+                   int32_t* idx, int seg_base, int seg_stride, hipStream_t stream, const float* ragged_scores,
+                   const int32_t* ragged_start, const int32_t* ragged_len) {
   const int segs = tab.first[tab.n];
   if (segs <= 0) return;
   // the LDS region is sized for the longest sequence of this launch that can use it
@@ -400,16 +410,17 @@ void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total
   size_t region = cached_limit > 0 ? (overlay ? cached_words * 4 : cached_words * 4 + kSelStageBytes) : 0;
   const size_t bitmap_stage_off = 2 * (size_t)((bitmap_limit + 31) / 32);
   if (bitmap_limit > 0 && bitmap_stage_off * 4 + kSelStageBytes > region) region = bitmap_stage_off * 4 + kSelStageBytes;
+  const SelRagged ragged = {ragged_scores, ragged_start, ragged_len};
   InlineOffsets inl;
   if (host_offsets != nullptr) {
     for (int i = 0; i <= n_total_segments; ++i) inl.v[i] = host_offsets[i];
     hipLaunchKernelGGL(select_kernel<true>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
-                       inl, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
+                       inl, ragged, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
                        (int)bitmap_stage_off);
   } else {
     inl.v[0] = 0;
     hipLaunchKernelGGL(select_kernel<false>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
-                       inl, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
+                       inl, ragged, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
                        (int)bitmap_stage_off);
   }
 }

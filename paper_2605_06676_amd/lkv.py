@@ -22,7 +22,7 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
-           "lkv_append", "lkv_decode_attn_grown")
+           "lkv_append", "lkv_decode_attn_grown", "lkv_reevict")
 
 
 class LkvError(RuntimeError):
@@ -99,6 +99,11 @@ def load_library() -> C.CDLL:
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float,
                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lkv_decode_attn_grown.restype = C.c_int
+    lib.lkv_reevict.argtypes = [C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int32, C.c_void_p,
+                                C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                C.POINTER(C.c_int64), C.c_void_p]
+    lib.lkv_reevict.restype = C.c_int
     lib.lkv_soft_topk_max_n.argtypes = [C.c_int32]
     lib.lkv_soft_topk_max_n.restype = C.c_int32
     lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
@@ -299,3 +304,19 @@ def lkv_decode_attn_grown(ctx: Context, n_seq: int, L: int, H: int, Hq: int, d: 
     ctx._check(ctx.lib.lkv_decode_attn_grown(ctx.h, n_seq, L, H, Hq, d, _ptr(q), _ptr(kp), _ptr(vp), _ptr(cap_offsets),
                                              _ptr(lengths), int(total_rows), float(scale), _ptr(out), _ptr(lse),
                                              _ptr(workspace), ws_bytes, _stream_ptr(stream)))
+
+
+def lkv_reevict(ctx: Context, d: int, kp, vp, up, cap_offsets, lengths, lengths_host, new_budgets, slack: int, idx,
+                offsets, kp_new, vp_new, up_new, cap_offsets_new, lengths_new, stream=None) -> int:
+    """Shrinks a cache with slack to new_budgets (host int32 [n_segments]) and returns the rows kept."""
+    import numpy as np
+
+    lh = np.ascontiguousarray(np.asarray(lengths_host, dtype=np.int32).reshape(-1))
+    nb = np.ascontiguousarray(np.asarray(new_budgets, dtype=np.int32).reshape(-1))
+    assert lh.size == nb.size
+    total = C.c_int64(0)
+    ctx._check(ctx.lib.lkv_reevict(ctx.h, lh.size, d, _ptr(kp), _ptr(vp), _ptr(up), _ptr(cap_offsets), _ptr(lengths),
+                                   lh.ctypes.data_as(C.POINTER(C.c_int32)), nb.ctypes.data_as(C.POINTER(C.c_int32)),
+                                   int(slack), _ptr(idx), _ptr(offsets), _ptr(kp_new), _ptr(vp_new), _ptr(up_new),
+                                   _ptr(cap_offsets_new), _ptr(lengths_new), C.byref(total), _stream_ptr(stream)))
+    return int(total.value)

@@ -103,6 +103,37 @@ class Grown:
             assert int(self.overflow.item()) == 1
         return any_full
 
+    def reevict(self, new_budgets, slack):
+        """new_budgets: int array [n_seg].  Swaps in the new cache on both sides."""
+        w = self.w
+        nb = np.asarray(new_budgets, dtype=np.int32).reshape(-1)
+        lengths_host = np.concatenate([o[4] for o in self.oracle]).astype(np.int32)
+        total = int(nb.sum())
+        rows = total + self.n_seg * slack
+        kp2 = torch.zeros((max(rows, 1), w.d), dtype=torch.bfloat16, device="cuda")
+        vp2 = torch.zeros_like(kp2)
+        up2 = torch.zeros((max(rows, 1),), dtype=torch.float32, device="cuda")
+        cap2 = torch.full((self.n_seg + 1,), -1, dtype=torch.int32, device="cuda")
+        len2 = torch.full((self.n_seg,), -1, dtype=torch.int32, device="cuda")
+        idx = torch.full((max(total, 1) + 64,), -7, dtype=torch.int32, device="cuda")      # 64 guard entries
+        off = torch.full((self.n_seg + 1,), -1, dtype=torch.int32, device="cuda")
+        kept = lkv.lkv_reevict(self.ctx, w.d, self.kp, self.vp, self.up, self.cap, self.len, lengths_host, nb, slack,
+                               idx, off, kp2, vp2, up2, cap2, len2)
+        torch.cuda.synchronize()
+        assert kept == total
+        assert torch.all(idx[total:] == -7), "the index scratch was written past its end"
+        idx_h = idx.cpu().numpy()[:total]
+        off_h = off.cpu().numpy()
+        self.kp, self.vp, self.up, self.cap, self.len, self.rows, self.slack = kp2, vp2, up2, cap2, len2, rows, slack
+        for s in range(len(self.Ts)):
+            Ko, Vo, uo, cap_o, len_o = self.oracle[s]
+            seg0 = s * self.heads
+            K2, V2, u2, c2, l2, pos = GR.reevict(Ko, Vo, uo, cap_o, len_o, nb[seg0:seg0 + self.heads], slack)
+            for j in range(self.heads):
+                a, b = off_h[seg0 + j], off_h[seg0 + j + 1]
+                assert np.array_equal(idx_h[a:b], pos[j]), f"seq {s} seg {j}: kept row positions"
+            self.oracle[s] = [K2, V2, u2, c2, l2]
+
     def decode_and_check(self, what=""):
         w = self.w
         out = torch.full((len(self.Ts), w.L, w.Hq, w.d), float("nan"), dtype=torch.float32, device="cuda")
@@ -183,6 +214,71 @@ def test_append_to_full_segments_sets_the_flag_and_writes_nothing(ctx):
     after = g.gpu_state()
     assert all(np.array_equal(a, b) for a, b in zip(before, after))
     g.assert_state_matches("after refused append")
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_reevict_then_keep_growing(ctx, seed):
+    w = W.scaled(W.CONFIGS[0], n_seq=2, L=2, H=3, Hq=6, b_min=4, scorer="mlp", hidden=32, act="silu", per_head=True)
+    g = Grown(ctx, w, [500, 333], seed, slack=6)
+    toks = _new_tokens(w, 2, 12, seed)
+    for kn, vn in toks[:6]:
+        g.append(kn, vn)
+    g.assert_state_matches("before re-eviction")
+    rng = np.random.default_rng(seed)
+    lengths = np.concatenate([o[4] for o in g.oracle])
+    # budgets of the longer context: anything from nothing to everything held
+    nb = np.array([int(rng.integers(0, n + 1)) for n in lengths])
+    nb[0] = lengths[0]          # one head keeps all it holds
+    nb[1] = 0                   # one head keeps nothing
+    g.reevict(nb, slack=6)
+    g.assert_state_matches("after re-eviction")
+    g.decode_and_check("after re-eviction")
+    for kn, vn in toks[6:]:
+        g.append(kn, vn)
+    g.assert_state_matches("grown again")
+    g.decode_and_check("grown again")
+    assert int(g.overflow.item()) == 0
+
+
+def test_reevict_with_the_paper_budget_rule(ctx):
+    # b = floor(r t): evict at T, generate n tokens, re-evict with the budgets of T + n (Sec. 3.3)
+    w = W.scaled(W.CONFIGS[0], L=4, H=2, Hq=4, b_min=4)
+    T, n_new = 2000, 50
+    g = Grown(ctx, w, [T], 7, slack=n_new)
+    r = g.B[0].reshape(-1) / float(T)
+    for kn, vn in _new_tokens(w, 1, n_new, 7):
+        g.append(kn, vn)
+    nb = np.floor(r * (T + n_new)).astype(np.int64)
+    assert np.all(nb <= g.oracle[0][4])
+    g.reevict(nb, slack=n_new)
+    g.assert_state_matches("floor(r t')")
+    g.decode_and_check("floor(r t')")
+
+
+def test_reevict_long_segments_take_the_uncached_selection(ctx):
+    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=2, b_min=16, R=0.9, alpha=50.0)
+    g = Grown(ctx, w, [45000], 5, slack=3)
+    for kn, vn in _new_tokens(w, 1, 3, 5):
+        g.append(kn, vn)
+    lengths = g.oracle[0][4]
+    assert lengths.max() > 34304
+    g.reevict((lengths * 0.6).astype(np.int64), slack=2)
+    g.assert_state_matches("long")
+    g.decode_and_check("long")
+
+
+def test_reevict_argument_errors(ctx):
+    w = W.scaled(W.CONFIGS[0], L=2, H=2, Hq=4, b_min=4)
+    g = Grown(ctx, w, [200], 0, slack=2)
+    lengths = np.concatenate([o[4] for o in g.oracle]).astype(np.int32)
+    bad = lengths.copy(); bad[2] += 1
+    scratch = torch.empty((int(lengths.sum()) + 8,), dtype=torch.int32, device="cuda")
+    with pytest.raises(lkv.LkvError) as e:
+        lkv.lkv_reevict(ctx, w.d, g.kp, g.vp, g.up, g.cap, g.len, lengths, bad, 1, scratch, torch.empty_like(g.cap),
+                        torch.empty_like(g.kp), torch.empty_like(g.vp), torch.empty_like(g.up), torch.empty_like(g.cap),
+                        torch.empty_like(g.len))
+    assert e.value.status == 1
+    torch.cuda.synchronize()
 
 
 def test_growth_argument_errors(ctx):
