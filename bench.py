@@ -40,6 +40,7 @@ def parse():
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
                     help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-growth", action="store_true", help="skip the decode-time growth measurement")
     ap.add_argument("--no-layerwise", action="store_true", help="skip the layer-by-layer eviction measurement")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (a kernel of known "
@@ -201,9 +202,71 @@ def main():
                        "note": "head scores + Soft-TopK + floor(r t); computed once, outside the step"}
     if layerwise_result is not None:
         result["layerwise"] = layerwise_result
+    if not args.no_growth:
+        result["growth"] = growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
     print(json.dumps(result))
+
+
+def growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev, slack=128, n_new=64):
+    """Decode-time growth (spare rows per segment): compaction with slack, n_new appended tokens,
+    decode over the rows in use, then a re-eviction with the budgets floor(r t') of the longer context."""
+    import torch
+
+    n_seg = cache.n_segments
+    rows = total + n_seg * slack
+    kp = torch.empty((rows, w.d), dtype=torch.bfloat16, device=dev)
+    vp = torch.empty_like(kp)
+    up = torch.empty((rows,), dtype=torch.float32, device=dev)
+    cap = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
+    ln = torch.empty((n_seg,), dtype=torch.int32, device=dev)
+    out = torch.empty((w.n_seq, w.L, w.Hq, w.d), dtype=torch.float32, device=dev)
+    lse = torch.empty((w.n_seq, w.L, w.Hq), dtype=torch.float32, device=dev)
+    ws = torch.empty((lkv.lkv_decode_workspace_bytes(n_seg, rows, w.Hq, w.H),), dtype=torch.uint8, device=dev)
+    k_new = torch.randn((w.n_seq, w.L, w.H, w.d), device=dev).to(torch.bfloat16)
+    v_new = torch.randn((w.n_seq, w.L, w.H, w.d), device=dev).to(torch.bfloat16)
+
+    def timed(fn, reps):
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(reps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / reps
+
+    def compact():
+        lkv.lkv_compact_grow(ctx, cache, scores, idx, offsets, total, slack, kp, vp, up, cap, ln)
+
+    compact()
+    t_compact = timed(compact, 5)
+    t_append = timed(lambda: lkv.lkv_append(ctx, w.n_seq, w.L, w.H, w.d, scorer, k_new, v_new, kp, vp, up, cap, ln), n_new)
+    used = total + n_seg * n_new
+    dec = lambda: lkv.lkv_decode_attn_grown(ctx, w.n_seq, w.L, w.H, w.Hq, w.d, q, kp, vp, cap, ln, rows, scale, out, lse, ws)
+    dec()
+    t_decode = timed(dec, 10)
+    seg_T = np.repeat(np.asarray(Ts, dtype=np.float64), w.L * w.H)
+    len_h = budgets_flat.astype(np.int64) + n_new
+    nb = np.minimum(np.floor(budgets_flat / seg_T * (seg_T + n_new)).astype(np.int64), len_h)
+    total2 = int(nb.sum())
+    rows2 = total2 + n_seg * slack
+    kp2 = torch.empty((rows2, w.d), dtype=torch.bfloat16, device=dev)
+    vp2 = torch.empty_like(kp2)
+    up2 = torch.empty((rows2,), dtype=torch.float32, device=dev)
+    cap2, len2 = torch.empty_like(cap), torch.empty_like(ln)
+    idx2 = torch.empty((total2,), dtype=torch.int32, device=dev)
+    off2 = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
+    re = lambda: lkv.lkv_reevict(ctx, w.d, kp, vp, up, cap, ln, len_h, nb, slack, idx2, off2, kp2, vp2, up2, cap2, len2)
+    re()
+    t_reevict = timed(re, 5)
+    re_bytes = used * 4 + total2 * (4 + 4 + 4 + 4 + 1024)
+    return {"slack": slack, "appended": n_new, "rows_in_use": int(used),
+            "compact_with_slack_ms": t_compact, "append_us_per_token": t_append * 1e3,
+            "decode_ms": t_decode, "decode_GBps": used * 512 / (t_decode * 1e6),
+            "decode_frac_of_peak": used * 512 / (t_decode * 1e6) / HBM_PEAK_GBS,
+            "reevict_ms": t_reevict, "reevict_kept": total2, "reevict_GBps": re_bytes / (t_reevict * 1e6)}
 
 
 def layerwise(ctx, lkv, W, w, scorer, dev, reps=3):

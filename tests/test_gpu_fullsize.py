@@ -160,3 +160,93 @@ def test_full_size_group7_shared_budgets():
     for seq in (0, w.n_seq - 1):
         _check_sampled_heads(r, seq, [(0, 0), (int(lmax), int(hmax)), (int(lmin), int(hmin)), (w.L - 1, w.H - 1)])
     r["ctx"].close()
+
+
+def test_full_size_growth_and_reeviction():
+    """Workload 1 with 128 spare rows per segment: three generated tokens are appended, the decode
+    reads the rows in use, then the cache is re-evicted with the budgets floor(r t') of the longer
+    context.  Sampled heads are rebuilt by the oracle from the same bytes."""
+    from oracle import lkv_growth as GR
+
+    w = W.CONFIGS[1]
+    r = _run_full(w)
+    ctx, dev = r["ctx"], torch.device("cuda:0")
+    T, n_seg, slack, n_new = r["Ts"][0], w.L * w.H, 128, 3
+    cache = lkv.Cache(r["Ks"], r["Vs"], w.Hq)
+    rows = r["total"] + n_seg * slack
+    kp = torch.zeros((rows, w.d), dtype=torch.bfloat16, device=dev)
+    vp = torch.zeros_like(kp)
+    up = torch.zeros((rows,), dtype=torch.float32, device=dev)
+    cap = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
+    ln = torch.empty((n_seg,), dtype=torch.int32, device=dev)
+    overflow = torch.zeros((1,), dtype=torch.int32, device=dev)
+    scorer = G.scorer_to_gpu(r["sc"])
+    lkv.lkv_compact_grow(ctx, cache, r["scores"], r["idx"], r["offsets"], r["total"], slack, kp, vp, up, cap, ln)
+    gen = torch.Generator(device=dev); gen.manual_seed(123)
+    new_k = [torch.randn((1, w.L, w.H, w.d), device=dev, generator=gen).to(torch.bfloat16) for _ in range(n_new)]
+    new_v = [torch.randn((1, w.L, w.H, w.d), device=dev, generator=gen).to(torch.bfloat16) for _ in range(n_new)]
+    for kn, vn in zip(new_k, new_v):
+        lkv.lkv_append(ctx, 1, w.L, w.H, w.d, scorer, kn, vn, kp, vp, up, cap, ln, overflow)
+    q = torch.stack([G.bits_to_bf16_gpu(x) for x in r["qbits"]]).contiguous()
+    out = torch.full((1, w.L, w.Hq, w.d), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((1, w.L, w.Hq), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.empty((lkv.lkv_decode_workspace_bytes(n_seg, rows, w.Hq, w.H),), dtype=torch.uint8, device=dev)
+    lkv.lkv_decode_attn_grown(ctx, 1, w.L, w.H, w.Hq, w.d, q, kp, vp, cap, ln, rows, G.SCALE, out, lse, ws)
+    torch.cuda.synchronize()
+    assert int(overflow.item()) == 0
+    cap_h, len_h = cap.cpu().numpy().astype(np.int64), ln.cpu().numpy().astype(np.int64)
+    assert np.array_equal(len_h, r["flat"] + n_new)
+    assert np.array_equal(cap_h, np.concatenate([[0], np.cumsum(r["flat"].astype(np.int64) + slack)]))
+    assert bool(torch.isfinite(out).all())
+
+    # re-eviction with the budgets of the longer context
+    ratios = r["flat"].astype(np.float64) / T
+    nb = np.minimum(np.floor(ratios * (T + n_new)).astype(np.int64), len_h)
+    total2 = int(nb.sum())
+    rows2 = total2 + n_seg * slack
+    kp2 = torch.zeros((rows2, w.d), dtype=torch.bfloat16, device=dev)
+    vp2 = torch.zeros_like(kp2)
+    up2 = torch.zeros((rows2,), dtype=torch.float32, device=dev)
+    cap2 = torch.empty_like(cap); len2 = torch.empty_like(ln)
+    idx2 = torch.empty((total2,), dtype=torch.int32, device=dev)
+    off2 = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
+    assert lkv.lkv_reevict(ctx, w.d, kp, vp, up, cap, ln, len_h, nb, slack, idx2, off2, kp2, vp2, up2, cap2, len2) == total2
+    torch.cuda.synchronize()
+    cap2_h = cap2.cpu().numpy().astype(np.int64)
+    assert np.array_equal(len2.cpu().numpy(), nb)
+
+    sc_o = G.scorer_to_oracle(r["sc"])
+    off = r["offsets"].cpu().numpy().astype(np.int64)
+    for (l, h) in _sample(r, 0):
+        seg = l * w.H + h
+        a, n = int(cap_h[seg]), int(len_h[seg])
+        b = int(r["flat"][seg])
+        # rows in use: the kept prefill rows (bit for bit, checked against the tight cache) then the new tokens
+        assert torch.equal(kp[a:a + b].view(torch.int16), r["kp"][off[seg]:off[seg + 1]].view(torch.int16))
+        assert torch.equal(vp[a:a + b].view(torch.int16), r["vp"][off[seg]:off[seg + 1]].view(torch.int16))
+        u_head = r["scores"][0][l, h]
+        assert torch.equal(up[a:a + b], u_head[r["idx"][off[seg]:off[seg + 1]].long()])
+        one = {"kind": sc_o["kind"], "act": sc_o["act"], "w1": sc_o["w1"][l:l + 1, 0:1], "b1": sc_o["b1"][l:l + 1, 0:1],
+               "w2": None, "b2": None}
+        rms = float(u_head.double().pow(2).mean().sqrt())
+        for j in range(n_new):
+            assert torch.equal(kp[a + b + j].view(torch.int16), new_k[j][0, l, h].view(torch.int16))
+            assert torch.equal(vp[a + b + j].view(torch.int16), new_v[j][0, l, h].view(torch.int16))
+            u_ref = O.score(O.bf16_bits_to_f64(_bits(new_k[j][0, l, h]))[None, None, None],
+                            O.bf16_bits_to_f64(_bits(new_v[j][0, l, h]))[None, None, None], one)[0, 0, 0]
+            assert abs(float(up[a + b + j]) - float(u_ref)) <= G.SCORE_RTOL * max(abs(float(u_ref)), rms)
+        # decode over the rows in use
+        Kh, Vh = _bits(kp[a:a + n]), _bits(vp[a:a + n])
+        g = w.g
+        qh = O.bf16_bits_to_f64(r["qbits"][0][l, h * g:(h + 1) * g])[None]
+        o_ref, lse_ref = O.decode_attn(qh, O.bf16_bits_to_f64(Kh), O.bf16_bits_to_f64(Vh), np.array([0, n]), 1, G.SCALE)
+        G.assert_decode_close(out[0, l, h * g:(h + 1) * g].cpu().numpy(), lse[0, l, h * g:(h + 1) * g].cpu().numpy(),
+                              o_ref[0], lse_ref[0], f"grown decode of segment {seg}")
+        # re-eviction of this segment, by the oracle, on the scores the GPU holds
+        u_held = up[a:a + n].cpu().numpy()
+        K2, V2, u2, c2, l2, pos = GR.reevict(Kh, Vh, u_held, np.array([0, n]), np.array([n]), np.array([nb[seg]]), 0)
+        a2 = int(cap2_h[seg])
+        assert np.array_equal(_bits(kp2[a2:a2 + nb[seg]]), K2), f"re-evicted K of segment {seg}"
+        assert np.array_equal(_bits(vp2[a2:a2 + nb[seg]]), V2), f"re-evicted V of segment {seg}"
+        assert np.array_equal(up2[a2:a2 + nb[seg]].cpu().numpy(), u2), f"re-evicted scores of segment {seg}"
+    ctx.close()
