@@ -40,8 +40,11 @@ def parse():
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
                     help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-growth", action="store_true", help="skip the decode-time growth measurement")
-    ap.add_argument("--no-layerwise", action="store_true", help="skip the layer-by-layer eviction measurement")
+    ap.add_argument("--growth", action="store_true",
+                    help="also measure decode-time growth (compaction with slack, append, grown decode, re-eviction); "
+                         "adds the key `growth`")
+    ap.add_argument("--layerwise", action="store_true",
+                    help="also measure layer-by-layer eviction during prefill; adds the key `layerwise`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (a kernel of known "
                          "traffic for scaling hardware byte counters under rocprofv3 --pmc)")
@@ -83,7 +86,7 @@ def main():
               "per_head": sc_host["per_head"], "w1": to_dev(sc_host["w1"], True), "b1": to_dev(sc_host["b1"]),
               "w2": to_dev(sc_host["w2"]), "b2": to_dev(sc_host["b2"])}
     # ---- layer-by-layer mode first, while the whole cache does not exist yet ---------------
-    if not args.no_layerwise:
+    if args.layerwise:
         layerwise_result = layerwise(ctx, lkv, W, w, scorer, dev)
         torch.cuda.empty_cache()
 
@@ -202,7 +205,7 @@ def main():
                        "note": "head scores + Soft-TopK + floor(r t); computed once, outside the step"}
     if layerwise_result is not None:
         result["layerwise"] = layerwise_result
-    if not args.no_growth:
+    if args.growth:
         result["growth"] = growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
