@@ -26,9 +26,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the score kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
-# by what the counter reads for a plain 1 GiB copy (profiles/hbm_traffic_counters__cfg1_L32_H8_T32768_linear.md).
+# by what the counter reads for a plain 1 GiB copy (profiles/hbm_traffic_counters__*.md).
 # Hardware counters cannot be read from inside this script, so the figure is carried per workload; None = not measured.
-MEASURED_SCORE_TRAFFIC_BYTES = {1: 4328786289}
+MEASURED_SCORE_TRAFFIC_BYTES = {1: 4328786289, 2: 17324229632, 5: 4465987584}
 
 
 def parse():
