@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
                     help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--decode-per-layer", action="store_true",
+                    help="also time the decode as one launch per layer (single-sequence workloads); adds the key "
+                         "`decode_per_layer_launches`")
     ap.add_argument("--growth", action="store_true",
                     help="also measure decode-time growth (compaction with slack, append, grown decode, re-eviction); "
                          "adds the key `growth`")
@@ -200,6 +203,42 @@ def main():
                      "bytes_per_launch": score_bytes},
     }
 
+    # ---- context figures: a plain device copy on this machine, and decode launched once per layer ----
+    src = torch.empty((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ec = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ec[0].record()
+    for _ in range(5):
+        dst.copy_(src)
+    ec[1].record()
+    torch.cuda.synchronize()
+    copy_gbps = 5 * 2 * src.numel() * 4 / (ec[0].elapsed_time(ec[1]) * 1e6)
+    del src, dst
+    result["device_copy_GBps"] = copy_gbps
+    if w.n_seq == 1 and args.decode_per_layer:
+        # a real model runs its layers one after the other, so decode is one launch per layer there
+        off_h = offsets.cpu().numpy().astype(np.int64)
+        lay_off = [torch.from_numpy((off_h[l * w.H:(l + 1) * w.H + 1] - off_h[l * w.H]).astype(np.int32)).to(dev)
+                   for l in range(w.L)]
+        lay_rows = [int(off_h[(l + 1) * w.H] - off_h[l * w.H]) for l in range(w.L)]
+        def decode_layers():
+            for l in range(w.L):
+                r0 = int(off_h[l * w.H])
+                lkv.lkv_decode_attn(ctx, 1, 1, w.H, w.Hq, w.d, q[0, l], kp[r0:], vp[r0:], lay_off[l], lay_rows[l],
+                                    scale, out[0, l], lse[0, l], ws)
+        decode_layers()
+        torch.cuda.synchronize()
+        ec[0].record()
+        for _ in range(5):
+            decode_layers()
+        ec[1].record()
+        torch.cuda.synchronize()
+        t_layers = ec[0].elapsed_time(ec[1]) / 5
+        result["decode_per_layer_launches"] = {"ms_all_layers": t_layers, "us_per_layer": t_layers * 1e3 / w.L,
+                                               "GBps": decode_bytes / (t_layers * 1e6),
+                                               "note": "launch-latency bound at batch 1: one layer is ~20-54 MB"}
     result["config"]["budgets"] = "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe"
     result["lkv_h"] = {"n_heads": w.L * w.H, "us_per_call": lkv_h_us, "dtype": "f64",
                        "note": "head scores + Soft-TopK + floor(r t); computed once, outside the step"}
