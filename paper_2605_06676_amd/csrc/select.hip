@@ -76,6 +76,19 @@ __device__ __forceinline__ uint32_t wave_inclusive_scan(uint32_t x, int lane) {
   return x;
 }
 
+// Sum of x over the 64 lanes of a wave, in every lane.
+__device__ __forceinline__ uint32_t wave_sum(uint32_t x) {
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) x += __shfl_xor(x, d, 64);
+  return x;
+}
+
+// Sum of the per-wave totals of the waves ahead of `wave`: one LDS read per lane and a wave
+// reduction instead of a chain of dependent reads.
+__device__ __forceinline__ uint32_t waves_before(const uint32_t* totals, int wave, int lane) {
+  return wave_sum(lane < wave ? totals[lane] : 0u);
+}
+
 // Calls f(key, token) for every token of the head, in no particular order, reading the fp32
 // scores from global memory with kSelBatch loads in flight per thread (16-byte loads when the
 // head is 16-byte aligned and its length a multiple of four).
@@ -122,21 +135,24 @@ __device__ __forceinline__ void for_each_global_key(const float* __restrict__ u,
 
 // One level of the radix descent.  `count(fn)` must call fn(key) for every key of the head.
 // On return prefix / prefix_mask / need are advanced by this level's digit.
+// `counted`: the histogram of this level has already been filled (and a barrier passed).
 template <typename Count>
 __device__ __forceinline__ void descend_level(SelShared& sh, int level, uint32_t& prefix, uint32_t& prefix_mask,
-                                              uint32_t& need, Count count) {
+                                              uint32_t& need, Count count, bool counted = false) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
   const int shift = level == 0 ? 21 : (level == 1 ? 10 : 0);
   const int nbins = level == 2 ? 1024 : 2048;
-  for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
-  __syncthreads();   // also orders an LDS key cache fill before its first use
-  const uint32_t pfx = prefix, msk = prefix_mask;
-  count([&](uint32_t key) {
-    if ((key & msk) == pfx) atomicAdd(&sh.hist[(key >> shift) & (nbins - 1)], 1u);
-  });
-  __syncthreads();
+  if (!counted) {
+    for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
+    __syncthreads();   // also orders an LDS key cache fill before its first use
+    const uint32_t pfx = prefix, msk = prefix_mask;
+    count([&](uint32_t key) {
+      if ((key & msk) == pfx) atomicAdd(&sh.hist[(key >> shift) & (nbins - 1)], 1u);
+    });
+    __syncthreads();
+  }
   // scan the bins from the top: thread t owns bins nbins-1-2t and nbins-2-2t
   uint32_t c0 = 0, c1 = 0;
   const int top = nbins - 1 - 2 * tid;
@@ -145,8 +161,7 @@ __device__ __forceinline__ void descend_level(SelShared& sh, int level, uint32_t
   const uint32_t incl = wave_inclusive_scan(c0 + c1, lane);
   if (lane == 63) sh.wave_tot[wave] = incl;
   __syncthreads();
-  uint32_t before = 0;
-  for (int w = 0; w < wave; ++w) before += sh.wave_tot[w];
+  const uint32_t before = waves_before(sh.wave_tot, wave, lane);
   const uint32_t excl = before + incl - (c0 + c1);   // keys in bins above this thread's pair
   // exactly one bin satisfies: above < need <= above + count
   if (c0 && excl < need && need <= excl + c0) { sh.found_bin = (uint32_t)top; sh.found_above = excl; }
@@ -178,8 +193,8 @@ __device__ __forceinline__ void emit_from_keys(SelShared& sh, int T, uint32_t th
   }
   if (lane == 0) { sh.wave_gt[wave] = n_gt; sh.wave_eq[wave] = n_eq; }
   __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0;
-  for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
+  const uint32_t gt_before = waves_before(sh.wave_gt, wave, lane);
+  const uint32_t eq_before = waves_before(sh.wave_eq, wave, lane);
   uint32_t eq_seen = eq_before;                                  // copies of thr before the current 64 tokens
   uint32_t pos = gt_before + min(eq_before, need);               // kept tokens before the current 64 tokens
   for (int base = lo; base < hi; base += 64) {
@@ -238,8 +253,8 @@ __device__ __forceinline__ void emit_from_bitmaps(SelShared& sh, int T, uint32_t
   for (int d = 32; d >= 1; d >>= 1) { n_gt += __shfl_xor(n_gt, d, 64); n_eq += __shfl_xor(n_eq, d, 64); }
   if (lane == 0) { sh.wave_gt[wave] = n_gt; sh.wave_eq[wave] = n_eq; }
   __syncthreads();
-  uint32_t gt_before = 0, eq_before = 0;
-  for (int w = 0; w < wave; ++w) { gt_before += sh.wave_gt[w]; eq_before += sh.wave_eq[w]; }
+  const uint32_t gt_before = waves_before(sh.wave_gt, wave, lane);
+  const uint32_t eq_before = waves_before(sh.wave_eq, wave, lane);
   uint32_t eq_seen = eq_before;
   uint32_t pos = gt_before + min(eq_before, need);
   const int half = lane & 1;
@@ -329,24 +344,60 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
     const int n_words = (T + 31) >> 5;
     uint32_t* gt_map = region + cached_limit;   // after the key cache of the launch's longest cached head
     uint32_t* eq_map = gt_map + n_words;
-    for_each_global_key(u, T, [&](uint32_t key, int i) { keys[i] = key; });
-    auto count = [&](auto fn) { for (int i = tid; i < T; i += kSelThreads) fn(keys[i]); };
-#pragma unroll 1
-    for (int level = 0; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
-    const uint32_t thr = prefix;
-    // classification: a wave covers 64 consecutive tokens, so a ballot is two finished bitmap words
-    const int lane = tid & 63;
-    for (int base = (tid >> 6) * 64; base < T; base += kSelThreads) {
-      const int i = base + lane;
-      const uint32_t key = i < T ? keys[i] : 0u;
-      const unsigned long long m_gt = __ballot(i < T && key > thr);
-      const unsigned long long m_eq = __ballot(i < T && key == thr);
-      if (lane == 0) {
-        const int w = base >> 5;
-        gt_map[w] = (uint32_t)m_gt;
-        eq_map[w] = (uint32_t)m_eq;
-        if (w + 1 < n_words) { gt_map[w + 1] = (uint32_t)(m_gt >> 32); eq_map[w + 1] = (uint32_t)(m_eq >> 32); }
+    // the first level's histogram is counted while the keys pass through registers on their way to LDS
+    for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
+    __syncthreads();
+    for_each_global_key(u, T, [&](uint32_t key, int i) {
+      keys[i] = key;
+      atomicAdd(&sh.hist[key >> 21], 1u);
+    });
+    __syncthreads();
+    // later levels read the cached keys eight at a time so that the LDS latency is paid once per batch
+    auto count = [&](auto fn) {
+      for (int base = tid; base < T; base += kSelThreads * kSelBatch) {
+        uint32_t kb[kSelBatch];
+#pragma unroll
+        for (int k = 0; k < kSelBatch; ++k) {
+          const int i = base + k * kSelThreads;
+          kb[k] = keys[i < T ? i : base];
+        }
+#pragma unroll
+        for (int k = 0; k < kSelBatch; ++k)
+          if (base + k * kSelThreads < T) fn(kb[k]);
       }
+    };
+    descend_level(sh, 0, prefix, prefix_mask, need, count, true);
+#pragma unroll 1
+    for (int level = 1; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
+    const uint32_t thr = prefix;
+    // classification: a wave covers 64 consecutive tokens, so a ballot is two finished bitmap
+    // words.  The words of 32 rounds are collected in registers (lane 2k + j keeps half j of round
+    // k) and written with one LDS store per lane and map.
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    constexpr int kClsBatch = 4;
+    for (int chunk0 = 0; chunk0 < T; chunk0 += 32 * kSelThreads) {   // one pass for every length the cache holds up to 32768
+      uint32_t my_gt = 0, my_eq = 0;
+#pragma unroll 1
+      for (int kk = 0; kk < 32; kk += kClsBatch) {
+        uint32_t kb[kClsBatch];
+#pragma unroll
+        for (int k = 0; k < kClsBatch; ++k) {
+          const int i = chunk0 + (kk + k) * kSelThreads + wave * 64 + lane;
+          kb[k] = i < T ? keys[i] : 0u;
+        }
+#pragma unroll
+        for (int k = 0; k < kClsBatch; ++k) {
+          const int i = chunk0 + (kk + k) * kSelThreads + wave * 64 + lane;
+          const unsigned long long m_gt = __ballot(i < T && kb[k] > thr);
+          const unsigned long long m_eq = __ballot(i < T && kb[k] == thr);
+          const int slot = 2 * (kk + k);
+          if (lane == slot) { my_gt = (uint32_t)m_gt; my_eq = (uint32_t)m_eq; }
+          if (lane == slot + 1) { my_gt = (uint32_t)(m_gt >> 32); my_eq = (uint32_t)(m_eq >> 32); }
+        }
+      }
+      const int w = ((chunk0 + (lane >> 1) * kSelThreads + wave * 64) >> 5) + (lane & 1);
+      if (w < n_words) { gt_map[w] = my_gt; eq_map[w] = my_eq; }
     }
     __syncthreads();
     emit_from_bitmaps(sh, T, need, out, gt_map, eq_map, region + cached_stage_off);   // the key cache is dead by now
