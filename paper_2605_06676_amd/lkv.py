@@ -12,7 +12,7 @@ import os
 from typing import Optional, Sequence
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblkv.so")
+LIB_PATH = os.environ.get("LKV_LIBRARY", os.path.join(_HERE, "liblkv.so"))   # LKV_LIBRARY: load another build of the library
 
 LKV_OK = 0
 SCORER_LINEAR, SCORER_MLP = 0, 1
