@@ -329,12 +329,14 @@ def layerwise(ctx, lkv, W, w, scorer, dev, reps=3):
     ring = [([torch.empty((1, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts],
              [torch.empty((1, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts]) for _ in range(2)]
     views = [lkv.Cache(k, v, w.Hq) for k, v in ring]
-    scratch = [torch.empty((w.H, T), dtype=torch.float32, device=dev) for T in Ts]
+    # eviction alternates between two streams (each with its own score scratch) so that the latency-bound
+    # top-k of one layer overlaps the bandwidth-bound scoring of the next
+    scratch = [[torch.empty((w.H, T), dtype=torch.float32, device=dev) for T in Ts] for _ in range(2)]
     idx = torch.empty((total,), dtype=torch.int32, device=dev)
     offsets = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
     kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
     vp = torch.empty_like(kp)
-    s_fill, s_evict = torch.cuda.Stream(), torch.cuda.Stream()
+    s_fill, s_evicts = torch.cuda.Stream(), [torch.cuda.Stream(), torch.cuda.Stream()]
 
     def fill(slot):
         for t in ring[slot][0] + ring[slot][1]:
@@ -347,9 +349,13 @@ def layerwise(ctx, lkv, W, w, scorer, dev, reps=3):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         if evict:
-            lkv.lkv_plan_offsets(ctx, budgets, offsets, stream=s_evict)
+            lkv.lkv_plan_offsets(ctx, budgets, offsets, stream=s_evicts[0])
+            planned = torch.cuda.Event()
+            planned.record(s_evicts[0])
+            s_evicts[1].wait_event(planned)
         for l in range(w.L):
             slot = l & 1
+            s_evict = s_evicts[slot]
             if produce:
                 with torch.cuda.stream(s_fill):
                     if evict and l >= 2:
@@ -360,7 +366,7 @@ def layerwise(ctx, lkv, W, w, scorer, dev, reps=3):
                 if produce:
                     s_evict.wait_event(filled[l])
                 started[l].record(s_evict)
-                lkv.lkv_evict_layer(ctx, views[slot], l, w.L, scorer, budgets, offsets, scratch, idx, kp, vp,
+                lkv.lkv_evict_layer(ctx, views[slot], l, w.L, scorer, budgets, offsets, scratch[slot], idx, kp, vp,
                                     stream=s_evict)
                 evicted[l].record(s_evict)
         torch.cuda.synchronize()
