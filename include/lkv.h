@@ -247,6 +247,23 @@ lkv_status lkv_reevict(lkv_ctx *ctx, int64_t n_segments, int32_t head_dim, const
                        int32_t *idx, int32_t *offsets, void *kp_new, void *vp_new, float *up_new,
                        int32_t *cap_offsets_new, int32_t *lengths_new, int64_t *total_kept, void *stream);
 
+/* ---- Attention with a multiplicative retention mask over the UNCOMPACTED cache (App. B.2) ----
+ * For one query per head: p_i = e^{s_i} m_i / sum_j e^{s_j} m_j, s_i = scale * q . K[l, h, i, :],
+ * out = sum_i p_i V[l, h, i, :]; this equals softmax(s + log m).  With a 0/1 mask it is what
+ * lkv_decode_attn computes on the compacted cache (the identity the eviction rests on); with
+ * m = ST_k(u / tau) it is the relaxed forward the scorer is trained through (Sec. 3.4).
+ * q    : DEVICE bf16 [n_seq, L, Hq, d]
+ * mask : HOST [n_seq] of DEVICE fp32 [L, H, T_s], values in [0, 1]; a head whose mask is all zero
+ *        gives out = 0 and lse = -inf
+ * out  : DEVICE fp32 [n_seq, L, Hq, d];  lse : DEVICE fp32 [n_seq, L, Hq] or NULL
+ *        (lse = log sum_i m_i e^{s_i})
+ * workspace : DEVICE, at least lkv_masked_decode_workspace_bytes(cache) bytes, 256-byte aligned.
+ * Sequences are processed one after the other on `stream`. */
+size_t lkv_masked_decode_workspace_bytes(const lkv_cache *cache);
+lkv_status lkv_masked_decode_attn(lkv_ctx *ctx, const lkv_cache *cache, const void *q,
+                                  const float *const *mask, float scale, float *out, float *lse,
+                                  void *workspace, size_t workspace_bytes, void *stream);
+
 /* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
 
 /* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):

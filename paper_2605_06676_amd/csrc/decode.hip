@@ -73,13 +73,17 @@ __device__ __forceinline__ s16x4_t lds_read_tr16(const unsigned char* p) {
       (__attribute__((address_space(3))) s16x4_t*)(p));
 }
 
+// kMasked: every row carries a retention weight m in [0, 1] and the probabilities are
+// p_i = e^{s_i} m_i / sum_j e^{s_j} m_j (the multiplicative mask of App. B.2, which is softmax(s + log m));
+// the rows are then those of the uncompacted cache.
+template <bool kMasked>
 __global__ void __launch_bounds__(kDecThreads, 2)
 decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ kp,
                       const uint4* __restrict__ vp, const int32_t* __restrict__ offsets,
                       const int32_t* __restrict__ lengths /* rows in use per segment, or null: all of them */,
                       int n_segments, int64_t total_kept, int chunk_rows, int G, float scale, float* __restrict__ out,
                       float* __restrict__ lse, float* __restrict__ ws_acc, float* __restrict__ ws_m,
-                      float* __restrict__ ws_l) {
+                      float* __restrict__ ws_l, const float* __restrict__ mask) {
   extern __shared__ __align__(16) unsigned char smem[];
 
   const int chunk = blockIdx.x;
@@ -178,8 +182,11 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-          const bool ok = tok0 + tt * 16 + 4 * r + e < n_rows;
-          sv[tt * 4 + e] = ok ? sacc[tt][e] * qscale : -INFINITY;
+          const int tok = tok0 + tt * 16 + 4 * r + e;
+          const bool ok = tok < n_rows;
+          float sc = sacc[tt][e] * qscale;
+          if (kMasked) sc += __log2f(mask[a + (ok ? tok : 0)]);   // log2(0) = -inf drops the row
+          sv[tt * 4 + e] = ok ? sc : -INFINITY;
           mx = fmaxf(mx, sv[tt * 4 + e]);
         }
       mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
@@ -240,16 +247,18 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
       float mxw = -INFINITY;
 #pragma unroll
       for (int w = 0; w < kDecWaves; ++w) mxw = fmaxf(mxw, mg.m[w][h]);
+      const float refw = mxw == -INFINITY ? 0.f : mxw;   // -inf: no row of this piece carries weight
       float num = 0.f, den = 0.f;
 #pragma unroll
       for (int w = 0; w < kDecWaves; ++w) {
-        const float wgt = fast_exp2(mg.m[w][h] - mxw);   // 0 for a wave that saw no row (m = -inf)
+        const float wgt = fast_exp2(mg.m[w][h] - refw);   // 0 for a wave that saw no row (m = -inf)
         num = fmaf(mg.acc[w][h][ch], wgt, num);
         den = fmaf(mg.l[w][h], wgt, den);
       }
       if (whole) {
-        out[((size_t)s * G + h) * kHeadDim + ch] = num / den;
-        if (ch == 0 && lse != nullptr) lse[(size_t)s * G + h] = mxw * kLn2 + __logf(den);
+        // den = 0 only when every row of the segment carries weight 0: zero output, lse = -inf
+        out[((size_t)s * G + h) * kHeadDim + ch] = den > 0.f ? num / den : 0.f;
+        if (ch == 0 && lse != nullptr) lse[(size_t)s * G + h] = den > 0.f ? mxw * kLn2 + __logf(den) : -INFINITY;
       } else {
         ws_acc[(slot * G + h) * kHeadDim + ch] = num;
         if (ch == 0) { ws_m[slot * G + h] = mxw; ws_l[slot * G + h] = den; }
@@ -297,20 +306,21 @@ decode_merge_kernel(const int32_t* __restrict__ offsets, const int32_t* __restri
     }
     float mnew = mx;
 #pragma unroll
-    for (int u = 0; u < kU; ++u) mnew = fmaxf(mnew, mv[u]);   // finite: every piece holds at least one row
-    const float keep = fast_exp2(mx - mnew);                   // 0 in the first round
+    for (int u = 0; u < kU; ++u) mnew = fmaxf(mnew, mv[u]);   // -inf only if every row so far carries weight 0
+    const float ref = mnew == -INFINITY ? 0.f : mnew;
+    const float keep = fast_exp2(mx - ref);                    // 0 in the first round
     num *= keep;
     den *= keep;
     mx = mnew;
 #pragma unroll
     for (int u = 0; u < kU; ++u) {
-      const float wgt = c0 + u <= c_last ? fast_exp2(mv[u] - mx) : 0.f;
+      const float wgt = c0 + u <= c_last ? fast_exp2(mv[u] - ref) : 0.f;
       num = fmaf(av[u], wgt, num);
       den = fmaf(lv[u], wgt, den);
     }
   }
-  out[row * kHeadDim + ch] = num / den;
-  if (ch == 0 && lse != nullptr) lse[row] = mx * kLn2 + __logf(den);
+  out[row * kHeadDim + ch] = den > 0.f ? num / den : 0.f;
+  if (ch == 0 && lse != nullptr) lse[row] = den > 0.f ? mx * kLn2 + __logf(den) : -INFINITY;
 }
 
 // Rows per block: a multiple of the wave tile, sized for LKV_DEC_TARGET_BLOCKS blocks.
@@ -334,13 +344,27 @@ size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G) {
 
 // The four staging tiles exceed the default 64 KB of LDS per workgroup.
 hipError_t decode_prepare() {
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel),
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel<false>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, kDecWaves * kDecWaveLds);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel<true>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, kDecWaves * kDecWaveLds);
+}
+
+// offsets[s] = s * len for s = 0..n_segments: the uncompacted cache of one sequence seen as a packed cache
+__global__ void uniform_offsets_kernel(int n_segments, int len, int32_t* __restrict__ offsets) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s <= n_segments) offsets[s] = s * len;
+}
+
+void launch_uniform_offsets(int n_segments, int len, int32_t* offsets, hipStream_t stream) {
+  hipLaunchKernelGGL(uniform_offsets_kernel, dim3((n_segments + 256) / 256), dim3(256), 0, stream, n_segments, len,
+                     offsets);
 }
 
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
                          const int32_t* lengths, int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
-                         hipStream_t stream) {
+                         hipStream_t stream, const float* mask) {
   if (G < 1 || G > kDecMaxGroup) return hipErrorInvalidValue;
   const size_t slots = decode_slots(n_segments, total_kept);
   float* ws_acc = ws;
@@ -348,11 +372,16 @@ hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, c
   float* ws_l = ws_m + slots * G;
   const int chunk_rows = decode_chunk_rows(total_kept);
   const int chunks = (int)((total_kept + chunk_rows - 1) / chunk_rows);
-  if (chunks > 0) {
-    hipLaunchKernelGGL(decode_partial_kernel, dim3(chunks), dim3(kDecThreads), kDecWaves * kDecWaveLds, stream,
+  if (chunks > 0 && mask == nullptr) {
+    hipLaunchKernelGGL(decode_partial_kernel<false>, dim3(chunks), dim3(kDecThreads), kDecWaves * kDecWaveLds, stream,
                        reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint4*>(kp),
                        reinterpret_cast<const uint4*>(vp), offsets, lengths, n_segments, total_kept, chunk_rows, G, scale,
-                       out, lse, ws_acc, ws_m, ws_l);
+                       out, lse, ws_acc, ws_m, ws_l, mask);
+  } else if (chunks > 0) {
+    hipLaunchKernelGGL(decode_partial_kernel<true>, dim3(chunks), dim3(kDecThreads), kDecWaves * kDecWaveLds, stream,
+                       reinterpret_cast<const uint16_t*>(q), reinterpret_cast<const uint4*>(kp),
+                       reinterpret_cast<const uint4*>(vp), offsets, lengths, n_segments, total_kept, chunk_rows, G, scale,
+                       out, lse, ws_acc, ws_m, ws_l, mask);
   }
   const int blocks_per_segment = (G * kHeadDim + kDecThreads - 1) / kDecThreads;
   hipLaunchKernelGGL(decode_merge_kernel, dim3(n_segments * blocks_per_segment), dim3(kDecThreads), 0, stream,

@@ -595,6 +595,58 @@ lkv_status lkv_reevict(lkv_ctx* ctx, int64_t n_segments, int32_t head_dim, const
   return LKV_OK;
 }
 
+size_t lkv_masked_decode_workspace_bytes(const lkv_cache* cache) {
+  if (cache == nullptr || cache->seq_len == nullptr || cache->n_seq < 1 || cache->n_layers < 1 ||
+      cache->n_kv_heads < 1 || cache->n_q_heads < cache->n_kv_heads)
+    return 0;
+  const int heads = cache->n_layers * cache->n_kv_heads;
+  size_t need = 0;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    const size_t b = lkv::decode_workspace_bytes(heads, (int64_t)heads * cache->seq_len[s], cache->n_q_heads / cache->n_kv_heads);
+    if (b > need) need = b;
+  }
+  return need + (((size_t)heads + 1) * sizeof(int32_t) + 255) / 256 * 256;
+}
+
+lkv_status lkv_masked_decode_attn(lkv_ctx* ctx, const lkv_cache* cache, const void* q, const float* const* mask,
+                                  float scale, float* out, float* lse, void* workspace, size_t workspace_bytes,
+                                  void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (q == nullptr || mask == nullptr || out == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q, mask or out is NULL");
+  if (!aligned16(q) || !aligned16(out)) return fail(ctx, LKV_ERR_INVALID_ARG, "q or out is not 16-byte aligned");
+  const int G = cache->n_q_heads / cache->n_kv_heads;
+  if (G > lkv::kDecodeMaxGroup) return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", G, lkv::kDecodeMaxGroup);
+  const int heads = cache->n_layers * cache->n_kv_heads;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    if (mask[s] == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "mask[%d] is NULL", s);
+    if ((int64_t)heads * cache->seq_len[s] >= (int64_t)1 << 31)
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "sequence %d has 2^31 or more cache rows", s);
+  }
+  const size_t need = lkv_masked_decode_workspace_bytes(cache);
+  if (workspace == nullptr || workspace_bytes < need)
+    return fail(ctx, LKV_ERR_WORKSPACE, "masked decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(ctx, LKV_ERR_WORKSPACE, "masked decode workspace is not 256-byte aligned");
+  const size_t off_bytes = (((size_t)heads + 1) * sizeof(int32_t) + 255) / 256 * 256;
+  int32_t* offsets = static_cast<int32_t*>(workspace);
+  float* ws = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + off_bytes);
+  hipStream_t st = as_stream(stream);
+  // the uncompacted cache of one sequence is a packed cache whose segments all have T rows
+  for (int s = 0; s < cache->n_seq; ++s) {
+    const int T = cache->seq_len[s];
+    lkv::launch_uniform_offsets(heads, T, offsets, st);
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_masked_decode_attn offsets launch");
+    const size_t qrow = (size_t)s * cache->n_layers * cache->n_q_heads;
+    if (hipError_t e = lkv::launch_decode(G, static_cast<const uint16_t*>(q) + qrow * lkv::kHeadDim, cache->k[s],
+                                          cache->v[s], offsets, nullptr, heads, (int64_t)heads * T, scale,
+                                          out + qrow * lkv::kHeadDim, lse != nullptr ? lse + qrow : nullptr, ws, st,
+                                          mask[s]))
+      return hip_fail(ctx, e, "lkv_masked_decode_attn launch");
+  }
+  return LKV_OK;
+}
+
 int32_t lkv_soft_topk_max_n(int32_t x_is_f64) { return lkv::soft_topk_max_n(x_is_f64 != 0); }
 
 lkv_status lkv_soft_topk(lkv_ctx* ctx, const void* x, int32_t x_is_f64, int32_t n, double k, double tau, double* y,

@@ -51,7 +51,8 @@ hipError_t decode_prepare();
 size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G);
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
                          const int32_t* lengths, int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
-                         hipStream_t stream);
+                         hipStream_t stream, const float* mask = nullptr);
+void launch_uniform_offsets(int n_segments, int len, int32_t* offsets, hipStream_t stream);
 
 // lkv_h.hip
 hipError_t lkv_h_prepare();

@@ -22,7 +22,8 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
-           "lkv_append", "lkv_decode_attn_grown", "lkv_reevict")
+           "lkv_append", "lkv_decode_attn_grown", "lkv_reevict", "lkv_masked_decode_workspace_bytes",
+           "lkv_masked_decode_attn")
 
 
 class LkvError(RuntimeError):
@@ -104,6 +105,11 @@ def load_library() -> C.CDLL:
                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                 C.POINTER(C.c_int64), C.c_void_p]
     lib.lkv_reevict.restype = C.c_int
+    lib.lkv_masked_decode_workspace_bytes.argtypes = [C.POINTER(_Cache)]
+    lib.lkv_masked_decode_workspace_bytes.restype = C.c_size_t
+    lib.lkv_masked_decode_attn.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.POINTER(C.c_void_p), C.c_float,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lkv_masked_decode_attn.restype = C.c_int
     lib.lkv_soft_topk_max_n.argtypes = [C.c_int32]
     lib.lkv_soft_topk_max_n.restype = C.c_int32
     lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
@@ -320,3 +326,16 @@ def lkv_reevict(ctx: Context, d: int, kp, vp, up, cap_offsets, lengths, lengths_
                                    int(slack), _ptr(idx), _ptr(offsets), _ptr(kp_new), _ptr(vp_new), _ptr(up_new),
                                    _ptr(cap_offsets_new), _ptr(lengths_new), C.byref(total), _stream_ptr(stream)))
     return int(total.value)
+
+
+def lkv_masked_decode_workspace_bytes(cache: Cache) -> int:
+    return int(load_library().lkv_masked_decode_workspace_bytes(C.byref(cache.c)))
+
+
+def lkv_masked_decode_attn(ctx: Context, cache: Cache, q, mask: Sequence, scale: float, out, lse, workspace,
+                           stream=None) -> None:
+    """mask: per-sequence GPU fp32 [L, H, T_s] with values in [0, 1]."""
+    mp = (C.c_void_p * cache.n_seq)(*[m.data_ptr() for m in mask])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ctx._check(ctx.lib.lkv_masked_decode_attn(ctx.h, C.byref(cache.c), _ptr(q), mp, float(scale), _ptr(out), _ptr(lse),
+                                              _ptr(workspace), ws_bytes, _stream_ptr(stream)))

@@ -250,3 +250,33 @@ def test_full_size_growth_and_reeviction():
         assert np.array_equal(_bits(vp2[a2:a2 + nb[seg]]), V2), f"re-evicted V of segment {seg}"
         assert np.array_equal(up2[a2:a2 + nb[seg]].cpu().numpy(), u2), f"re-evicted scores of segment {seg}"
     ctx.close()
+
+
+def test_full_size_masked_attention_identity():
+    """App. B.2 at full size: attention over the whole 4.3 GB cache with the 0/1 retention mask must
+    give, for every query head, what the decode over the compacted cache gives (a property that
+    holds at any size; both routes are GPU results, the oracle checks sampled heads of each)."""
+    w = W.CONFIGS[1]
+    r = _run_full(w)
+    ctx, dev = r["ctx"], torch.device("cuda:0")
+    T = r["Ts"][0]
+    cache = lkv.Cache(r["Ks"], r["Vs"], w.Hq)
+    seg_of_row = torch.repeat_interleave(torch.arange(w.L * w.H, device=dev),
+                                         torch.from_numpy(r["flat"].astype(np.int64)).to(dev))
+    mask = torch.zeros((w.L * w.H * T,), dtype=torch.float32, device=dev)
+    mask[seg_of_row * T + r["idx"].long()] = 1.0
+    assert int(mask.sum().item()) == r["total"]
+    q = torch.stack([G.bits_to_bf16_gpu(x) for x in r["qbits"]]).contiguous()
+    out = torch.full((1, w.L, w.Hq, w.d), float("nan"), dtype=torch.float32, device=dev)
+    lse = torch.full((1, w.L, w.Hq), float("nan"), dtype=torch.float32, device=dev)
+    ws = torch.empty((lkv.lkv_masked_decode_workspace_bytes(cache),), dtype=torch.uint8, device=dev)
+    lkv.lkv_masked_decode_attn(ctx, cache, q, [mask.view(w.L, w.H, T)], G.SCALE, out, lse, ws)
+    torch.cuda.synchronize()
+    a, b = out.double(), r["out"].double()
+    scale = torch.maximum(b.abs().amax(dim=-1), b.pow(2).mean(dim=-1).sqrt())
+    err = (a - b).abs().amax(dim=-1)
+    # each route is within DECODE_RTOL of the exact result, so two routes are within twice that of each other
+    assert bool((err <= 2 * G.DECODE_RTOL * scale).all()), f"worst {(err / scale).max().item():.3g}"
+    assert bool(((lse.double() - r["lse"].double()).abs() <= 2 * G.LSE_ATOL).all())
+    print(f"masked vs compacted decode over {w.L * w.Hq} query heads: worst relative difference {(err / scale).max().item():.3g}")
+    ctx.close()

@@ -147,3 +147,22 @@ def test_compacted_attention_equals_masked_full_attention(seed):
         s = K @ q * SCALE + np.log(O.mask_from_indices(idx, T))
     p = np.exp(s - s.max()); p /= p.sum()
     assert np.allclose(o[0, 0], p @ V, rtol=1e-11, atol=1e-13)
+
+
+def test_masked_attention_with_a_soft_mask_is_softmax_of_scores_plus_log_mask():
+    # App. B.2: multiplying the exponentiated scores by m and renormalising is softmax(s + log m)
+    from scipy.special import logsumexp
+    rng = np.random.default_rng(42)
+    T, d = 300, 128
+    q = rng.standard_normal(d)
+    K = rng.standard_normal((T, d))
+    V = rng.standard_normal((T, d))
+    m = rng.uniform(0.0, 1.0, T)
+    m[::7] = 0.0
+    got = O.masked_attention_full(q, K, V, m, SCALE)
+    s = K @ q * SCALE
+    with np.errstate(divide="ignore"):
+        z = s + np.log(m)
+    p = np.exp(z - logsumexp(z))
+    assert np.allclose(got, p @ V, rtol=1e-12, atol=1e-14)
+    assert np.all(p[::7] == 0.0)
