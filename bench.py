@@ -203,6 +203,20 @@ def main():
                      "bytes_per_launch": score_bytes},
     }
 
+    # decode by itself, back to back: what a serving loop sees between evictions (the in-step figure above
+    # has the compaction's write-backs still draining)
+    es = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    es[0].record()
+    for _ in range(args.steps):
+        lkv.lkv_decode_attn(ctx, w.n_seq, w.L, w.H, w.Hq, w.d, q, kp, vp, offsets, total, scale, out, lse, ws)
+    es[1].record()
+    torch.cuda.synchronize()
+    t_steady = es[0].elapsed_time(es[1]) / args.steps
+    result["decode"]["steady_state_ms"] = t_steady
+    result["decode"]["steady_state_GBps"] = decode_bytes / (t_steady * 1e6)
+    result["decode"]["steady_state_frac_of_peak"] = decode_bytes / (t_steady * 1e6) / HBM_PEAK_GBS
+
     # ---- context figures: a plain device copy on this machine, and decode launched once per layer ----
     src = torch.empty((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
     dst = torch.empty_like(src)
