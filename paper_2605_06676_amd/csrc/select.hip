@@ -42,6 +42,7 @@ constexpr int kSelRegionBytes = 144 * 1024;                 // LDS after the his
 constexpr int kSelMaxCachedKeys = 34304;                    // 134 KB of keys + 8.4 KB of bitmaps fit the region
 constexpr int kSelStageWords = 1024;                        // staged indices per wave and step (one per token of the step)
 constexpr int kSelStageBytes = kSelWaves * kSelStageWords * 4;   // 64 KB
+constexpr int kSelCandCap = kSelStageBytes / 4;             // candidate tokens of a long head (they overlay the staging buffer)
 constexpr int kSelMaxBitmapT = (kSelRegionBytes - kSelStageBytes) / 8 * 32;   // 327680 tokens: two bitmaps + staging
 static_assert(kSelMaxCachedKeys * 4 + 2 * ((kSelMaxCachedKeys + 31) / 32) * 4 <= kSelRegionBytes, "key cache + bitmaps");
 constexpr int kSelBatch = 8;                                // loads in flight per thread
@@ -64,6 +65,7 @@ struct SelShared {
   uint32_t wave_eq[kSelWaves];
   uint32_t found_bin;
   uint32_t found_above;
+  uint32_t cand_count;
 };
 
 // Inclusive prefix sum over the 64 lanes of a wave.
@@ -405,8 +407,50 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
   }
 
   auto count = [&](auto fn) { for_each_global_key(u, T, [&](uint32_t key, int) { fn(key); }); };
+  descend_level(sh, 0, prefix, prefix_mask, need, count);
+  // Heads too long for the key cache: the first level leaves one bin of 2048 undecided.  When its
+  // keys are few enough to list (their token indices, in the space the emission stages through
+  // later), one more pass over the scores settles everything above that bin and collects the
+  // list; the remaining two levels and the final comparison then touch the listed tokens only.
+  const uint32_t bin0 = prefix >> 21;
+  const uint32_t n_cand = sh.hist[bin0];   // level-0 counts stay until the next level clears them
+  if (T <= bitmap_limit && n_cand <= (uint32_t)kSelCandCap) {
+    const int n_words = (T + 31) >> 5;
+    uint32_t* gt_map = region;
+    uint32_t* eq_map = region + n_words;
+    uint32_t* cand = region + bitmap_stage_off;
+    for (int i = tid; i < 2 * n_words; i += kSelThreads) region[i] = 0;
+    if (tid == 0) sh.cand_count = 0;
+    __syncthreads();
+    for_each_global_key(u, T, [&](uint32_t key, int i) {
+      const uint32_t top = key >> 21;
+      if (top > bin0) {
+        atomicOr(&gt_map[i >> 5], 1u << (i & 31));
+      } else if (top == bin0) {
+        // (handing out slots per wave with a ballot was measured slower than the plain atomic)
+        const uint32_t slot = atomicAdd(&sh.cand_count, 1u);
+        if (slot < (uint32_t)kSelCandCap) cand[slot] = (uint32_t)i;
+      }
+    });
+    __syncthreads();
+    auto count_listed = [&](auto fn) {
+      for (uint32_t j = tid; j < n_cand; j += kSelThreads) fn(order_key(u[cand[j]]));
+    };
 #pragma unroll 1
-  for (int level = 0; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
+    for (int level = 1; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count_listed);
+    const uint32_t thr_listed = prefix;
+    for (uint32_t j = tid; j < n_cand; j += kSelThreads) {
+      const uint32_t i = cand[j];
+      const uint32_t key = order_key(u[i]);
+      if (key > thr_listed) atomicOr(&gt_map[i >> 5], 1u << (i & 31));
+      else if (key == thr_listed) atomicOr(&eq_map[i >> 5], 1u << (i & 31));
+    }
+    __syncthreads();   // the list is dead: its space becomes the staging buffer
+    emit_from_bitmaps(sh, T, need, out, gt_map, eq_map, region + bitmap_stage_off);
+    return;
+  }
+#pragma unroll 1
+  for (int level = 1; level < 3; ++level) descend_level(sh, level, prefix, prefix_mask, need, count);
   const uint32_t thr = prefix;   // full 32-bit key of the budget-th largest score; keep `need` of its copies
 
   if (T <= bitmap_limit) {

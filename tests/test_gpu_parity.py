@@ -176,6 +176,30 @@ def test_select_on_crafted_scores(ctx, T):
         assert np.array_equal(got[off_ref[h]:off_ref[h + 1]], idx_ref[off_ref[h]:off_ref[h + 1]]), f"head {h}"
 
 
+@pytest.mark.parametrize("n_top", [16383, 16384, 16385, 30000])
+def test_select_long_head_candidate_list_limit(ctx, n_top):
+    # a head too long for the key cache: after the first radix level the undecided bin holds n_top keys;
+    # up to 16384 of them are listed in LDS, more fall back to re-reading the scores
+    rng = np.random.default_rng(n_top)
+    T, H = 50000, 2
+    k = torch.empty((1, H, T, 128), dtype=torch.bfloat16, device="cuda")
+    cache = lkv.Cache([k], [k], H)
+    u = rng.uniform(-6.0, -2.0, size=(1, H, T)).astype(np.float32)
+    for h in range(H):
+        where = rng.choice(T, size=n_top, replace=False)
+        u[0, h, where] = rng.uniform(1.0, 1.18, size=n_top).astype(np.float32)     # one bin of the first level
+    u[0, 1, ::3] = np.float32(1.0625)                                              # and many ties inside it
+    budgets = np.array([[n_top // 2, n_top // 3 + 7]], dtype=np.int32)
+    total = int(budgets.sum())
+    buf = torch.full((total + 64,), -1, dtype=torch.int32, device="cuda")
+    offsets = torch.full((H + 1,), -1, dtype=torch.int32, device="cuda")
+    lkv.lkv_select(ctx, cache, [torch.from_numpy(u).cuda()], budgets, buf[:total], offsets)
+    torch.cuda.synchronize()
+    idx_ref, off_ref = O.select_all(u, budgets)
+    assert bool((buf[total:] == -1).all()), "writes past the end of idx"
+    assert np.array_equal(buf[:total].cpu().numpy(), idx_ref)
+
+
 def test_select_mixed_lengths_in_one_launch(ctx):
     # sequences whose heads use different storage modes share one launch (and one LDS size)
     rng = np.random.default_rng(5)
