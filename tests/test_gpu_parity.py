@@ -94,6 +94,16 @@ def test_paper_scorer_shape(ctx):
     G.check_against_oracle(run, K, V, Q, sc, B, "paper scorer")
 
 
+def test_paper_scorer_count_of_the_deeper_model(ctx):
+    # App. C.1: the 36-layer model has 36 x 8 = 288 independent scorers; all of them are exercised here
+    w = W.scaled(W.CONFIGS[5], L=36, H=8, Hq=32, T=200, b_min=4)
+    K, V, Q, sc, B = _inputs(w, [200])
+    assert sc["w1"].shape == (36, 8, 128, 256)
+    run = G.GpuRun(ctx, K, V, Q, sc, B, w.Hq)
+    run.run_all()
+    G.check_against_oracle(run, K, V, Q, sc, B, "288 scorers")
+
+
 def test_per_head_linear_scorer(ctx):
     w = W.scaled(W.CONFIGS[1], L=3, H=4, Hq=16, T=2048, b_min=8, per_head=True)
     _run_and_check(ctx, w, [2048], what="per-head linear")
