@@ -250,8 +250,29 @@ def main():
         ec[1].record()
         torch.cuda.synchronize()
         t_layers = ec[0].elapsed_time(ec[1]) / 5
+        # the same 2 L launches captured once into a HIP graph and replayed: no per-launch host cost
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            decode_layers()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                decode_layers()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        ec[0].record()
+        for _ in range(5):
+            graph.replay()
+        ec[1].record()
+        torch.cuda.synchronize()
+        t_graph = ec[0].elapsed_time(ec[1]) / 5
         result["decode_per_layer_launches"] = {"ms_all_layers": t_layers, "us_per_layer": t_layers * 1e3 / w.L,
                                                "GBps": decode_bytes / (t_layers * 1e6),
+                                               "hip_graph_ms_all_layers": t_graph,
+                                               "hip_graph_us_per_layer": t_graph * 1e3 / w.L,
+                                               "hip_graph_GBps": decode_bytes / (t_graph * 1e6),
                                                "note": "launch-latency bound at batch 1: one layer is ~20-54 MB"}
     result["config"]["budgets"] = "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe"
     result["lkv_h"] = {"n_heads": w.L * w.H, "us_per_call": lkv_h_us, "dtype": "f64",

@@ -1,0 +1,57 @@
+"""The hot calls only enqueue kernels on the caller's stream, so a step can be captured into a HIP
+graph and replayed: every replay must reproduce the eager result (replays are interleaved with
+eager work and synchronisations, as a serving loop would)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_06676_amd import lkv
+from paper_2605_06676_amd import workloads as W
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = lkv.Context(0)
+    yield c
+    c.close()
+
+
+def test_captured_step_replays_to_the_eager_result(ctx):
+    w = W.scaled(W.CONFIGS[0], L=4, H=4, Hq=16, b_min=8)      # 16 segments: offsets ride in the kernel arguments
+    T = 3000
+    K, V = W.draw_kv(w, T, 0, 1)
+    Q, sc, B = W.draw_q(w, 0, 1), W.draw_scorer(w, 1), W.draw_budgets(w, T, 0, 1)
+    run = G.GpuRun(ctx, [K], [V], [Q], sc, [B], w.Hq)
+    run.run_all()
+    G.check_against_oracle(run, [K], [V], [Q], sc, [B], "eager")
+    want = {k: getattr(run, k).clone() for k in ("idx", "offsets", "kp", "vp", "out", "lse")}
+    want_scores = run.scores[0].clone()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        run.score(); run.select(); run.compact(); run.decode()      # warm-up on the capture stream
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            run.score(); run.select(); run.compact(); run.decode()
+    torch.cuda.synchronize()
+    for rep in range(4):
+        # eager work between replays: scribble over every output, then replay
+        for k in want:
+            getattr(run, k).fill_(-3 if getattr(run, k).dtype == torch.int32 else float("nan"))
+        run.scores[0].fill_(float("nan"))
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.scores[0], want_scores), f"replay {rep}: scores"
+        for k in ("idx", "offsets"):
+            assert torch.equal(getattr(run, k), want[k]), f"replay {rep}: {k}"
+        for k in ("kp", "vp"):
+            assert torch.equal(getattr(run, k).view(torch.int16), want[k].view(torch.int16)), f"replay {rep}: {k}"
+        for k in ("out", "lse"):
+            assert torch.equal(getattr(run, k), want[k]), f"replay {rep}: {k}"
