@@ -18,13 +18,14 @@ constexpr int kActGelu = 1;
 __device__ __forceinline__ float gelu_erf(float z) {
   const float az = fabsf(z);
   const float t = __builtin_amdgcn_rcpf(fmaf(0.3275911f * 0.70710678118654752f, az, 1.0f));
-  float p = fmaf(1.061405429f, t, -1.453152027f);
-  p = fmaf(p, t, 1.421413741f);
-  p = fmaf(p, t, -0.284496736f);
-  p = fmaf(p, t, 0.254829592f);
+  // -poly(t) / 2: the factor of the last line is folded into the coefficients
+  float p = fmaf(-0.5f * 1.061405429f, t, 0.5f * 1.453152027f);
+  p = fmaf(p, t, -0.5f * 1.421413741f);
+  p = fmaf(p, t, 0.5f * 0.284496736f);
+  p = fmaf(p, t, -0.5f * 0.254829592f);
   p *= t;
   const float e = __builtin_amdgcn_exp2f((z * z) * (-0.5f * 1.4426950408889634f));   // exp(-z^2 / 2)
-  return fmaf(-0.5f * az, p * e, fmaxf(z, 0.f));
+  return fmaf(az, p * e, fmaxf(z, 0.f));
 }
 
 template <int kAct>
