@@ -191,6 +191,22 @@ def test_append_several_sequences_many_tokens(ctx):
     g.decode_and_check("40 tokens")
 
 
+def test_growth_with_more_sequences_than_one_launch_table_holds(ctx):
+    rng = np.random.default_rng(40)
+    Ts = [int(t) for t in rng.integers(30, 300, size=40)]
+    w = W.scaled(W.CONFIGS[0], n_seq=40, L=1, H=2, Hq=4, b_min=2)
+    g = Grown(ctx, w, Ts, 8, slack=3)
+    g.assert_state_matches("40 sequences")
+    for kn, vn in _new_tokens(w, 40, 3, 8):
+        g.append(kn, vn)
+    g.assert_state_matches("40 sequences, 3 tokens")
+    g.decode_and_check("40 sequences")
+    lengths = np.concatenate([o[4] for o in g.oracle])
+    g.reevict(lengths // 2, slack=2)
+    g.assert_state_matches("40 sequences, re-evicted")
+    g.decode_and_check("40 sequences, re-evicted")
+
+
 def test_append_spanning_many_decode_chunks(ctx):
     # long enough that segments are split over several blocks of the decode kernel and some
     # blocks see only spare rows

@@ -60,6 +60,16 @@ def test_several_sequences_of_different_length(ctx):
     _run_and_check(ctx, w, [100, 1000, 5000], what="multi-seq")
 
 
+@pytest.mark.parametrize("scorer,hidden", [("linear", 0), ("mlp", 32)])
+def test_more_sequences_than_one_launch_table_holds(ctx, scorer, hidden):
+    # a launch table describes up to 32 sequences: 70 of them take three launches of every kernel
+    rng = np.random.default_rng(70)
+    Ts = [int(t) for t in rng.integers(20, 400, size=70)]
+    Ts[5], Ts[40] = 5000, 17            # mixed tile sizes of the MLP scorer inside one call
+    w = W.scaled(W.CONFIGS[0], n_seq=70, L=1, H=2, Hq=4, scorer=scorer, hidden=hidden, act="gelu", b_min=2)
+    _run_and_check(ctx, w, Ts, seed=4, what="70 sequences")
+
+
 @pytest.mark.parametrize("g", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_gqa_group_sizes(ctx, g):
     w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=2 * g, T=1500, b_min=16)
