@@ -152,13 +152,13 @@ lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* sco
     lkv::SeqTable tab;
     memset(&tab, 0, sizeof(tab));
     int64_t blocks = 0;
-    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s], (int)heads) : 0;
+    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s], (int)heads, scorer->hidden) : 0;
     int n = 0;
     while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
       const int T = cache->seq_len[s];
       int64_t per_head;
       if (scorer->kind == LKV_SCORER_MLP) {
-        if (lkv::score_mlp_rows_per_block(T, (int)heads) != rpb0) break;
+        if (lkv::score_mlp_rows_per_block(T, (int)heads, scorer->hidden) != rpb0) break;
         per_head = (T + rpb0 - 1) / rpb0;
       } else {
         per_head = lkv::score_linear_blocks_per_head(T);

@@ -15,7 +15,7 @@ hipError_t score_mlp_prepare();
 void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
                       const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
                       hipStream_t stream);
-int score_mlp_rows_per_block(int T, int heads);
+int score_mlp_rows_per_block(int T, int heads, int hidden);
 
 // select.hip
 hipError_t select_prepare();

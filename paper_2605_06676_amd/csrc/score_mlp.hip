@@ -320,13 +320,15 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   store_tile(last, held);
 }
 
-int score_mlp_rows_per_block(int T, int heads) {
-  // large tiles amortise the 32 KB of W1 each wave loads; short heads, and launches over few
-  // heads (one layer at a time), take smaller tiles so that the grid still covers the chip
+int score_mlp_rows_per_block(int T, int heads, int hidden) {
+  // large tiles amortise the W1 fragments each wave loads; short heads, and launches over few
+  // heads (one layer at a time), take smaller tiles so that the grid still covers the chip.
+  // The wave-pair kernel has twice as many resident blocks, so half the rows give it as many rounds.
 #ifdef LKV_MLP_ROWS
   if (T >= 16384) return LKV_MLP_ROWS;
 #endif
-  int rows = T >= 16384 ? 2048 : (T >= 4096 ? 1024 : 256);
+  const int longest = hidden > 64 ? 2048 : 4096;
+  int rows = T >= 16384 ? longest : (T >= 4096 ? 1024 : 256);
   while (rows > 256 && (int64_t)heads * ((T + rows - 1) / rows) < 1024) rows >>= 1;
   return rows;
 }
