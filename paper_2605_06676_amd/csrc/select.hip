@@ -380,8 +380,9 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
     constexpr int kClsBatch = 4;
     for (int chunk0 = 0; chunk0 < T; chunk0 += 32 * kSelThreads) {   // one pass for every length the cache holds up to 32768
       uint32_t my_gt = 0, my_eq = 0;
+      const int rounds = min(32, (T - chunk0 + kSelThreads - 1) / kSelThreads);   // short heads need fewer
 #pragma unroll 1
-      for (int kk = 0; kk < 32; kk += kClsBatch) {
+      for (int kk = 0; kk < rounds; kk += kClsBatch) {
         uint32_t kb[kClsBatch];
 #pragma unroll
         for (int k = 0; k < kClsBatch; ++k) {
