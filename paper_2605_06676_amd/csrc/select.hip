@@ -16,21 +16,25 @@
 //      this ordered scan; no atomic decides a position, so the result is unique
 //      and reproducible bit for bit.
 // Where the keys live depends on the head length T:
-//   * T <= 34304: the keys are cached in LDS by one batched read of the scores;
-//     the histogram passes and the classification read LDS.
-//   * T <= 589824: too long for LDS.  The three histogram passes and the
-//     classification pass re-read the scores (they sit in L2 / the memory-side
-//     cache right after scoring) with batched 16-byte loads.
-//   In both cases every token is classified against `thr` into two LDS bitmaps
-//   (greater / equal) and the ordered emission runs on the bitmaps, 1024 tokens
-//   per wave step: every lane expands its 16 bits into the wave's LDS staging
-//   buffer at the position given by a prefix count, then the wave copies the
-//   staged indices out with fully coalesced stores.
-//   * T <= 327680 is the limit for this; longer heads re-read the scores in
-//     order during emission, 64 tokens a step.
-// All global reads are issued eight at a time per thread before any is used:
-// the kernel is latency-bound, not bandwidth-bound, so what counts is how few
-// dependent round trips each pass makes.
+//   * T <= 34304: the keys are cached in LDS by one batched read of the scores (the first
+//     level's histogram is counted on the way in); the later passes and the classification
+//     read LDS, eight keys at a time.
+//   * longer heads do not fit.  The first level reads the scores from memory (they sit in L2 /
+//     the memory-side cache right after scoring).  A second read settles every token outside
+//     the one undecided bin and lists the tokens inside it (up to 16384 indices, in the LDS the
+//     emission stages through later); the last two levels and the final comparison touch the
+//     listed tokens only.  If more tokens than that share the bin, all three levels and the
+//     classification re-read the scores instead.
+//   In every case each token is classified against `thr` into two LDS bitmaps (greater / equal)
+//   and the ordered emission runs on the bitmaps, 1024 tokens per wave step: every lane expands
+//   its 16 bits into the wave's LDS staging buffer at the position given by a prefix count, then
+//   the wave copies the staged indices out with fully coalesced stores.
+//   * T <= 327680 is the limit for the bitmaps; longer heads re-read the scores in order during
+//     emission, 64 tokens a step.
+// All global reads are issued eight at a time per thread before any is used: the kernel is
+// latency-bound, not bandwidth-bound, so what counts is how few dependent round trips each pass
+// makes.  A launch can also rank ragged pieces of one flat score array (the re-eviction of a
+// packed cache) instead of the heads of a [L, H, T] tensor.
 #include "lkv_common.h"
 
 namespace lkv {
