@@ -1,13 +1,18 @@
 /*
  * lkv.h -- C ABI of the MI355X (gfx950) implementation of LKV's inference-time
  * KV-cache eviction path: token scoring, head-wise budgeted top-k, compaction
- * into a padding-free ragged cache, and GQA decode attention over that cache.
+ * into a padding-free ragged cache, and GQA decode attention over that cache
+ * (lkv_score, lkv_select, lkv_compact, lkv_decode_attn); further down, the same
+ * path one layer at a time during prefill, the growth of the packed cache
+ * during decoding with re-eviction, attention with a multiplicative mask over
+ * the uncompacted cache, and the LKV-H budget allocation with the forward
+ * Soft-TopK operator.
  *
  * General conventions
  * -------------------
  * Memory.   Every pointer is marked HOST or DEVICE.  All device buffers are
- *           allocated, owned and freed by the caller; the library allocates no
- *           device memory inside the four hot calls.  The context owns only a
+ *           allocated, owned and freed by the caller; no call allocates device
+ *           memory.  The context owns only a
  *           small ring of pinned host staging buffers.  Device pointers must be
  *           16-byte aligned.
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
