@@ -189,3 +189,12 @@ def test_hard_topk_is_the_zero_temperature_limit_of_soft_topk(seed):
     mask = np.zeros(T); mask[O.select(u, b)] = 1.0
     assert np.array_equal(np.round(soft), mask)
     assert soft.sum() == pytest.approx(b, rel=1e-9)
+
+
+def test_total_budget_is_a_floor():
+    # B_total = floor(R L H t), Sec. 3.1: products that are not integers must round down
+    assert O.total_budget(0.15, 32, 8, 32768) == 1258291          # 1258291.2
+    assert O.total_budget(0.15, 32, 8, 1001) == 38438              # 38438.4
+    assert O.total_budget(0.10, 32, 8, 131072) == 3355443          # 3355443.2
+    assert O.total_budget(0.5, 1, 1, 7) == 3                       # 3.5
+    assert np.array_equal(O.integer_budgets(np.array([0.5, 0.999, 0.25]), 7), [3, 6, 1])
