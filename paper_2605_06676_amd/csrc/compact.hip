@@ -66,7 +66,9 @@ compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __r
       live[u] = p < row_hi;
       p = live[u] ? p : row_hi - 1;
       int s = s0;
-      while ((int64_t)offsets[s + 1] <= p) ++s;     // skips empty segments too; p < offsets[n_segments]
+      // skips empty segments too; p < offsets[n_segments] when total_kept matches the table, and the
+      // walk stops at the last segment when it does not
+      while (s + 1 < n_segments && (int64_t)offsets[s + 1] <= p) ++s;
       dst[u] = kMode == kCompactPlain ? p : p + (int64_t)grow.slack * s;
       if (kMode == kCompactGrowPacked) {
         // a row index outside the old segment cannot come from the selection; clamped, never followed

@@ -72,7 +72,7 @@ __device__ __forceinline__ int wave_upper_segment(const int32_t* __restrict__ ta
     const int step = (len + 63) >> 6;
     const int i = lo + lane * step;
     const bool le = i < lo + len && (int64_t)table[i] <= p;
-    const int cnt = __popcll(__ballot(le));   // >= 1 because table[lo] <= p
+    const int cnt = max(1, __popcll(__ballot(le)));   // table[lo] <= p in a well-formed table; never steps below lo
     const int new_lo = lo + (cnt - 1) * step;
     len = min(step, lo + len - new_lo);
     lo = new_lo;
