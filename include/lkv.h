@@ -269,6 +269,23 @@ lkv_status lkv_masked_decode_attn(lkv_ctx *ctx, const lkv_cache *cache, const vo
                                   const float *const *mask, float scale, float *out, float *lse,
                                   void *workspace, size_t workspace_bytes, void *stream);
 
+/* ---- Training-time attention with the multiplicative soft mask (Sec. 3.5, App. B) ---------
+ * Causal self-attention of one layer of one sequence, every token a query:
+ *   p_ij = e^{s_ij} m_j / sum_{k <= i} e^{s_ik} m_k,  s_ij = scale * q_i . k_j,  o_i = sum_{j <= i} p_ij v_j.
+ * The mask multiplies the exponentials inside the online softmax (App. B.2); no log m is taken,
+ * so m_j = 0 is an ordinary value.  Query head hq reads KV head hq / (n_q_heads / n_kv_heads) and
+ * that head's mask (Sec. 3.1).
+ * q   : DEVICE bf16 [n_q_heads, seq_len, d]        k, v : DEVICE bf16 [n_kv_heads, seq_len, d]
+ * m   : DEVICE fp32 [n_kv_heads, seq_len], values in [0, 1]
+ * o   : DEVICE bf16 [n_q_heads, seq_len, d]
+ * lse : DEVICE fp32 [n_q_heads, seq_len] = log sum_{k <= i} e^{s_ik} m_k (needed by the backward pass)
+ * A query whose whole prefix has weight 0 gets o = 0 and lse = -inf.
+ * q, k, v, o 16-byte aligned; head_dim must be 128; scale > 0; n_q_heads <= 65535.
+ * Errors: LKV_ERR_INVALID_ARG / LKV_ERR_UNSUPPORTED before anything is enqueued. */
+lkv_status lkv_masked_attn_forward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
+                                   int32_t head_dim, const void *q, const void *k, const void *v,
+                                   const float *m, float scale, void *o, float *lse, void *stream);
+
 /* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
 
 /* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):

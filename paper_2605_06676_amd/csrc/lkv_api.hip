@@ -647,6 +647,25 @@ lkv_status lkv_masked_decode_attn(lkv_ctx* ctx, const lkv_cache* cache, const vo
   return LKV_OK;
 }
 
+lkv_status lkv_masked_attn_forward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
+                                   int32_t head_dim, const void* q, const void* k, const void* v, const float* m,
+                                   float scale, void* o, float* lse, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
+  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  if (n_q_heads > 65535) return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads = %d exceeds 65535", n_q_heads);
+  if (!(scale > 0.f) || std::isinf(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale = %g must be positive and finite", (double)scale);
+  if (q == nullptr || k == nullptr || v == nullptr || m == nullptr || o == nullptr || lse == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v, m, o or lse is NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v or o is not 16-byte aligned");
+  lkv::launch_masked_attn_fwd(q, k, v, m, n_q_heads, n_kv_heads, seq_len, scale, o, lse, as_stream(stream));
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_masked_attn_forward launch");
+  return LKV_OK;
+}
+
 int32_t lkv_soft_topk_max_n(int32_t x_is_f64) { return lkv::soft_topk_max_n(x_is_f64 != 0); }
 
 lkv_status lkv_soft_topk(lkv_ctx* ctx, const void* x, int32_t x_is_f64, int32_t n, double k, double tau, double* y,

@@ -54,6 +54,10 @@ hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, c
                          hipStream_t stream, const float* mask = nullptr);
 void launch_uniform_offsets(int n_segments, int len, int32_t* offsets, hipStream_t stream);
 
+// masked_attn.hip
+void launch_masked_attn_fwd(const void* q, const void* k, const void* v, const float* m, int n_q_heads, int n_kv_heads,
+                            int T, float scale, void* o, float* lse, hipStream_t stream);
+
 // lkv_h.hip
 hipError_t lkv_h_prepare();
 int soft_topk_max_n(bool is_f64);

@@ -30,6 +30,11 @@ Recipe
   3.3); every head gets ``b_min`` and floor(p_h * rest) of what remains, with
   water-filling when a head would exceed T.  Hence b_min <= b <= T and
   sum(b) <= B_total.
+* Training-time attention (``draw_training_attention``): q, k, v, dO i.i.d. N(0,1) in bf16 (one
+  layer of one sequence; the paper trains on 2k-16k token samples of its own corpus, App. C.2,
+  which is not available); soft mask m = x^4 with x ~ U(0,1) (mean 0.2, most weights small, as
+  late in the annealing of Sec. 3.4), 10 % of the weights set to exactly 0 and 5 % to exactly 1,
+  the first key of every head kept above 0.25 so that every causal prefix carries weight.
 * Sub-streams are keyed by (seed, config id, tensor tag, sequence, layer) so
   that any single layer can be regenerated on its own.
 """
@@ -43,7 +48,7 @@ import numpy as np
 
 D_HEAD = 128
 
-_TAGS = {"kv": 1, "q": 2, "scorer": 3, "budget": 4, "seqlen": 5, "chan": 6, "noise": 7, "headpred": 8}
+_TAGS = {"kv": 1, "q": 2, "scorer": 3, "budget": 4, "seqlen": 5, "chan": 6, "noise": 7, "headpred": 8, "train": 9}
 
 
 @dataclasses.dataclass(frozen=True)
@@ -253,6 +258,23 @@ def draw_q(w: Workload, seq: int = 0, seed: int = 0) -> np.ndarray:
 # --------------------------------------------------------------------------
 # device-side draws for the full-size workloads (torch is plumbing here)
 # --------------------------------------------------------------------------
+
+
+def draw_training_attention(Hq: int, H: int, T: int, seed: int = 0, d: int = D_HEAD):
+    """Inputs of one layer of training-time attention: bf16 bit patterns q, dO [Hq, T, d],
+    k, v [H, T, d] and the fp32 soft mask m [H, T] (see the recipe above)."""
+    rng = _rng(seed, 100, "train", Hq * 1000 + H, T)
+    q = f32_to_bf16_bits(rng.standard_normal((Hq, T, d), dtype=np.float32))
+    k = f32_to_bf16_bits(rng.standard_normal((H, T, d), dtype=np.float32))
+    v = f32_to_bf16_bits(rng.standard_normal((H, T, d), dtype=np.float32))
+    d_o = f32_to_bf16_bits(rng.standard_normal((Hq, T, d), dtype=np.float32))
+    x = rng.uniform(size=(H, T)).astype(np.float32)
+    m = (x * x) * (x * x)
+    pick = rng.uniform(size=(H, T))
+    m[pick < 0.10] = 0.0
+    m[pick > 0.95] = 1.0
+    m[:, 0] = np.maximum(m[:, 0], np.float32(0.25))
+    return q, k, v, m.astype(np.float32), d_o
 
 
 def device_kv(w: Workload, T: int, seq: int, device, seed: int = 0):
