@@ -98,7 +98,8 @@ lkv_status lkv_create(lkv_ctx** out, int device) {
     }
   }
   if (lkv::select_prepare() != hipSuccess || lkv::decode_prepare() != hipSuccess ||
-      lkv::score_mlp_prepare() != hipSuccess || lkv::lkv_h_prepare() != hipSuccess) {
+      lkv::score_mlp_prepare() != hipSuccess || lkv::lkv_h_prepare() != hipSuccess ||
+      lkv::masked_attn_prepare() != hipSuccess) {
     lkv_destroy(ctx);
     return LKV_ERR_HIP;
   }

@@ -55,6 +55,7 @@ hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, c
 void launch_uniform_offsets(int n_segments, int len, int32_t* offsets, hipStream_t stream);
 
 // masked_attn.hip
+hipError_t masked_attn_prepare();
 void launch_masked_attn_fwd(const void* q, const void* k, const void* v, const float* m, int n_q_heads, int n_kv_heads,
                             int T, float scale, void* o, float* lse, hipStream_t stream);
 

@@ -20,6 +20,8 @@
 // half) is the A-operand layout of P for one K-step over the 32 keys, so probabilities go from
 // the first product to the second without leaving their lanes.  Each K and V operand read is
 // shared by the kQB query blocks of the wave.
+#include <type_traits>
+
 #include "lkv_common.h"
 #include "lkv_kernels.h"
 
@@ -57,14 +59,17 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 }  // namespace
 
-template <int kQB>
+template <int kQB, int kSteps>
 __global__ void __launch_bounds__(kMaThreads, kQB >= 4 ? 1 : 2)
 masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ k, const uint4* __restrict__ v,
                        const float* __restrict__ m, int T, int G, float scale, uint16_t* __restrict__ o,
                        float* __restrict__ lse) {
-  __shared__ __align__(16) unsigned char smem[2 * kMaTileLds];
+  extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveQ = 16 * kQB;
   constexpr int kBlockQ = kMaWaves * kWaveQ;
+  constexpr int kTileKeys = kMaKeys * kSteps;          // keys staged per barrier
+  constexpr int kTileLds = kSteps * kMaTileLds;
+  constexpr int kStage = kTileKeys / 16;               // staged rows per thread and tensor
   const int n_qtiles = (T + kBlockQ - 1) / kBlockQ;
   const int qtile = n_qtiles - 1 - (int)blockIdx.x;    // the longest rows of the causal triangle start first
   const int hq = blockIdx.y;
@@ -76,20 +81,18 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
   const int c = lane & 15;
   const int q0 = qtile * kBlockQ;
   const int qw0 = q0 + wave * kWaveQ;                  // first query of this wave
-  const int n_tiles = (min(q0 + kBlockQ, T) + kMaKeys - 1) / kMaKeys;
+  const int n_tiles = (min(q0 + kBlockQ, T) + kTileKeys - 1) / kTileKeys;
   const float qscale = scale * kMaLog2e;
 
   // B operand of the first product: Q^T, lane (query c of block qb, K-block r) holds q[query][32 ks + 8 r .. +7]
   bf16x8_t qfrag[kQB][4];
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
-    const int query = qw0 + 16 * qb + c;
+    const int query = min(qw0 + 16 * qb + c, T - 1);   // queries past the end repeat the last one; never stored
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      uint4 x = make_uint4(0, 0, 0, 0);
-      if (query < T) x = reinterpret_cast<const uint4*>(q + ((size_t)hq * T + query) * kHeadDim)[ks * 4 + r];
-      qfrag[qb][ks] = __builtin_bit_cast(bf16x8_t, x);
-    }
+    for (int ks = 0; ks < 4; ++ks)
+      qfrag[qb][ks] = __builtin_bit_cast(
+          bf16x8_t, reinterpret_cast<const uint4*>(q + ((size_t)hq * T + query) * kHeadDim)[ks * 4 + r]);
   }
   float m_run[kQB], l_run[kQB];     // per query c of block qb: running maximum (log2 domain), this lane's share of the denominator
   f32x4_t acc_o[kQB][8];            // O[query 4 r + e of block qb][channel 16 ct + c]
@@ -101,121 +104,153 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
     for (int ct = 0; ct < 8; ++ct) acc_o[qb][ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
 
-  // staging: thread (row slot tid / 16, piece tid % 16) moves rows slot and slot + 16 of the tile
+  // staging: thread (row slot tid / 16, piece tid % 16) moves rows slot, slot + 16, ... of the tile.
+  // The registers are loaded unconditionally (an array assigned under a condition ends up in scratch memory).
   const uint4* kh = k + (size_t)h * T * kChunksPerRow;
   const uint4* vh = v + (size_t)h * T * kChunksPerRow;
   const float* mh = m + (size_t)h * T;
   const int srow = tid >> 4, spiece = tid & 15;
-  // named registers, loaded unconditionally: an array that is assigned under a condition ends up in scratch memory
-  uint4 k_a, k_b, v_a, v_b;
+  // Named registers: as arrays these ended up in scratch memory, which also serialised the loads.
+  static_assert(kStage == 4, "the staging registers below are written out for 64-key tiles");
+  uint4 k_s0, k_s1, k_s2, k_s3, v_s0, v_s1, v_s2, v_s3;
   float mk;
-  auto load_tile = [&](int t) {
-    const int key_a = min(t * kMaKeys + srow, T - 1);        // rows past the end re-read the last row; never used
-    const int key_b = min(t * kMaKeys + srow + 16, T - 1);
-    k_a = kh[(size_t)key_a * kChunksPerRow + spiece];
-    k_b = kh[(size_t)key_b * kChunksPerRow + spiece];
-    v_a = vh[(size_t)key_a * kChunksPerRow + spiece];
-    v_b = vh[(size_t)key_b * kChunksPerRow + spiece];
-    mk = mh[min(t * kMaKeys + (tid & (kMaKeys - 1)), T - 1)];
-  };
-  load_tile(0);
+#define LKV_MA_LOAD_ROW(j_, kreg_, vreg_, t_)                                                                 \
+  {                                                                                                           \
+    const int key = min((t_) * kTileKeys + srow + 16 * (j_), T - 1); /* past the end: the last row, unused */ \
+    kreg_ = kh[(size_t)key * kChunksPerRow + spiece];                                                         \
+    vreg_ = vh[(size_t)key * kChunksPerRow + spiece];                                                         \
+  }
+#define LKV_MA_LOAD_TILE(t_)                                            \
+  {                                                                     \
+    LKV_MA_LOAD_ROW(0, k_s0, v_s0, t_)                                  \
+    LKV_MA_LOAD_ROW(1, k_s1, v_s1, t_)                                  \
+    LKV_MA_LOAD_ROW(2, k_s2, v_s2, t_)                                  \
+    LKV_MA_LOAD_ROW(3, k_s3, v_s3, t_)                                  \
+    mk = mh[min((t_) * kTileKeys + (tid & (kTileKeys - 1)), T - 1)];    \
+  }
+#define LKV_MA_STORE_ROW(j_, kreg_, vreg_)                                                                     \
+  {                                                                                                            \
+    unsigned char* step_buf = buf + ((j_) >> 1) * kMaTileLds;                                                  \
+    const int row = srow + 16 * ((j_) & 1);                                                                    \
+    *reinterpret_cast<uint4*>(step_buf + row * kMaKStride + spiece * 16) = kreg_;                              \
+    *reinterpret_cast<uint4*>(step_buf + kMaKeys * kMaKStride + row * kMaVStride + spiece * 16) = vreg_;       \
+  }
+  LKV_MA_LOAD_TILE(0)
 
 #pragma unroll 1
   for (int t = 0; t < n_tiles; ++t) {
-    unsigned char* k_lds = smem + (t & 1) * kMaTileLds;
-    unsigned char* v_lds = k_lds + kMaKeys * kMaKStride;
-    float* m_lds = reinterpret_cast<float*>(v_lds + kMaKeys * kMaVStride);
-    *reinterpret_cast<uint4*>(k_lds + srow * kMaKStride + spiece * 16) = k_a;
-    *reinterpret_cast<uint4*>(k_lds + (srow + 16) * kMaKStride + spiece * 16) = k_b;
-    *reinterpret_cast<uint4*>(v_lds + srow * kMaVStride + spiece * 16) = v_a;
-    *reinterpret_cast<uint4*>(v_lds + (srow + 16) * kMaVStride + spiece * 16) = v_b;
-    if (tid < kMaKeys) m_lds[tid] = mk;
-    load_tile(min(t + 1, n_tiles - 1));   // the last iteration re-reads its own tile: no branch around the loads
+    // row 32 s + i of the tile lives in step buffer s: K rows, V rows, then the 32 mask weights
+    unsigned char* buf = smem + (t & 1) * kTileLds;
+    LKV_MA_STORE_ROW(0, k_s0, v_s0)
+    LKV_MA_STORE_ROW(1, k_s1, v_s1)
+    LKV_MA_STORE_ROW(2, k_s2, v_s2)
+    LKV_MA_STORE_ROW(3, k_s3, v_s3)
+    if (tid < kTileKeys)
+      reinterpret_cast<float*>(buf + (tid >> 5) * kMaTileLds + kMaKeys * (kMaKStride + kMaVStride))[tid & 31] = mk;
+    LKV_MA_LOAD_TILE(min(t + 1, n_tiles - 1))   // the last iteration re-reads its own tile: no branch around the loads
     // One barrier per tile is enough with two buffers: a wave that runs ahead writes the other
     // buffer, and it cannot come back to this one before every wave has passed the next barrier.
     __syncthreads();
-    const int key0 = t * kMaKeys;
-    if (key0 > qw0 + kWaveQ - 1 || qw0 >= T) continue;   // wave-uniform: the tile lies wholly above this wave's diagonal
+    const int key0 = t * kTileKeys;
+    // wave-uniform: nothing to do when the tile lies wholly above this wave's diagonal
+    if (key0 <= qw0 + kWaveQ - 1 && qw0 < T) {
 
-    // S^T for the two 16-key halves: lane (rb = r, query c) gets keys 16 tt + 4 r + e
-    f32x4_t sacc[kQB][2];
+    // S^T for the 16-key pieces of the tile: lane (rb = r, query c) gets keys 16 sub + 4 r + e
+    f32x4_t sacc[kQB][2 * kSteps];
 #pragma unroll
     for (int qb = 0; qb < kQB; ++qb)
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt) sacc[qb][tt] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+      for (int sub = 0; sub < 2 * kSteps; ++sub) sacc[qb][sub] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int tt = 0; tt < 2; ++tt)
+    for (int sub = 0; sub < 2 * kSteps; ++sub) {
+      const unsigned char* k_lds = buf + (sub >> 1) * kMaTileLds;
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
-        const uint4 kx = *reinterpret_cast<const uint4*>(k_lds + (tt * 16 + c) * kMaKStride + ks * 64 + r * 16);
+        const uint4 kx = *reinterpret_cast<const uint4*>(k_lds + ((sub & 1) * 16 + c) * kMaKStride + ks * 64 + r * 16);
 #pragma unroll
         for (int qb = 0; qb < kQB; ++qb)
-          sacc[qb][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx), qfrag[qb][ks],
-                                                                 sacc[qb][tt], 0, 0, 0);
+          sacc[qb][sub] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, kx), qfrag[qb][ks],
+                                                                  sacc[qb][sub], 0, 0, 0);
       }
-    // the mask weights of this lane's eight keys
-    float mw[8];
-#pragma unroll
-    for (int tt = 0; tt < 2; ++tt) {
-      const float4 x = *reinterpret_cast<const float4*>(m_lds + 16 * tt + 4 * r);
-      mw[tt * 4 + 0] = x.x; mw[tt * 4 + 1] = x.y; mw[tt * 4 + 2] = x.z; mw[tt * 4 + 3] = x.w;
     }
-    const bool diagonal = key0 + kMaKeys - 1 > qw0;   // wave-uniform: some (query, key) pair of the tile has key > query
 
-    bf16x8_t pfrag[kQB];
+    bf16x8_t pfrag[kQB][kSteps];
+    // online softmax of one query block over the tile; kDiag: some key of the tile lies above some query's diagonal
+    auto softmax = [&](auto diag_tag) {
+      constexpr bool kDiag = decltype(diag_tag)::value;
 #pragma unroll
-    for (int qb = 0; qb < kQB; ++qb) {
-      const int query = qw0 + 16 * qb + c;
-      float sv[8];
-      float mx = -INFINITY;
+      for (int qb = 0; qb < kQB; ++qb) {
+        const int query = qw0 + 16 * qb + c;
+        float sv[8 * kSteps];
+        float mx = -INFINITY;
 #pragma unroll
-      for (int tt = 0; tt < 2; ++tt)
+        for (int sub = 0; sub < 2 * kSteps; ++sub)
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          float s = sacc[qb][tt][e];
-          if (diagonal) s = key0 + 16 * tt + 4 * r + e <= query ? s : -INFINITY;
-          sv[tt * 4 + e] = s;
-          mx = fmaxf(mx, s);
+          for (int e = 0; e < 4; ++e) {
+            const float s = sacc[qb][sub][e];
+            sv[4 * sub + e] = kDiag && key0 + 16 * sub + 4 * r + e > query ? -INFINITY : s;
+            mx = fmaxf(mx, sv[4 * sub + e]);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = fmaxf(m_run[qb], mx * qscale);              // qscale > 0: scaling commutes with the maximum
+        const float ref = mx == -INFINITY ? 0.f : mx;
+        const float alpha = ma_exp2(m_run[qb] - ref);    // exp2(-inf) = 0 on the first tile
+        m_run[qb] = mx;
+        float psum = 0.f;
+#pragma unroll
+        for (int st = 0; st < kSteps; ++st) {
+          const float* m_lds = reinterpret_cast<const float*>(buf + st * kMaTileLds + kMaKeys * (kMaKStride + kMaVStride));
+#pragma unroll
+          for (int tt = 0; tt < 2; ++tt) {
+            const float4 mw4 = *reinterpret_cast<const float4*>(m_lds + 16 * tt + 4 * r);
+            const float mw[4] = {mw4.x, mw4.y, mw4.z, mw4.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              // the mask multiplies the exponential (App. B.2)
+              const float p = ma_exp2(fmaf(sv[8 * st + 4 * tt + e], qscale, -ref)) * mw[e];
+              psum += p;
+              pfrag[qb][st][tt * 4 + e] = (__bf16)p;
+            }
+          }
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      mx = fmaxf(m_run[qb], mx * qscale);              // qscale > 0: scaling commutes with the maximum
-      const float ref = mx == -INFINITY ? 0.f : mx;
-      const float alpha = ma_exp2(m_run[qb] - ref);    // exp2(-inf) = 0 on the first tile
-      m_run[qb] = mx;
-      float psum = 0.f;
+        l_run[qb] = l_run[qb] * alpha + psum;
+        // rescale the output rows (queries 4 r + e) when any running maximum of the block moved
+        if (__ballot(alpha != 1.f) != 0ull) {
+          float al[4];
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        sv[i] = ma_exp2(fmaf(sv[i], qscale, -ref)) * mw[i];   // the mask multiplies the exponential (App. B.2)
-        psum += sv[i];
+          for (int e = 0; e < 4; ++e) al[e] = __shfl(alpha, 4 * r + e, 64);
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc_o[qb][ct][e] *= al[e];
+        }
       }
-      l_run[qb] = l_run[qb] * alpha + psum;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) pfrag[qb][i] = (__bf16)sv[i];
-      // rescale the output rows (queries 4 r + e) when any running maximum of the block moved
-      if (__ballot(alpha != 1.f) != 0ull) {
-        float al[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) al[e] = __shfl(alpha, 4 * r + e, 64);
-#pragma unroll
-        for (int ct = 0; ct < 8; ++ct)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc_o[qb][ct][e] *= al[e];
-      }
-    }
+    };
+    if (key0 + kTileKeys - 1 > qw0) softmax(std::true_type{});   // wave-uniform
+    else softmax(std::false_type{});
+
     // O += P V: B operand lane (channel c of tile ct, K-block r) holds V[keys 4r..4r+3 and 16+4r..16+4r+3][channel]
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct) {
-      const unsigned char* base = v_lds + (4 * r + (c >> 2)) * kMaVStride + ct * 32 + (c & 3) * 8;
-      const s16x4_t v0 = ma_read_tr16(base);
-      const s16x4_t v1 = ma_read_tr16(base + 16 * kMaVStride);
-      const s16x8_t vb = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+    for (int st = 0; st < kSteps; ++st) {
+      const unsigned char* v_lds = buf + st * kMaTileLds + kMaKeys * kMaKStride;
 #pragma unroll
-      for (int qb = 0; qb < kQB; ++qb)
-        acc_o[qb][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pfrag[qb], __builtin_bit_cast(bf16x8_t, vb),
-                                                                acc_o[qb][ct], 0, 0, 0);
+      for (int ct = 0; ct < 8; ++ct) {
+        const unsigned char* base = v_lds + (4 * r + (c >> 2)) * kMaVStride + ct * 32 + (c & 3) * 8;
+        const s16x4_t v0 = ma_read_tr16(base);
+        const s16x4_t v1 = ma_read_tr16(base + 16 * kMaVStride);
+        const s16x8_t vb = __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int qb = 0; qb < kQB; ++qb)
+          acc_o[qb][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pfrag[qb][st], __builtin_bit_cast(bf16x8_t, vb),
+                                                                  acc_o[qb][ct], 0, 0, 0);
+      }
+    }
     }
   }
+#undef LKV_MA_LOAD_TILE
+#undef LKV_MA_LOAD_ROW
+#undef LKV_MA_STORE_ROW
 
   // normalise and store: lane (r, c) holds O[query 4 r + e][channels 16 ct + c]
 #pragma unroll
@@ -243,20 +278,20 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
   }
 }
 
-int masked_attn_block_queries(int T) { return T >= 8192 ? 256 : 128; }
+constexpr int kMaFwdSteps = 2;   // 64 keys per staged tile
+constexpr int kMaFwdLds = 2 * kMaFwdSteps * kMaTileLds;
+
+hipError_t masked_attn_prepare() {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(masked_attn_fwd_kernel<2, kMaFwdSteps>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kMaFwdLds);
+}
 
 void launch_masked_attn_fwd(const void* q, const void* k, const void* v, const float* m, int n_q_heads, int n_kv_heads,
                             int T, float scale, void* o, float* lse, hipStream_t stream) {
   const int G = n_q_heads / n_kv_heads;
-  if (masked_attn_block_queries(T) == 256) {
-    hipLaunchKernelGGL(masked_attn_fwd_kernel<4>, dim3((T + 255) / 256, n_q_heads), dim3(kMaThreads), 0, stream,
-                       static_cast<const uint16_t*>(q), static_cast<const uint4*>(k), static_cast<const uint4*>(v), m, T,
-                       G, scale, static_cast<uint16_t*>(o), lse);
-  } else {
-    hipLaunchKernelGGL(masked_attn_fwd_kernel<2>, dim3((T + 127) / 128, n_q_heads), dim3(kMaThreads), 0, stream,
-                       static_cast<const uint16_t*>(q), static_cast<const uint4*>(k), static_cast<const uint4*>(v), m, T,
-                       G, scale, static_cast<uint16_t*>(o), lse);
-  }
+  hipLaunchKernelGGL((masked_attn_fwd_kernel<2, kMaFwdSteps>), dim3((T + 127) / 128, n_q_heads), dim3(kMaThreads),
+                     kMaFwdLds, stream, static_cast<const uint16_t*>(q), static_cast<const uint4*>(k),
+                     static_cast<const uint4*>(v), m, T, G, scale, static_cast<uint16_t*>(o), lse);
 }
 
 }  // namespace lkv
