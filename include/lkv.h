@@ -277,14 +277,38 @@ lkv_status lkv_masked_decode_attn(lkv_ctx *ctx, const lkv_cache *cache, const vo
  * that head's mask (Sec. 3.1).
  * q   : DEVICE bf16 [n_q_heads, seq_len, d]        k, v : DEVICE bf16 [n_kv_heads, seq_len, d]
  * m   : DEVICE fp32 [n_kv_heads, seq_len], values in [0, 1]
- * o   : DEVICE bf16 [n_q_heads, seq_len, d]
+ * o   : DEVICE fp32 [n_q_heads, seq_len, d] (fp32 so that the backward pass forms D_i = d_o_i . o_i from
+ *       unrounded outputs: with a bf16 o the rounding of D dominates the gradient error of short prefixes)
  * lse : DEVICE fp32 [n_q_heads, seq_len] = log sum_{k <= i} e^{s_ik} m_k (needed by the backward pass)
  * A query whose whole prefix has weight 0 gets o = 0 and lse = -inf.
  * q, k, v, o 16-byte aligned; head_dim must be 128; scale > 0; n_q_heads <= 65535.
  * Errors: LKV_ERR_INVALID_ARG / LKV_ERR_UNSUPPORTED before anything is enqueued. */
 lkv_status lkv_masked_attn_forward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
                                    int32_t head_dim, const void *q, const void *k, const void *v,
-                                   const float *m, float scale, void *o, float *lse, void *stream);
+                                   const float *m, float scale, float *o, float *lse, void *stream);
+
+/* Backward pass of lkv_masked_attn_forward (App. B.3): gradients of a scalar loss given its
+ * gradient d_o with respect to o.  With e_ij = e^{s_ij - lse_i}, p_ij = e_ij m_j, dP_ij = d_o_i . v_j,
+ * D_i = d_o_i . o_i:
+ *   dv_j = sum_i p_ij d_o_i        dm_j = sum_i e_ij (dP_ij - D_i)        dS_ij = p_ij (dP_ij - D_i)
+ *   dq_i = scale sum_j dS_ij k_j   dk_j = scale sum_i dS_ij q_i
+ * over the causal pairs j <= i; dk, dv and dm also sum over the query heads that share the KV head.
+ * The factor towards the mask is e_ij, not 1 / m_j, so dm is finite where m_j = 0.  Queries with
+ * lse = -inf contribute nothing.
+ * q, k, v, m : as given to the forward call;  o, lse : as it returned them
+ * d_o : DEVICE bf16 [n_q_heads, seq_len, d]
+ * dq  : DEVICE fp32 [n_q_heads, seq_len, d];  dk, dv : DEVICE fp32 [n_kv_heads, seq_len, d]
+ * dm  : DEVICE fp32 [n_kv_heads, seq_len]
+ * workspace : DEVICE, at least lkv_masked_attn_backward_workspace_bytes(n_q_heads, seq_len) bytes,
+ *             16-byte aligned (holds D).
+ * Every output element is written exactly once (no atomics: results are reproducible bit for bit).
+ * Errors as for the forward call, plus LKV_ERR_WORKSPACE. */
+size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t seq_len);
+lkv_status lkv_masked_attn_backward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
+                                    int32_t head_dim, const void *q, const void *k, const void *v,
+                                    const float *m, const float *o, const float *lse, const void *d_o,
+                                    float scale, float *dq, float *dk, float *dv, float *dm,
+                                    void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---- LKV-H: global budget allocation, inference side (Sec. 3.3) ------------------------- */
 

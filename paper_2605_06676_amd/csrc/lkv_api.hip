@@ -99,7 +99,7 @@ lkv_status lkv_create(lkv_ctx** out, int device) {
   }
   if (lkv::select_prepare() != hipSuccess || lkv::decode_prepare() != hipSuccess ||
       lkv::score_mlp_prepare() != hipSuccess || lkv::lkv_h_prepare() != hipSuccess ||
-      lkv::masked_attn_prepare() != hipSuccess) {
+      lkv::masked_attn_prepare() != hipSuccess || lkv::masked_attn_bwd_prepare() != hipSuccess) {
     lkv_destroy(ctx);
     return LKV_ERR_HIP;
   }
@@ -650,7 +650,7 @@ lkv_status lkv_masked_decode_attn(lkv_ctx* ctx, const lkv_cache* cache, const vo
 
 lkv_status lkv_masked_attn_forward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
                                    int32_t head_dim, const void* q, const void* k, const void* v, const float* m,
-                                   float scale, void* o, float* lse, void* stream) {
+                                   float scale, float* o, float* lse, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1)
     return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
@@ -664,6 +664,39 @@ lkv_status lkv_masked_attn_forward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv
     return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v or o is not 16-byte aligned");
   lkv::launch_masked_attn_fwd(q, k, v, m, n_q_heads, n_kv_heads, seq_len, scale, o, lse, as_stream(stream));
   if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_masked_attn_forward launch");
+  return LKV_OK;
+}
+
+size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t seq_len) {
+  if (n_q_heads < 1 || seq_len < 1) return 0;
+  return lkv::masked_attn_bwd_workspace_bytes(n_q_heads, seq_len);
+}
+
+lkv_status lkv_masked_attn_backward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
+                                    int32_t head_dim, const void* q, const void* k, const void* v, const float* m,
+                                    const float* o, const float* lse, const void* d_o, float scale, float* dq, float* dk,
+                                    float* dv, float* dm, void* workspace, size_t workspace_bytes, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
+  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  if (n_q_heads > 65535) return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads = %d exceeds 65535", n_q_heads);
+  if ((int64_t)n_q_heads * seq_len >= ((int64_t)1 << 31) * 16)
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
+  if (!(scale > 0.f) || std::isinf(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale = %g must be positive and finite", (double)scale);
+  if (q == nullptr || k == nullptr || v == nullptr || m == nullptr || o == nullptr || lse == nullptr || d_o == nullptr ||
+      dq == nullptr || dk == nullptr || dv == nullptr || dm == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "an input or output pointer is NULL");
+  if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v, o or d_o is not 16-byte aligned");
+  const size_t need = lkv::masked_attn_bwd_workspace_bytes(n_q_heads, seq_len);
+  if (workspace == nullptr || workspace_bytes < need)
+    return fail(ctx, LKV_ERR_WORKSPACE, "masked attention backward workspace: need %zu bytes, got %zu", need, workspace_bytes);
+  if (!aligned16(workspace)) return fail(ctx, LKV_ERR_WORKSPACE, "masked attention backward workspace is not 16-byte aligned");
+  lkv::launch_masked_attn_bwd(q, k, v, m, o, lse, d_o, n_q_heads, n_kv_heads, seq_len, scale, dq, dk, dv, dm,
+                              static_cast<float*>(workspace), as_stream(stream));
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_masked_attn_backward launch");
   return LKV_OK;
 }
 

@@ -49,20 +49,12 @@ __device__ __forceinline__ s16x4_t ma_read_tr16(const unsigned char* p) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4_t*)(p));
 }
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2_t;
-  bf16x2_t v;
-  v[0] = (__bf16)lo;
-  v[1] = (__bf16)hi;
-  return __builtin_bit_cast(uint32_t, v);
-}
-
 }  // namespace
 
 template <int kQB, int kSteps>
 __global__ void __launch_bounds__(kMaThreads, kQB >= 4 ? 1 : 2)
 masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ k, const uint4* __restrict__ v,
-                       const float* __restrict__ m, int T, int G, float scale, uint16_t* __restrict__ o,
+                       const float* __restrict__ m, int T, int G, float scale, float* __restrict__ o,
                        float* __restrict__ lse) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveQ = 16 * kQB;
@@ -83,6 +75,9 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
   const int qw0 = q0 + wave * kWaveQ;                  // first query of this wave
   const int n_tiles = (min(q0 + kBlockQ, T) + kTileKeys - 1) / kTileKeys;
   const float qscale = scale * kMaLog2e;
+  bf16x8_t ones;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
 
   // B operand of the first product: Q^T, lane (query c of block qb, K-block r) holds q[query][32 ks + 8 r .. +7]
   bf16x8_t qfrag[kQB][4];
@@ -94,12 +89,19 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
       qfrag[qb][ks] = __builtin_bit_cast(
           bf16x8_t, reinterpret_cast<const uint4*>(q + ((size_t)hq * T + query) * kHeadDim)[ks * 4 + r]);
   }
-  float m_run[kQB], l_run[kQB];     // per query c of block qb: running maximum (log2 domain), this lane's share of the denominator
+  float m_run[kQB], l_run[kQB];     // per query c of block qb: running maximum (log2 domain), this lane's share of the
+                                    // unrounded denominator (for the log-normaliser that is returned)
   f32x4_t acc_o[kQB][8];            // O[query 4 r + e of block qb][channel 16 ct + c]
+  // Denominator the output is divided by, for query 4 r + e, the same in all 16 lanes of a row block: it is
+  // accumulated by the matrix cores as one more output column, P times a column of ones, hence from the same
+  // bf16-rounded weights as the output.  The output is then an exact convex combination of value rows, which keeps o (and the
+  // D_i = dO_i . o_i of the backward pass) accurate where one key holds nearly all the weight.
+  f32x4_t acc_l[kQB];
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
     m_run[qb] = -INFINITY;
     l_run[qb] = 0.f;
+    acc_l[qb] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int ct = 0; ct < 8; ++ct) acc_o[qb][ct] = f32x4_t{0.f, 0.f, 0.f, 0.f};
   }
@@ -224,6 +226,8 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
           for (int ct = 0; ct < 8; ++ct)
 #pragma unroll
             for (int e = 0; e < 4; ++e) acc_o[qb][ct][e] *= al[e];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc_l[qb][e] *= al[e];
         }
       }
     };
@@ -234,6 +238,9 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
 #pragma unroll
     for (int st = 0; st < kSteps; ++st) {
       const unsigned char* v_lds = buf + st * kMaTileLds + kMaKeys * kMaKStride;
+#pragma unroll
+      for (int qb = 0; qb < kQB; ++qb)
+        acc_l[qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pfrag[qb][st], ones, acc_l[qb], 0, 0, 0);
 #pragma unroll
       for (int ct = 0; ct < 8; ++ct) {
         const unsigned char* base = v_lds + (4 * r + (c >> 2)) * kMaVStride + ct * 32 + (c & 3) * 8;
@@ -252,27 +259,23 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
 #undef LKV_MA_LOAD_ROW
 #undef LKV_MA_STORE_ROW
 
-  // normalise and store: lane (r, c) holds O[query 4 r + e][channels 16 ct + c]
+  // normalise and store: lane (r, c) holds O[query 4 r + e][channels 16 ct + c] and the (rounded) denominators of
+  // those queries; the log-normaliser comes from the unrounded sum, held per query c
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
     float l = l_run[qb];
     l += __shfl_xor(l, 16, 64);
     l += __shfl_xor(l, 32, 64);
     const int query = qw0 + 16 * qb + c;
-    if (r == 0 && query < T)
-      lse[(size_t)hq * T + query] = l > 0.f ? m_run[qb] * kMaLn2 + __logf(l) : -INFINITY;
-    const float linv = l > 0.f ? 1.f / l : 0.f;     // no weight in the whole prefix: zero output
+    if (r == 0 && query < T) lse[(size_t)hq * T + query] = l > 0.f ? m_run[qb] * kMaLn2 + __logf(l) : -INFINITY;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
-      const float li = __shfl(linv, 4 * r + e, 64);
+      const float lr = acc_l[qb][e];
+      const float li = lr > 0.f ? 1.f / lr : 0.f;          // no weight in the whole prefix: zero output
       const int qrow = qw0 + 16 * qb + 4 * r + e;
-      // neighbouring channels sit in neighbouring lanes: pair them so that each even lane stores 4 bytes
+      if (qrow < T) {
 #pragma unroll
-      for (int ct = 0; ct < 8; ++ct) {
-        const float mine = acc_o[qb][ct][e] * li;
-        const float next = __shfl_down(mine, 1, 64);
-        if ((c & 1) == 0 && qrow < T)
-          *reinterpret_cast<uint32_t*>(o + ((size_t)hq * T + qrow) * kHeadDim + 16 * ct + c) = pack_bf16x2(mine, next);
+        for (int ct = 0; ct < 8; ++ct) o[((size_t)hq * T + qrow) * kHeadDim + 16 * ct + c] = acc_o[qb][ct][e] * li;
       }
     }
   }
@@ -287,11 +290,11 @@ hipError_t masked_attn_prepare() {
 }
 
 void launch_masked_attn_fwd(const void* q, const void* k, const void* v, const float* m, int n_q_heads, int n_kv_heads,
-                            int T, float scale, void* o, float* lse, hipStream_t stream) {
+                            int T, float scale, float* o, float* lse, hipStream_t stream) {
   const int G = n_q_heads / n_kv_heads;
   hipLaunchKernelGGL((masked_attn_fwd_kernel<2, kMaFwdSteps>), dim3((T + 127) / 128, n_q_heads), dim3(kMaThreads),
                      kMaFwdLds, stream, static_cast<const uint16_t*>(q), static_cast<const uint4*>(k),
-                     static_cast<const uint4*>(v), m, T, G, scale, static_cast<uint16_t*>(o), lse);
+                     static_cast<const uint4*>(v), m, T, G, scale, o, lse);
 }
 
 }  // namespace lkv

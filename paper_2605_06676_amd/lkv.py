@@ -23,7 +23,8 @@ EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_sc
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
            "lkv_append", "lkv_decode_attn_grown", "lkv_reevict", "lkv_masked_decode_workspace_bytes",
-           "lkv_masked_decode_attn", "lkv_masked_attn_forward")
+           "lkv_masked_decode_attn", "lkv_masked_attn_forward",
+           "lkv_masked_attn_backward_workspace_bytes", "lkv_masked_attn_backward")
 
 
 class LkvError(RuntimeError):
@@ -114,6 +115,11 @@ def load_library() -> C.CDLL:
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
     lib.lkv_masked_attn_forward.restype = C.c_int
+    lib.lkv_masked_attn_backward_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.lkv_masked_attn_backward_workspace_bytes.restype = C.c_size_t
+    lib.lkv_masked_attn_backward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 7 + [
+        C.c_float] + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]
+    lib.lkv_masked_attn_backward.restype = C.c_int
     lib.lkv_soft_topk_max_n.argtypes = [C.c_int32]
     lib.lkv_soft_topk_max_n.restype = C.c_int32
     lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
@@ -346,8 +352,24 @@ def lkv_masked_decode_attn(ctx: Context, cache: Cache, q, mask: Sequence, scale:
 
 
 def lkv_masked_attn_forward(ctx: Context, q, k, v, m, scale: float, o, lse, stream=None) -> None:
-    """q, o: bf16 [Hq, T, 128]; k, v: bf16 [H, T, 128]; m: fp32 [H, T]; lse: fp32 [Hq, T]."""
+    """q: bf16 [Hq, T, 128]; k, v: bf16 [H, T, 128]; m: fp32 [H, T]; o: fp32 [Hq, T, 128]; lse: fp32 [Hq, T]."""
     Hq, T, d = q.shape
     H = k.shape[0]
     ctx._check(ctx.lib.lkv_masked_attn_forward(ctx.h, Hq, H, T, d, _ptr(q), _ptr(k), _ptr(v), _ptr(m), float(scale),
                                                _ptr(o), _ptr(lse), _stream_ptr(stream)))
+
+
+def lkv_masked_attn_backward_workspace_bytes(n_q_heads: int, seq_len: int) -> int:
+    return int(load_library().lkv_masked_attn_backward_workspace_bytes(n_q_heads, seq_len))
+
+
+def lkv_masked_attn_backward(ctx: Context, q, k, v, m, o, lse, d_o, scale: float, dq, dk, dv, dm, workspace,
+                             stream=None) -> None:
+    """q, d_o: bf16 [Hq, T, 128]; k, v: bf16 [H, T, 128]; m: fp32 [H, T]; o: fp32 [Hq, T, 128]; lse: fp32 [Hq, T];
+    dq fp32 [Hq, T, 128]; dk, dv fp32 [H, T, 128]; dm fp32 [H, T]."""
+    Hq, T, d = q.shape
+    H = k.shape[0]
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ctx._check(ctx.lib.lkv_masked_attn_backward(ctx.h, Hq, H, T, d, _ptr(q), _ptr(k), _ptr(v), _ptr(m), _ptr(o),
+                                                _ptr(lse), _ptr(d_o), float(scale), _ptr(dq), _ptr(dk), _ptr(dv),
+                                                _ptr(dm), _ptr(workspace), ws_bytes, _stream_ptr(stream)))

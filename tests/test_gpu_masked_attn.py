@@ -1,6 +1,6 @@
 """GPU parity of the training-time attention with a multiplicative mask (App. B) against the
-fp64 oracle, through the C ABI.  Outputs are bf16: the bound is the decode bound (2e-2 of the
-output scale of the query row); the log-normaliser is fp32 and held to 1e-3 absolute."""
+fp64 oracle, through the C ABI.  The bound on the outputs is the decode bound (2e-2 of the
+output scale of the query row); the log-normaliser is held to 1e-3 absolute."""
 import numpy as np
 import pytest
 import torch
@@ -24,11 +24,11 @@ def ctx():
 def run_forward(ctx, q, k, v, m):
     tq, tk, tv = (bits_to_bf16_gpu(x) for x in (q, k, v))
     tm = torch.from_numpy(m).cuda()
-    o = torch.full(tq.shape, float("nan"), dtype=torch.bfloat16, device="cuda")
+    o = torch.full(tq.shape, float("nan"), dtype=torch.float32, device="cuda")
     lse = torch.full(tq.shape[:2], float("nan"), dtype=torch.float32, device="cuda")
     lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, tm, SCALE, o, lse)
     torch.cuda.synchronize()
-    return O.bf16_bits_to_f64(bf16_gpu_to_bits(o)), lse.cpu().numpy()
+    return o.cpu().numpy(), lse.cpu().numpy()
 
 
 def check_forward(ctx, Hq, H, T, seed=0, mask=None):
@@ -66,7 +66,7 @@ def test_forward_rejects_bad_arguments(ctx):
     q, k, v, m, _ = W.draw_training_attention(4, 2, 64)
     tq, tk, tv = (bits_to_bf16_gpu(x) for x in (q, k, v))
     tm = torch.from_numpy(m).cuda()
-    o = torch.empty_like(tq)
+    o = torch.empty(tq.shape, dtype=torch.float32, device="cuda")
     lse = torch.empty(tq.shape[:2], dtype=torch.float32, device="cuda")
     with pytest.raises(lkv.LkvError):
         lkv.lkv_masked_attn_forward(ctx, tq, tk[:1].repeat(3, 1, 1), tv, tm, SCALE, o, lse)   # 4 query heads, 3 KV heads
@@ -76,3 +76,102 @@ def test_forward_rejects_bad_arguments(ctx):
         lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, None, SCALE, o, lse)
     with pytest.raises(lkv.LkvError):
         lkv.lkv_masked_attn_forward(ctx, tq[:, :, :64].contiguous(), tk, tv, tm, SCALE, o, lse)   # head_dim 64
+
+
+# ---- backward -------------------------------------------------------------------------------------
+# Every gradient element is an fp32 sum of products in which one factor (P or dS) was rounded to bf16 on
+# its way through the matrix cores (relative error up to 2^-9).  On top of that the per-query quantities the
+# backward pass takes from the forward one (o_i in D_i = dO_i . o_i, and lse_i) carry the forward pass's own
+# rounding of P, and an error dD_i enters every dS_ij of the row as p_ij dD_i whatever the size of the
+# row's own gradient (the second query has two keys whose dS cancel: its dQ is small, the inherited error
+# is not).  Hence a relative and an absolute part: per row, max error <= 2e-2 * (scale of the row: the
+# larger of its biggest entry and its rms) + 2e-3 * (rms of the whole gradient tensor).
+GRAD_RTOL = 2e-2
+GRAD_ATOL_OF_RMS = 2e-3
+
+
+def assert_rows_close(got, ref, what):
+    ref = ref.reshape(-1, ref.shape[-1]).astype(np.float64)
+    got = got.reshape(ref.shape).astype(np.float64)
+    assert np.isfinite(got).all(), f"{what}: non-finite values"
+    err = np.abs(got - ref).max(axis=-1)
+    scale = np.maximum(np.abs(ref).max(axis=-1), np.sqrt((ref ** 2).mean(axis=-1)))
+    if not np.any(ref):
+        # a gradient that vanishes identically (a single key: dS = 0) comes out at the rounding level of
+        # o = (p v) * (1 / l); the inputs are N(0, 1), so 1e-4 is far below any real gradient
+        assert err.max() <= 1e-4, f"{what}: a gradient that must vanish is {err.max():.3g}"
+        return
+    tol = GRAD_RTOL * scale + GRAD_ATOL_OF_RMS * np.sqrt((ref ** 2).mean())
+    bad = err > tol
+    assert not bad.any(), f"{what}: {bad.sum()} rows out of tolerance, worst ratio {(err / tol).max():.3g}"
+
+
+def run_backward(ctx, q, k, v, m, d_o):
+    tq, tk, tv, tg = (bits_to_bf16_gpu(x) for x in (q, k, v, d_o))
+    tm = torch.from_numpy(m).cuda()
+    o = torch.empty(tq.shape, dtype=torch.float32, device="cuda")
+    lse = torch.empty(tq.shape[:2], dtype=torch.float32, device="cuda")
+    lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, tm, SCALE, o, lse)
+    nan = float("nan")
+    dq = torch.full(tq.shape, nan, dtype=torch.float32, device="cuda")
+    dk = torch.full(tk.shape, nan, dtype=torch.float32, device="cuda")
+    dv = torch.full(tk.shape, nan, dtype=torch.float32, device="cuda")
+    dm = torch.full(tm.shape, nan, dtype=torch.float32, device="cuda")
+    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(tq.shape[0], tq.shape[1]), dtype=torch.uint8, device="cuda")
+    lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, o, lse, tg, SCALE, dq, dk, dv, dm, ws)
+    torch.cuda.synchronize()
+    return [x.cpu().numpy() for x in (dq, dk, dv, dm)]
+
+
+def check_backward(ctx, Hq, H, T, seed=0, mask=None):
+    q, k, v, m, d_o = W.draw_training_attention(Hq, H, T, seed)
+    if mask is not None:
+        m = mask(m)
+    dq, dk, dv, dm = run_backward(ctx, q, k, v, m, d_o)
+    rq, rk, rv, rm = MA.backward(*(O.bf16_bits_to_f64(x) for x in (q, k, v)), m, SCALE, O.bf16_bits_to_f64(d_o))
+    tag = f"Hq{Hq} H{H} T{T}"
+    assert_rows_close(dq, rq, tag + " dQ")
+    assert_rows_close(dk, rk, tag + " dK")
+    assert_rows_close(dv, rv, tag + " dV")
+    assert_rows_close(dm, rm, tag + " dm")   # one row per KV head: the mask gradient of a head is judged as a vector
+
+
+@pytest.mark.parametrize("Hq,H,T", [(4, 2, 300), (2, 2, 1), (1, 1, 33), (4, 1, 128), (2, 1, 129), (7, 1, 257), (8, 2, 1000)])
+def test_backward_small(ctx, Hq, H, T):
+    check_backward(ctx, Hq, H, T)
+
+
+def test_backward_mask_edge_cases(ctx):
+    def zero_prefix(m):
+        m = m.copy()
+        m[:, :37] = 0.0          # 37 queries without any weight: they contribute nothing, and dm stays finite
+        return m
+
+    check_backward(ctx, 4, 2, 200, mask=zero_prefix)
+    check_backward(ctx, 4, 2, 200, mask=lambda m: np.ones_like(m))
+    check_backward(ctx, 4, 2, 200, mask=lambda m: (m > 0.2).astype(np.float32))
+
+
+def test_backward_is_reproducible(ctx):
+    # no atomics: two runs give the same bits
+    q, k, v, m, d_o = W.draw_training_attention(8, 2, 777, 3)
+    a = run_backward(ctx, q, k, v, m, d_o)
+    b = run_backward(ctx, q, k, v, m, d_o)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+
+
+def test_backward_rejects_small_workspace(ctx):
+    q, k, v, m, d_o = W.draw_training_attention(4, 2, 64)
+    tq, tk, tv, tg = (bits_to_bf16_gpu(x) for x in (q, k, v, d_o))
+    tm = torch.from_numpy(m).cuda()
+    o = torch.zeros(tq.shape, dtype=torch.float32, device="cuda")
+    lse = torch.zeros(tq.shape[:2], dtype=torch.float32, device="cuda")
+    dq = torch.empty(tq.shape, dtype=torch.float32, device="cuda")
+    dk = torch.empty(tk.shape, dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    dm = torch.empty_like(tm)
+    ws = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(lkv.LkvError) as e:
+        lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, o, lse, tg, SCALE, dq, dk, dv, dm, ws)
+    assert e.value.status == 3
