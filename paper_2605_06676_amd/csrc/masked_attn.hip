@@ -37,7 +37,7 @@ typedef short s16x8_t __attribute__((ext_vector_type(8)));
 constexpr int kMaThreads = 256;
 constexpr int kMaWaves = kMaThreads / 64;
 constexpr int kMaKeys = 32;                   // keys per tile: one K-step of the P.V product
-constexpr int kMaKStride = 272;               // LDS bytes per staged K row (conflict-free 16-byte reads)
+constexpr int kMaKStride = 288;               // LDS bytes per staged K row (measured conflict free; 272 was not)
 constexpr int kMaVStride = 288;               // LDS bytes per staged V row (conflict-free transposing reads)
 constexpr int kMaTileLds = kMaKeys * (kMaKStride + kMaVStride) + kMaKeys * 4;   // K, V and the mask weights
 constexpr float kMaLog2e = 1.4426950408889634f;
@@ -54,7 +54,7 @@ __device__ __forceinline__ s16x4_t ma_read_tr16(const unsigned char* p) {
 template <int kQB, int kSteps>
 __global__ void __launch_bounds__(kMaThreads, kQB >= 4 ? 1 : 2)
 masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ k, const uint4* __restrict__ v,
-                       const float* __restrict__ m, int T, int G, float scale, float* __restrict__ o,
+                       const float* __restrict__ m, int T, int n_heads, int G, float scale, float* __restrict__ o,
                        float* __restrict__ lse) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveQ = 16 * kQB;
@@ -63,8 +63,10 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
   constexpr int kTileLds = kSteps * kMaTileLds;
   constexpr int kStage = kTileKeys / 16;               // staged rows per thread and tensor
   const int n_qtiles = (T + kBlockQ - 1) / kBlockQ;
-  const int qtile = n_qtiles - 1 - (int)blockIdx.x;    // the longest rows of the causal triangle start first
-  const int hq = blockIdx.y;
+  // blocks in order of decreasing work: the query tile is the slow index, the head the fast one,
+  // so that the longest rows of the causal triangle of every head start first
+  const int qtile = n_qtiles - 1 - (int)blockIdx.x / n_heads;
+  const int hq = (int)blockIdx.x % n_heads;
   const int h = hq / G;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -292,9 +294,9 @@ hipError_t masked_attn_prepare() {
 void launch_masked_attn_fwd(const void* q, const void* k, const void* v, const float* m, int n_q_heads, int n_kv_heads,
                             int T, float scale, float* o, float* lse, hipStream_t stream) {
   const int G = n_q_heads / n_kv_heads;
-  hipLaunchKernelGGL((masked_attn_fwd_kernel<2, kMaFwdSteps>), dim3((T + 127) / 128, n_q_heads), dim3(kMaThreads),
+  hipLaunchKernelGGL((masked_attn_fwd_kernel<2, kMaFwdSteps>), dim3((T + 127) / 128 * n_q_heads), dim3(kMaThreads),
                      kMaFwdLds, stream, static_cast<const uint16_t*>(q), static_cast<const uint4*>(k),
-                     static_cast<const uint4*>(v), m, T, G, scale, o, lse);
+                     static_cast<const uint4*>(v), m, T, n_q_heads, G, scale, o, lse);
 }
 
 }  // namespace lkv

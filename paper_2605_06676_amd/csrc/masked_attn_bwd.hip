@@ -45,8 +45,8 @@ constexpr int kMbWaves = kMbThreads / 64;
 constexpr int kMbStep = 32;                    // streamed rows per K-step of the second products
 constexpr int kMbSteps = 2;                    // steps staged per barrier (64 rows)
 constexpr int kMbTile = kMbStep * kMbSteps;
-constexpr int kMbStrideA = 272;                // LDS bytes per row read only straight (16-byte reads, conflict free)
-constexpr int kMbStrideT = 288;                // LDS bytes per row that is also read transposed
+constexpr int kMbStrideA = 288;                // LDS bytes per staged row: measured conflict free for the straight 16-byte
+constexpr int kMbStrideT = 288;                // reads and for the transposing reads (272 was not, for the straight ones)
 constexpr float kMbLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float mb_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -100,14 +100,15 @@ template <int kQB>
 __global__ void __launch_bounds__(kMbThreads, 1)
 masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ k, const uint4* __restrict__ v,
                           const float* __restrict__ m, const float* __restrict__ lse, const float* __restrict__ dvec,
-                          const uint16_t* __restrict__ d_o, int T, int G, float scale, float* __restrict__ dq) {
+                          const uint16_t* __restrict__ d_o, int T, int n_heads, int G, float scale, float* __restrict__ dq) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveQ = 16 * kQB;
   constexpr int kBlockQ = kMbWaves * kWaveQ;
   constexpr int kTileLds = kMbSteps * kDqStepLds;
   const int n_qtiles = (T + kBlockQ - 1) / kBlockQ;
-  const int qtile = n_qtiles - 1 - (int)blockIdx.x;    // the longest rows of the causal triangle start first
-  const int hq = blockIdx.y;
+  // blocks in order of decreasing work: query tile slow, head fast
+  const int qtile = n_qtiles - 1 - (int)blockIdx.x / n_heads;
+  const int hq = (int)blockIdx.x % n_heads;
   const int h = hq / G;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -269,14 +270,15 @@ template <int kKB>
 __global__ void __launch_bounds__(kMbThreads, 1)
 masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                            const float* __restrict__ m, const float* __restrict__ lse, const float* __restrict__ dvec,
-                           const uint4* __restrict__ d_o, int T, int G, float scale, float* __restrict__ dk,
+                           const uint4* __restrict__ d_o, int T, int n_kv_heads, int G, float scale, float* __restrict__ dk,
                            float* __restrict__ dv, float* __restrict__ dm) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveK = 16 * kKB;
   constexpr int kBlockK = kMbWaves * kWaveK;
   constexpr int kTileLds = kMbSteps * kDkvStepLds;
-  const int h = blockIdx.y;
-  const int k0 = (int)blockIdx.x * kBlockK;              // early keys have the most queries after them: they start first
+  // blocks in order of decreasing work: early keys have the most queries after them; key tile slow, head fast
+  const int h = (int)blockIdx.x % n_kv_heads;
+  const int k0 = (int)blockIdx.x / n_kv_heads * kBlockK;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -476,12 +478,12 @@ void launch_masked_attn_bwd(const void* q, const void* k, const void* v, const f
   const int64_t n_rows = (int64_t)n_q_heads * T;
   hipLaunchKernelGGL(masked_attn_bwd_prep_kernel, dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, stream,
                      reinterpret_cast<const float4*>(o), static_cast<const uint4*>(d_o), n_rows, workspace);
-  hipLaunchKernelGGL(masked_attn_bwd_dkv_kernel<2>, dim3((T + 127) / 128, n_kv_heads), dim3(kMbThreads), kDkvLds, stream,
+  hipLaunchKernelGGL(masked_attn_bwd_dkv_kernel<2>, dim3((T + 127) / 128 * n_kv_heads), dim3(kMbThreads), kDkvLds, stream,
                      static_cast<const uint4*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v), m,
-                     lse, workspace, static_cast<const uint4*>(d_o), T, G, scale, dk, dv, dm);
-  hipLaunchKernelGGL(masked_attn_bwd_dq_kernel<2>, dim3((T + 127) / 128, n_q_heads), dim3(kMbThreads), kDqLds, stream,
+                     lse, workspace, static_cast<const uint4*>(d_o), T, n_kv_heads, G, scale, dk, dv, dm);
+  hipLaunchKernelGGL(masked_attn_bwd_dq_kernel<2>, dim3((T + 127) / 128 * n_q_heads), dim3(kMbThreads), kDqLds, stream,
                      static_cast<const uint16_t*>(q), static_cast<const uint4*>(k), static_cast<const uint4*>(v), m, lse,
-                     workspace, static_cast<const uint16_t*>(d_o), T, G, scale, dq);
+                     workspace, static_cast<const uint16_t*>(d_o), T, n_q_heads, G, scale, dq);
 }
 
 }  // namespace lkv
