@@ -38,8 +38,11 @@ def _group(Hq: int, H: int) -> int:
     return Hq // H
 
 
-def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: float):
-    """Causal attention with the multiplicative mask.  Returns (O [Hq, T, d], lse [Hq, T])."""
+def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: float, rows=None):
+    """Causal attention with the multiplicative mask.  Returns (O [Hq, T, d], lse [Hq, T]).
+
+    ``rows``: the query positions to compute (default all); the others stay 0 / -inf.
+    """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -50,7 +53,7 @@ def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: f
     lse = np.full((Hq, T), -np.inf)
     for hq in range(Hq):
         h = hq // g
-        for i in range(T):
+        for i in (range(T) if rows is None else rows):
             s = scale * (K[h, : i + 1] @ Q[hq, i])
             top = s.max()
             e = np.exp(s - top)
@@ -64,8 +67,13 @@ def forward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: f
     return O, lse
 
 
-def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: float, dO: np.ndarray):
-    """Gradients of sum(O * dO) with respect to Q, K, V and m (App. B.3's graph, reversed)."""
+def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: float, dO: np.ndarray, rows=None):
+    """Gradients of sum(O * dO) with respect to Q, K, V and m (App. B.3's graph, reversed).
+
+    ``rows``: only these query positions contribute (default all).  With rows = range(j, T) the
+    gradients of the keys j .. T - 1 and of those queries are complete, since earlier queries do
+    not see these keys.
+    """
     Q = np.asarray(Q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
@@ -79,7 +87,7 @@ def backward(Q: np.ndarray, K: np.ndarray, V: np.ndarray, m: np.ndarray, scale: 
     dm = np.zeros_like(m)
     for hq in range(Hq):
         h = hq // g
-        for i in range(T):
+        for i in (range(T) if rows is None else rows):
             n = i + 1
             s = scale * (K[h, :n] @ Q[hq, i])
             e = np.exp(s - s.max())

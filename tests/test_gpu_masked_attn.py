@@ -175,3 +175,62 @@ def test_backward_rejects_small_workspace(ctx):
     with pytest.raises(lkv.LkvError) as e:
         lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, o, lse, tg, SCALE, dq, dk, dv, dm, ws)
     assert e.value.status == 3
+
+
+def test_full_size_sampled(ctx):
+    """Llama-3.1-8B's attention shape (32 query heads, 8 KV heads) at the longest training length of
+    the paper (16k tokens, App. C.2), in the launch configuration bench.py times.  Checked on what the
+    oracle can compute row by row: forward rows and dQ rows of sampled queries, dK / dV / dm of the last
+    keys (complete once every later query is included), and two identities that hold at any size:
+    sum_j dV_j = sum_i dO_i over the group's queries (the weights of a row sum to 1) and
+    sum_j m_j dm_j = 0 (scaling a head's mask changes nothing)."""
+    Hq, H, T = 32, 8, 16384
+    G = Hq // H
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20260506)
+    tq = torch.randn((Hq, T, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    tk = torch.randn((H, T, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    tv = torch.randn((H, T, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    tg = torch.randn((Hq, T, 128), device="cuda", generator=gen).to(torch.bfloat16)
+    x = torch.rand((H, T), device="cuda", generator=gen)
+    pick = torch.rand((H, T), device="cuda", generator=gen)
+    tm = (x * x) * (x * x)
+    tm[pick < 0.10] = 0.0
+    tm[pick > 0.95] = 1.0
+    tm[:, 0] = torch.clamp(tm[:, 0], min=0.25)
+    o = torch.empty((Hq, T, 128), dtype=torch.float32, device="cuda")
+    lse = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+    lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, tm, SCALE, o, lse)
+    dq = torch.empty_like(o)
+    dk = torch.empty((H, T, 128), dtype=torch.float32, device="cuda")
+    dv = torch.empty_like(dk)
+    dm = torch.empty_like(tm)
+    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(Hq, T), dtype=torch.uint8, device="cuda")
+    lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, o, lse, tg, SCALE, dq, dk, dv, dm, ws)
+    torch.cuda.synchronize()
+
+    # identities over everything
+    dv_sum = dv.double().sum(dim=1)                                            # [H, 128]
+    do_sum = tg.double().view(H, G, T, 128).sum(dim=(1, 2))
+    scale_dv = tg.double().abs().view(H, G, T, 128).sum(dim=(1, 2))
+    assert (dv_sum - do_sum).abs().max().item() <= 2.0 ** -9 * scale_dv.max().item()
+    along = (dm.double() * tm.double()).sum(dim=1)
+    assert along.abs().max().item() <= 2.0 ** -9 * (dm.double() * tm.double()).abs().sum(dim=1).max().item()
+
+    # one KV head and its group on the host; the last `tail` queries and a few scattered ones
+    tail = 150
+    for h in (0, H - 1):
+        heads = slice(h * G, (h + 1) * G)
+        q, g = (O.bf16_bits_to_f64(bf16_gpu_to_bits(x[heads])) for x in (tq, tg))
+        k, v = (O.bf16_bits_to_f64(bf16_gpu_to_bits(x[h:h + 1])) for x in (tk, tv))
+        m = tm[h:h + 1].cpu().numpy()
+        rows = [0, 1, 63, 64, 255, 256, 4097, 9000] + list(range(T - tail, T))
+        o_ref, lse_ref = MA.forward(q, k, v, m, SCALE, rows=rows)
+        assert_decode_close(o[heads][:, rows].cpu().numpy().reshape(-1, 128), lse[heads][:, rows].cpu().numpy().reshape(-1),
+                            o_ref[:, rows].reshape(-1, 128), lse_ref[:, rows].reshape(-1), f"full size head {h} forward")
+        rq, rk, rv, rm = MA.backward(q, k, v, m, SCALE, g, rows=rows)
+        assert_rows_close(dq[heads][:, rows].cpu().numpy(), rq[:, rows], f"full size head {h} dQ")
+        keys = slice(T - tail, T)
+        assert_rows_close(dk[h:h + 1, keys].cpu().numpy(), rk[:, keys], f"full size head {h} dK")
+        assert_rows_close(dv[h:h + 1, keys].cpu().numpy(), rv[:, keys], f"full size head {h} dV")
+        assert_rows_close(dm[h:h + 1, keys].cpu().numpy(), rm[:, keys], f"full size head {h} dm")

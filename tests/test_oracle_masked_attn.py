@@ -180,3 +180,20 @@ def test_group_heads_share_their_kv_head():
     assert np.allclose(dK[0], parts[0][1][0] + parts[1][1][0], atol=1e-13)
     assert np.allclose(dV[0], parts[0][2][0] + parts[1][2][0], atol=1e-13)
     assert np.allclose(dm[0], parts[0][3][0] + parts[1][3][0], atol=1e-13)
+
+
+def test_row_subsets():
+    # computing some query rows only gives those rows of the full result, and the key-side gradients
+    # of the last keys are complete once every query at or after them is included
+    Q, K, V, m, dO, scale = _draw(11, T=13)
+    O, lse = ma.forward(Q, K, V, m, scale)
+    pick = [2, 7, 12]
+    Os, ls = ma.forward(Q, K, V, m, scale, rows=pick)
+    assert np.array_equal(Os[:, pick], O[:, pick]) and np.array_equal(ls[:, pick], lse[:, pick])
+    rest = [i for i in range(13) if i not in pick]
+    assert (Os[:, rest] == 0).all() and np.isneginf(ls[:, rest]).all()
+    full = ma.backward(Q, K, V, m, scale, dO)
+    tail = ma.backward(Q, K, V, m, scale, dO, rows=range(9, 13))
+    assert np.allclose(tail[0][:, 9:], full[0][:, 9:], rtol=0, atol=1e-14)      # dQ of those queries
+    for a, b in zip(tail[1:], full[1:]):                                         # dK, dV, dm of keys 9..12
+        assert np.allclose(a[:, 9:], b[:, 9:], rtol=0, atol=1e-14)
