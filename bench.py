@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--growth", action="store_true",
                     help="also measure decode-time growth (compaction with slack, append, grown decode, re-eviction); "
                          "adds the key `growth`")
+    ap.add_argument("--train-attn", type=int, nargs="?", const=16384, default=0, metavar="T",
+                    help="also time the training-time attention with the multiplicative mask (forward and backward) "
+                         "over T tokens (default 16384) for the workload's head counts; adds the key `training_attention`")
     ap.add_argument("--layerwise", action="store_true",
                     help="also measure layer-by-layer eviction during prefill; adds the key `layerwise`")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -281,9 +284,61 @@ def main():
         result["layerwise"] = layerwise_result
     if args.growth:
         result["growth"] = growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev)
+    if args.train_attn:
+        result["training_attention"] = training_attention(ctx, lkv, w, args.train_attn, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
     print(json.dumps(result))
+
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def training_attention(ctx, lkv, w, T, dev, reps=10):
+    """Causal attention with the multiplicative mask (App. B) for one layer of one sequence of T tokens, the
+    workload's query and KV head counts: forward, and backward (dQ, dK, dV, dm).  FLOPs are the algorithmic
+    ones of the causal triangle: 2 products for the forward, 5 for the backward (the backward kernels execute
+    7, because s and dP are recomputed in both of them)."""
+    import torch
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(0)
+    q = torch.randn((w.Hq, T, w.d), device=dev, generator=gen).to(torch.bfloat16)
+    k = torch.randn((w.H, T, w.d), device=dev, generator=gen).to(torch.bfloat16)
+    v = torch.randn((w.H, T, w.d), device=dev, generator=gen).to(torch.bfloat16)
+    d_o = torch.randn((w.Hq, T, w.d), device=dev, generator=gen).to(torch.bfloat16)
+    m = torch.rand((w.H, T), device=dev, generator=gen) ** 4
+    o = torch.empty((w.Hq, T, w.d), dtype=torch.float32, device=dev)
+    lse = torch.empty((w.Hq, T), dtype=torch.float32, device=dev)
+    dq = torch.empty_like(o)
+    dk = torch.empty((w.H, T, w.d), dtype=torch.float32, device=dev)
+    dv = torch.empty_like(dk)
+    dm = torch.empty_like(m)
+    ws = torch.empty((lkv.lkv_masked_attn_backward_workspace_bytes(w.Hq, T),), dtype=torch.uint8, device=dev)
+    scale = 1.0 / math.sqrt(w.d)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(reps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / reps
+
+    t_fwd = timed(lambda: lkv.lkv_masked_attn_forward(ctx, q, k, v, m, scale, o, lse))
+    t_bwd = timed(lambda: lkv.lkv_masked_attn_backward(ctx, q, k, v, m, o, lse, d_o, scale, dq, dk, dv, dm, ws))
+    product = 2.0 * w.d * (T * (T + 1) / 2) * w.Hq      # one causal (query, key) product over d channels, all heads
+    out = {"tokens": T, "n_q_heads": w.Hq, "n_kv_heads": w.H, "dtype": "bf16 operands, fp32 accumulate"}
+    for name, t, n_products, executed in (("forward", t_fwd, 2, 2), ("backward", t_bwd, 5, 7)):
+        tf = n_products * product / (t * 1e9)
+        out[name] = {"ms": t, "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
+                                           "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                     "executed_TFLOPs": executed * product / (t * 1e9)}
+    return out
 
 
 def growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev, slack=128, n_new=64):

@@ -97,7 +97,7 @@ constexpr int kDqStepLds = kMbStep * (kMbStrideT + kMbStrideA) + kMbStep * 4;
 constexpr int kDqLds = 2 * kMbSteps * kDqStepLds;
 
 template <int kQB>
-__global__ void __launch_bounds__(kMbThreads, 1)
+__global__ void __launch_bounds__(kMbThreads, 2)
 masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ k, const uint4* __restrict__ v,
                           const float* __restrict__ m, const float* __restrict__ lse, const float* __restrict__ dvec,
                           const uint16_t* __restrict__ d_o, int T, int n_heads, int G, float scale, float* __restrict__ dq) {
