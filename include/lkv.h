@@ -5,7 +5,8 @@
  * (lkv_score, lkv_select, lkv_compact, lkv_decode_attn); further down, the same
  * path one layer at a time during prefill, the growth of the packed cache
  * during decoding with re-eviction, attention with a multiplicative mask over
- * the uncompacted cache, and the LKV-H budget allocation with the forward
+ * the uncompacted cache, the training-time attention kernel with that mask
+ * (forward and backward), and the LKV-H budget allocation with the forward
  * Soft-TopK operator.
  *
  * General conventions
