@@ -283,7 +283,7 @@ lkv_status lkv_masked_decode_attn(lkv_ctx *ctx, const lkv_cache *cache, const vo
  * lse : DEVICE fp32 [n_q_heads, seq_len] = log sum_{k <= i} e^{s_ik} m_k (needed by the backward pass)
  * A query whose whole prefix has weight 0 gets o = 0 and lse = -inf.
  * q, k, v, o 16-byte aligned; head_dim must be 128; scale > 0;
- * n_q_heads * ceil(seq_len / 128) < 2^31.
+ * seq_len < 2^24; n_q_heads * ceil(seq_len / 128) < 2^31.
  * Errors: LKV_ERR_INVALID_ARG / LKV_ERR_UNSUPPORTED before anything is enqueued. */
 lkv_status lkv_masked_attn_forward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
                                    int32_t head_dim, const void *q, const void *k, const void *v,

@@ -656,6 +656,7 @@ lkv_status lkv_masked_attn_forward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv
     return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
   if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
   if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  if (seq_len >= 1 << 24) return fail(ctx, LKV_ERR_UNSUPPORTED, "seq_len = %d must be below 2^24", seq_len);
   if (((int64_t)seq_len + 127) / 128 * n_q_heads >= (int64_t)1 << 31)
     return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
   if (!(scale > 0.f) || std::isinf(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale = %g must be positive and finite", (double)scale);
@@ -682,6 +683,7 @@ lkv_status lkv_masked_attn_backward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_k
     return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
   if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
   if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  if (seq_len >= 1 << 24) return fail(ctx, LKV_ERR_UNSUPPORTED, "seq_len = %d must be below 2^24", seq_len);
   if (((int64_t)seq_len + 127) / 128 * n_q_heads >= (int64_t)1 << 31)
     return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
   if ((int64_t)n_q_heads * seq_len >= ((int64_t)1 << 31) * 16)

@@ -121,8 +121,9 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
 #define LKV_MA_LOAD_ROW(j_, kreg_, vreg_, t_)                                                                 \
   {                                                                                                           \
     const int key = min((t_) * kTileKeys + srow + 16 * (j_), T - 1); /* past the end: the last row, unused */ \
-    kreg_ = kh[(size_t)key * kChunksPerRow + spiece];                                                         \
-    vreg_ = vh[(size_t)key * kChunksPerRow + spiece];                                                         \
+    const uint32_t off = (uint32_t)key * 256u + (uint32_t)spiece * 16u; /* a 32-bit offset from a uniform base */ \
+    kreg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(kh) + off);                \
+    vreg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vh) + off);                \
   }
 #define LKV_MA_LOAD_TILE(t_)                                            \
   {                                                                     \

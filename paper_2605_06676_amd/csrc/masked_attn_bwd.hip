@@ -152,8 +152,9 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
 #define LKV_MB_LOAD_ROW(j_, kreg_, vreg_, t_)                                                             \
   {                                                                                                       \
     const int key = min((t_) * kMbTile + srow + 16 * (j_), T - 1); /* past the end: the last row, unused */ \
-    kreg_ = kh[(size_t)key * kChunksPerRow + spiece];                                                     \
-    vreg_ = vh[(size_t)key * kChunksPerRow + spiece];                                                     \
+    const uint32_t off = (uint32_t)key * 256u + (uint32_t)spiece * 16u; /* 32-bit offset, uniform base */ \
+    kreg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(kh) + off);            \
+    vreg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(vh) + off);            \
   }
 #define LKV_MB_LOAD_TILE(t_)                                      \
   {                                                               \
@@ -321,8 +322,9 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
 #define LKV_MB_LOAD_ROW(j_, qreg_, greg_, base_, q0_)                                                       \
   {                                                                                                         \
     const int query = min((q0_) + srow + 16 * (j_), T - 1); /* past the end: the last row, masked later */  \
-    qreg_ = q[((base_) + query) * kChunksPerRow + spiece];                                                  \
-    greg_ = d_o[((base_) + query) * kChunksPerRow + spiece];                                                \
+    const uint32_t off = (uint32_t)query * 256u + (uint32_t)spiece * 16u; /* 32-bit offset, uniform base */ \
+    qreg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(q + (base_) * kChunksPerRow) + off);   \
+    greg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(d_o + (base_) * kChunksPerRow) + off); \
   }
 #define LKV_MB_LOAD_ITEM(it_)                                                       \
   {                                                                                 \
