@@ -41,7 +41,8 @@ def check_forward(ctx, Hq, H, T, seed=0, mask=None):
                                f"Hq{Hq} H{H} T{T}")
 
 
-@pytest.mark.parametrize("Hq,H,T", [(4, 2, 300), (2, 2, 1), (1, 1, 33), (4, 1, 128), (2, 1, 129), (7, 1, 257), (8, 2, 1000)])
+@pytest.mark.parametrize("Hq,H,T", [(4, 2, 300), (2, 2, 1), (1, 1, 33), (4, 1, 128), (2, 1, 129), (7, 1, 257), (8, 2, 1000), (16, 1, 70), (3, 3, 64),
+                                    (6, 2, 513)])
 def test_forward_small(ctx, Hq, H, T):
     check_forward(ctx, Hq, H, T)
 
@@ -136,7 +137,8 @@ def check_backward(ctx, Hq, H, T, seed=0, mask=None):
     assert_rows_close(dm, rm, tag + " dm")   # one row per KV head: the mask gradient of a head is judged as a vector
 
 
-@pytest.mark.parametrize("Hq,H,T", [(4, 2, 300), (2, 2, 1), (1, 1, 33), (4, 1, 128), (2, 1, 129), (7, 1, 257), (8, 2, 1000)])
+@pytest.mark.parametrize("Hq,H,T", [(4, 2, 300), (2, 2, 1), (1, 1, 33), (4, 1, 128), (2, 1, 129), (7, 1, 257), (8, 2, 1000), (16, 1, 70), (3, 3, 64),
+                                    (6, 2, 513)])
 def test_backward_small(ctx, Hq, H, T):
     check_backward(ctx, Hq, H, T)
 
