@@ -55,3 +55,46 @@ def test_captured_step_replays_to_the_eager_result(ctx):
             assert torch.equal(getattr(run, k).view(torch.int16), want[k].view(torch.int16)), f"replay {rep}: {k}"
         for k in ("out", "lse"):
             assert torch.equal(getattr(run, k), want[k]), f"replay {rep}: {k}"
+
+
+def test_captured_training_attention_replays_to_the_eager_result(ctx):
+    # forward and backward of the training-time attention only enqueue kernels: captured, every replay
+    # must give the bits of the eager run (the backward pass has no atomics)
+    Hq, H, T = 8, 2, 700
+    q, k, v, m, d_o = W.draw_training_attention(Hq, H, T, 5)
+    tq, tk, tv, tg = (G.bits_to_bf16_gpu(x) for x in (q, k, v, d_o))
+    tm = torch.from_numpy(m).cuda()
+    outs = {"o": torch.empty((Hq, T, 128), dtype=torch.float32, device="cuda"),
+            "lse": torch.empty((Hq, T), dtype=torch.float32, device="cuda"),
+            "dq": torch.empty((Hq, T, 128), dtype=torch.float32, device="cuda"),
+            "dk": torch.empty((H, T, 128), dtype=torch.float32, device="cuda"),
+            "dv": torch.empty((H, T, 128), dtype=torch.float32, device="cuda"),
+            "dm": torch.empty((H, T), dtype=torch.float32, device="cuda")}
+    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(Hq, T), dtype=torch.uint8, device="cuda")
+
+    def both():
+        lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, tm, G.SCALE, outs["o"], outs["lse"])
+        lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, outs["o"], outs["lse"], tg, G.SCALE, outs["dq"], outs["dk"],
+                                     outs["dv"], outs["dm"], ws)
+
+    both()
+    torch.cuda.synchronize()
+    want = {name: t.clone() for name, t in outs.items()}
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        both()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            both()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in outs.values():
+            t.fill_(float("nan"))
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for name, t in outs.items():
+            assert torch.equal(t, want[name]), f"replay {rep}: {name}"
