@@ -45,8 +45,8 @@ constexpr int kMbWaves = kMbThreads / 64;
 constexpr int kMbStep = 32;                    // streamed rows per K-step of the second products
 constexpr int kMbSteps = 2;                    // steps staged per barrier (64 rows)
 constexpr int kMbTile = kMbStep * kMbSteps;
-constexpr int kMbStrideA = 288;                // LDS bytes per staged row: measured conflict free for the straight 16-byte
-constexpr int kMbStrideT = 288;                // reads and for the transposing reads (272 was not, for the straight ones)
+constexpr int kMbStride = 288;                 // LDS bytes per staged row: measured conflict free for the straight 16-byte
+                                               // reads and for the transposing reads (272 was not, for the straight ones)
 constexpr float kMbLog2e = 1.4426950408889634f;
 
 __device__ __forceinline__ float mb_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -93,7 +93,7 @@ masked_attn_bwd_prep_kernel(const float4* __restrict__ o, const uint4* __restric
 
 // ---- dQ ------------------------------------------------------------------------------------------
 // per 32-key step buffer: K rows (also read transposed), V rows, the 32 mask weights
-constexpr int kDqStepLds = kMbStep * (kMbStrideT + kMbStrideA) + kMbStep * 4;
+constexpr int kDqStepLds = kMbStep * 2 * kMbStride + kMbStep * 4;
 constexpr int kDqLds = 2 * kMbSteps * kDqStepLds;
 
 template <int kQB>
@@ -168,8 +168,8 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
   {                                                                                                          \
     unsigned char* step_buf = buf + ((j_) >> 1) * kDqStepLds;                                                \
     const int row = srow + 16 * ((j_) & 1);                                                                  \
-    *reinterpret_cast<uint4*>(step_buf + row * kMbStrideT + spiece * 16) = kreg_;                            \
-    *reinterpret_cast<uint4*>(step_buf + kMbStep * kMbStrideT + row * kMbStrideA + spiece * 16) = vreg_;     \
+    *reinterpret_cast<uint4*>(step_buf + row * kMbStride + spiece * 16) = kreg_;                            \
+    *reinterpret_cast<uint4*>(step_buf + kMbStep * kMbStride + row * kMbStride + spiece * 16) = vreg_;     \
   }
   LKV_MB_LOAD_TILE(0)
 
@@ -181,7 +181,7 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
     LKV_MB_STORE_ROW(2, k_s2, v_s2)
     LKV_MB_STORE_ROW(3, k_s3, v_s3)
     if (tid < kMbTile)
-      reinterpret_cast<float*>(buf + (tid >> 5) * kDqStepLds + kMbStep * (kMbStrideT + kMbStrideA))[tid & 31] = mk;
+      reinterpret_cast<float*>(buf + (tid >> 5) * kDqStepLds + kMbStep * 2 * kMbStride)[tid & 31] = mk;
     LKV_MB_LOAD_TILE(min(t + 1, n_tiles - 1))   // the last iteration re-reads its own tile: no branch around the loads
     __syncthreads();                            // two buffers: one barrier per tile is enough
     const int key0 = t * kMbTile;
@@ -190,8 +190,8 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
 #pragma unroll
       for (int st = 0; st < kMbSteps; ++st) {
         const unsigned char* k_lds = buf + st * kDqStepLds;
-        const unsigned char* v_lds = k_lds + kMbStep * kMbStrideT;
-        const float* m_lds = reinterpret_cast<const float*>(v_lds + kMbStep * kMbStrideA);
+        const unsigned char* v_lds = k_lds + kMbStep * kMbStride;
+        const float* m_lds = reinterpret_cast<const float*>(v_lds + kMbStep * kMbStride);
         // S^T and dP^T for the two 16-key halves of the step: lane (rb = r, query c) gets keys 16 tt + 4 r + e
         f32x4_t sacc[kQB][2], pacc[kQB][2];
 #pragma unroll
@@ -205,8 +205,8 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
         for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
           for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8_t kx = mb_read_straight(k_lds + (tt * 16 + c) * kMbStrideT + ks * 64 + r * 16);
-            const bf16x8_t vx = mb_read_straight(v_lds + (tt * 16 + c) * kMbStrideA + ks * 64 + r * 16);
+            const bf16x8_t kx = mb_read_straight(k_lds + (tt * 16 + c) * kMbStride + ks * 64 + r * 16);
+            const bf16x8_t vx = mb_read_straight(v_lds + (tt * 16 + c) * kMbStride + ks * 64 + r * 16);
 #pragma unroll
             for (int qb = 0; qb < kQB; ++qb) {
               sacc[qb][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kx, qfrag[qb][ks], sacc[qb][tt], 0, 0, 0);
@@ -238,7 +238,7 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
         // dQ += dS K: B operand from the K rows by the transposing read
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) {
-          const bf16x8_t kb = mb_read_transposed(k_lds, kMbStrideT, r, c, ct);
+          const bf16x8_t kb = mb_read_transposed(k_lds, kMbStride, r, c, ct);
 #pragma unroll
           for (int qb = 0; qb < kQB; ++qb)
             acc[qb][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(dsfrag[qb], kb, acc[qb][ct], 0, 0, 0);
@@ -264,7 +264,7 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
 
 // ---- dK, dV, dm ----------------------------------------------------------------------------------
 // per 32-query step buffer: Q rows, dO rows (both also read transposed), 32 x lse (log2 domain), 32 x D
-constexpr int kDkvStepLds = kMbStep * (2 * kMbStrideT) + 2 * kMbStep * 4;
+constexpr int kDkvStepLds = kMbStep * 2 * kMbStride + 2 * kMbStep * 4;
 constexpr int kDkvLds = 2 * kMbSteps * kDkvStepLds;
 
 template <int kKB>
@@ -342,8 +342,8 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
   {                                                                                                          \
     unsigned char* step_buf = buf + ((j_) >> 1) * kDkvStepLds;                                               \
     const int row = srow + 16 * ((j_) & 1);                                                                  \
-    *reinterpret_cast<uint4*>(step_buf + row * kMbStrideT + spiece * 16) = qreg_;                            \
-    *reinterpret_cast<uint4*>(step_buf + kMbStep * kMbStrideT + row * kMbStrideT + spiece * 16) = greg_;     \
+    *reinterpret_cast<uint4*>(step_buf + row * kMbStride + spiece * 16) = qreg_;                            \
+    *reinterpret_cast<uint4*>(step_buf + kMbStep * kMbStride + row * kMbStride + spiece * 16) = greg_;     \
   }
   LKV_MB_LOAD_ITEM(0)
 
@@ -357,7 +357,7 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
     if (tid < 2 * kMbTile) {
       // lse goes to the log2 domain; -inf (no weight in the prefix) becomes +inf so that every e_ij is 0
       const float val = (tid & kMbTile) ? aux : (aux == -INFINITY ? INFINITY : aux * kMbLog2e);
-      float* aux_lds = reinterpret_cast<float*>(buf + ((tid >> 5) & 1) * kDkvStepLds + 2 * kMbStep * kMbStrideT);
+      float* aux_lds = reinterpret_cast<float*>(buf + ((tid >> 5) & 1) * kDkvStepLds + 2 * kMbStep * kMbStride);
       aux_lds[(tid & kMbTile ? kMbStep : 0) + (tid & 31)] = val;
     }
     const int g_cur = it / tiles_per_head;
@@ -370,8 +370,8 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
       // wave-uniform: nothing to do when all 32 queries come before this wave's keys, or lie past the end
       if (qs0 + kMbStep - 1 < kw0 || qs0 >= T || kw0 >= T) continue;
       const unsigned char* q_lds = buf + st * kDkvStepLds;
-      const unsigned char* g_lds = q_lds + kMbStep * kMbStrideT;
-      const float* aux_lds = reinterpret_cast<const float*>(g_lds + kMbStep * kMbStrideT);
+      const unsigned char* g_lds = q_lds + kMbStep * kMbStride;
+      const float* aux_lds = reinterpret_cast<const float*>(g_lds + kMbStep * kMbStride);
       // S and dP: lane (rb = r, key c) gets queries 16 tt + 4 r + e
       f32x4_t sacc[kKB][2], pacc[kKB][2];
 #pragma unroll
@@ -385,8 +385,8 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
       for (int tt = 0; tt < 2; ++tt)
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-          const bf16x8_t qx = mb_read_straight(q_lds + (tt * 16 + c) * kMbStrideT + ks * 64 + r * 16);
-          const bf16x8_t gx = mb_read_straight(g_lds + (tt * 16 + c) * kMbStrideT + ks * 64 + r * 16);
+          const bf16x8_t qx = mb_read_straight(q_lds + (tt * 16 + c) * kMbStride + ks * 64 + r * 16);
+          const bf16x8_t gx = mb_read_straight(g_lds + (tt * 16 + c) * kMbStride + ks * 64 + r * 16);
 #pragma unroll
           for (int kb = 0; kb < kKB; ++kb) {
             sacc[kb][tt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qx, kfrag[kb][ks], sacc[kb][tt], 0, 0, 0);
@@ -425,8 +425,8 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
       // dV += P^T dO and dK += dS^T Q: B operands from the dO and Q rows by the transposing read
 #pragma unroll
       for (int ct = 0; ct < 8; ++ct) {
-        const bf16x8_t gb = mb_read_transposed(g_lds, kMbStrideT, r, c, ct);
-        const bf16x8_t qb = mb_read_transposed(q_lds, kMbStrideT, r, c, ct);
+        const bf16x8_t gb = mb_read_transposed(g_lds, kMbStride, r, c, ct);
+        const bf16x8_t qb = mb_read_transposed(q_lds, kMbStride, r, c, ct);
 #pragma unroll
         for (int kb = 0; kb < kKB; ++kb) {
           acc_v[kb][ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(pfrag[kb], gb, acc_v[kb][ct], 0, 0, 0);
