@@ -179,14 +179,15 @@ def test_backward_rejects_small_workspace(ctx):
     assert e.value.status == 3
 
 
-def test_full_size_sampled(ctx):
+@pytest.mark.parametrize("Hq,H,T", [(32, 8, 16384), (4, 1, 131072 + 5)])
+def test_full_size_sampled(ctx, Hq, H, T):
     """Llama-3.1-8B's attention shape (32 query heads, 8 KV heads) at the longest training length of
     the paper (16k tokens, App. C.2), in the launch configuration bench.py times.  Checked on what the
     oracle can compute row by row: forward rows and dQ rows of sampled queries, dK / dV / dm of the last
     keys (complete once every later query is included), and two identities that hold at any size:
     sum_j dV_j = sum_i dO_i over the group's queries (the weights of a row sum to 1) and
-    sum_j m_j dm_j = 0 (scaling a head's mask changes nothing)."""
-    Hq, H, T = 32, 8, 16384
+    sum_j m_j dm_j = 0 (scaling a head's mask changes nothing).  The second case is one GQA group over a
+    context eight times longer, ragged against every tile size (index arithmetic at length)."""
     G = Hq // H
     gen = torch.Generator(device="cuda")
     gen.manual_seed(20260506)
@@ -226,7 +227,7 @@ def test_full_size_sampled(ctx):
         q, g = (O.bf16_bits_to_f64(bf16_gpu_to_bits(x[heads])) for x in (tq, tg))
         k, v = (O.bf16_bits_to_f64(bf16_gpu_to_bits(x[h:h + 1])) for x in (tk, tv))
         m = tm[h:h + 1].cpu().numpy()
-        rows = [0, 1, 63, 64, 255, 256, 4097, 9000] + list(range(T - tail, T))
+        rows = [0, 1, 63, 64, 255, 256, 4097, 9000, T // 2 + 1] + list(range(T - tail, T))
         o_ref, lse_ref = MA.forward(q, k, v, m, SCALE, rows=rows)
         assert_decode_close(o[heads][:, rows].cpu().numpy().reshape(-1, 128), lse[heads][:, rows].cpu().numpy().reshape(-1),
                             o_ref[:, rows].reshape(-1, 128), lse_ref[:, rows].reshape(-1), f"full size head {h} forward")
