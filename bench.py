@@ -516,11 +516,17 @@ def cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, cap_s):
         layers += 1
         evict_s += t_ev
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    cpu_model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            cpu_model = next((line.split(":", 1)[1].strip() for line in f if line.startswith("model name")), cpu_model)
+    except OSError:
+        pass
     return {"value": (done_tokens - done_kept) / evict_s, "unit": "evicted KV entries/s",
             "cores": threads, "kind": "oracle",
             "sample": f"layers 0..{layers - 1} of sequence 0 ({done_tokens} head-tokens), numpy fp64, "
                       f"{spent:.1f} s including the decode leg",
-            "host_cpus": os.cpu_count()}
+            "host_cpus": os.cpu_count(), "cpu_model": cpu_model}
 
 
 if __name__ == "__main__":
