@@ -14,8 +14,8 @@
 //
 // Three kernels, no atomics, every output element written once:
 //   masked_attn_bwd_prep_kernel   D_i for every query row.
-//   masked_attn_bwd_dkv_kernel    one block per KV head and 128 keys: K and V rows of the block stay in
-//                                 registers as matrix operands, the Q and dO rows of all later queries
+//   masked_attn_bwd_dkv_kernel    one block (eight waves, 16 keys each) per KV head and 128 keys: K and V rows of
+//                                 the block stay in registers as matrix operands, the Q and dO rows of all later queries
 //                                 (and of every query head of the group) stream through LDS; yields
 //                                 dK, dV and dm of its keys.
 //   masked_attn_bwd_dq_kernel     one block per query head and 128 queries: Q and dO rows in registers,
@@ -267,16 +267,20 @@ masked_attn_bwd_dq_kernel(const uint16_t* __restrict__ q, const uint4* __restric
 constexpr int kDkvStepLds = kMbStep * 2 * kMbStride + 2 * kMbStep * 4;
 constexpr int kDkvLds = 2 * kMbSteps * kDkvStepLds;
 
+constexpr int kDkvWaves = 8;                   // two per SIMD
+constexpr int kDkvThreads = 64 * kDkvWaves;
+
 template <int kKB>
-__global__ void __launch_bounds__(kMbThreads, 1)   // 348 registers: accumulators 128, K and V operands 64, staging 33
+__global__ void __launch_bounds__(kDkvThreads, 2)
 masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                            const float* __restrict__ m, const float* __restrict__ lse, const float* __restrict__ dvec,
                            const uint4* __restrict__ d_o, int T, int n_kv_heads, int G, float scale, float* __restrict__ dk,
                            float* __restrict__ dv, float* __restrict__ dm) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveK = 16 * kKB;
-  constexpr int kBlockK = kMbWaves * kWaveK;
+  constexpr int kBlockK = kDkvWaves * kWaveK;
   constexpr int kTileLds = kMbSteps * kDkvStepLds;
+  constexpr int kRowSlots = 4 * kDkvWaves;               // staged rows covered by one pass of the block: 32, half a tile
   // blocks in order of decreasing work: early keys have the most queries after them; key tile slow, head fast
   const int h = (int)blockIdx.x % n_kv_heads;
   const int k0 = (int)blockIdx.x / n_kv_heads * kBlockK;
@@ -317,11 +321,11 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
   const int tiles_per_head = (T - q_first + kMbTile - 1) / kMbTile;
   const int n_items = G * tiles_per_head;
   const int srow = tid >> 4, spiece = tid & 15;
-  uint4 q_s0, q_s1, q_s2, q_s3, g_s0, g_s1, g_s2, g_s3;
+  uint4 q_s0, q_s1, g_s0, g_s1;   // thread (row slot tid / 16 in 0..31, piece tid % 16) moves rows slot and slot + 32
   float aux;   // threads 0..63: lse of query tid; threads 64..127: D of query tid - 64
 #define LKV_MB_LOAD_ROW(j_, qreg_, greg_, base_, q0_)                                                       \
   {                                                                                                         \
-    const int query = min((q0_) + srow + 16 * (j_), T - 1); /* past the end: the last row, masked later */  \
+    const int query = min((q0_) + srow + kRowSlots * (j_), T - 1); /* past the end: the last row, masked later */ \
     const uint32_t off = (uint32_t)query * 256u + (uint32_t)spiece * 16u; /* 32-bit offset, uniform base */ \
     qreg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(q + (base_) * kChunksPerRow) + off);   \
     greg_ = *reinterpret_cast<const uint4*>(reinterpret_cast<const unsigned char*>(d_o + (base_) * kChunksPerRow) + off); \
@@ -333,15 +337,15 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
     const size_t base_ = ((size_t)h * G + g_) * T;                                  \
     LKV_MB_LOAD_ROW(0, q_s0, g_s0, base_, q0_)                                      \
     LKV_MB_LOAD_ROW(1, q_s1, g_s1, base_, q0_)                                      \
-    LKV_MB_LOAD_ROW(2, q_s2, g_s2, base_, q0_)                                      \
-    LKV_MB_LOAD_ROW(3, q_s3, g_s3, base_, q0_)                                      \
     const int query_ = min(q0_ + (tid & (kMbTile - 1)), T - 1);                     \
     aux = (tid & kMbTile) ? dvec[base_ + query_] : lse[base_ + query_];             \
   }
+  /* staged row srow + kRowSlots * j of the 64-row tile: step (row / 32), row-in-step (row % 32) */
 #define LKV_MB_STORE_ROW(j_, qreg_, greg_)                                                                   \
   {                                                                                                          \
-    unsigned char* step_buf = buf + ((j_) >> 1) * kDkvStepLds;                                               \
-    const int row = srow + 16 * ((j_) & 1);                                                                  \
+    const int trow = srow + kRowSlots * (j_);                                                                \
+    unsigned char* step_buf = buf + (trow >> 5) * kDkvStepLds;                                               \
+    const int row = trow & 31;                                                                               \
     *reinterpret_cast<uint4*>(step_buf + row * kMbStride + spiece * 16) = qreg_;                            \
     *reinterpret_cast<uint4*>(step_buf + kMbStep * kMbStride + row * kMbStride + spiece * 16) = greg_;     \
   }
@@ -352,8 +356,6 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
     unsigned char* buf = smem + (it & 1) * kTileLds;
     LKV_MB_STORE_ROW(0, q_s0, g_s0)
     LKV_MB_STORE_ROW(1, q_s1, g_s1)
-    LKV_MB_STORE_ROW(2, q_s2, g_s2)
-    LKV_MB_STORE_ROW(3, q_s3, g_s3)
     if (tid < 2 * kMbTile) {
       // lse goes to the log2 domain; -inf (no weight in the prefix) becomes +inf so that every e_ij is 0
       const float val = (tid & kMbTile) ? aux : (aux == -INFINITY ? INFINITY : aux * kMbLog2e);
@@ -464,7 +466,7 @@ hipError_t masked_attn_bwd_prepare() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(masked_attn_bwd_dq_kernel<2>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kDqLds);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(masked_attn_bwd_dkv_kernel<2>),
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(masked_attn_bwd_dkv_kernel<1>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, kDkvLds);
 }
 
@@ -480,7 +482,7 @@ void launch_masked_attn_bwd(const void* q, const void* k, const void* v, const f
   const int64_t n_rows = (int64_t)n_q_heads * T;
   hipLaunchKernelGGL(masked_attn_bwd_prep_kernel, dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, stream,
                      reinterpret_cast<const float4*>(o), static_cast<const uint4*>(d_o), n_rows, workspace);
-  hipLaunchKernelGGL(masked_attn_bwd_dkv_kernel<2>, dim3((T + 127) / 128 * n_kv_heads), dim3(kMbThreads), kDkvLds, stream,
+  hipLaunchKernelGGL(masked_attn_bwd_dkv_kernel<1>, dim3((T + 127) / 128 * n_kv_heads), dim3(kDkvThreads), kDkvLds, stream,
                      static_cast<const uint4*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v), m,
                      lse, workspace, static_cast<const uint4*>(d_o), T, n_kv_heads, G, scale, dk, dv, dm);
   hipLaunchKernelGGL(masked_attn_bwd_dq_kernel<2>, dim3((T + 127) / 128 * n_q_heads), dim3(kMbThreads), kDqLds, stream,
