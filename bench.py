@@ -314,7 +314,7 @@ def training_attention(ctx, lkv, w, T, dev, reps=10):
     dk = torch.empty((w.H, T, w.d), dtype=torch.float32, device=dev)
     dv = torch.empty_like(dk)
     dm = torch.empty_like(m)
-    ws = torch.empty((lkv.lkv_masked_attn_backward_workspace_bytes(w.Hq, T),), dtype=torch.uint8, device=dev)
+    ws = torch.empty((lkv.lkv_masked_attn_backward_workspace_bytes(w.Hq, w.H, T),), dtype=torch.uint8, device=dev)
     scale = 1.0 / math.sqrt(w.d)
 
     def timed(fn):

@@ -301,11 +301,12 @@ lkv_status lkv_masked_attn_forward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv
  * d_o : DEVICE bf16 [n_q_heads, seq_len, d]
  * dq  : DEVICE fp32 [n_q_heads, seq_len, d];  dk, dv : DEVICE fp32 [n_kv_heads, seq_len, d]
  * dm  : DEVICE fp32 [n_kv_heads, seq_len]
- * workspace : DEVICE, at least lkv_masked_attn_backward_workspace_bytes(n_q_heads, seq_len) bytes,
- *             16-byte aligned (holds D).
+ * workspace : DEVICE, at least lkv_masked_attn_backward_workspace_bytes(n_q_heads, n_kv_heads, seq_len)
+ *             bytes, 16-byte aligned (holds D and, for short sequences with grouped heads, per-query-head
+ *             partial sums of dk, dv and dm that a last pass adds up in a fixed order).
  * Every output element is written exactly once (no atomics: results are reproducible bit for bit).
  * Errors as for the forward call, plus LKV_ERR_WORKSPACE. */
-size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t seq_len);
+size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len);
 lkv_status lkv_masked_attn_backward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
                                     int32_t head_dim, const void *q, const void *k, const void *v,
                                     const float *m, const float *o, const float *lse, const void *d_o,

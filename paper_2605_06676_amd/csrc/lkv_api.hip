@@ -669,9 +669,9 @@ lkv_status lkv_masked_attn_forward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv
   return LKV_OK;
 }
 
-size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t seq_len) {
-  if (n_q_heads < 1 || seq_len < 1) return 0;
-  return lkv::masked_attn_bwd_workspace_bytes(n_q_heads, seq_len);
+size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len) {
+  if (n_q_heads < 1 || n_kv_heads < 1 || n_q_heads % n_kv_heads != 0 || seq_len < 1) return 0;
+  return lkv::masked_attn_bwd_workspace_bytes(n_q_heads, n_kv_heads, seq_len);
 }
 
 lkv_status lkv_masked_attn_backward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
@@ -694,7 +694,7 @@ lkv_status lkv_masked_attn_backward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_k
     return fail(ctx, LKV_ERR_INVALID_ARG, "an input or output pointer is NULL");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o))
     return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v, o or d_o is not 16-byte aligned");
-  const size_t need = lkv::masked_attn_bwd_workspace_bytes(n_q_heads, seq_len);
+  const size_t need = lkv::masked_attn_bwd_workspace_bytes(n_q_heads, n_kv_heads, seq_len);
   if (workspace == nullptr || workspace_bytes < need)
     return fail(ctx, LKV_ERR_WORKSPACE, "masked attention backward workspace: need %zu bytes, got %zu", need, workspace_bytes);
   if (!aligned16(workspace)) return fail(ctx, LKV_ERR_WORKSPACE, "masked attention backward workspace is not 16-byte aligned");

@@ -61,7 +61,7 @@ void launch_masked_attn_fwd(const void* q, const void* k, const void* v, const f
 
 // masked_attn_bwd.hip
 hipError_t masked_attn_bwd_prepare();
-size_t masked_attn_bwd_workspace_bytes(int n_q_heads, int T);
+size_t masked_attn_bwd_workspace_bytes(int n_q_heads, int n_kv_heads, int T);
 void launch_masked_attn_bwd(const void* q, const void* k, const void* v, const float* m, const float* o,
                             const float* lse, const void* d_o, int n_q_heads, int n_kv_heads, int T, float scale,
                             float* dq, float* dk, float* dv, float* dm, float* workspace, hipStream_t stream);

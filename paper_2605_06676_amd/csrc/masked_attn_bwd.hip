@@ -49,6 +49,10 @@ constexpr int kMbStride = 288;                 // LDS bytes per staged row: meas
                                                // reads and for the transposing reads (272 was not, for the straight ones)
 constexpr float kMbLog2e = 1.4426950408889634f;
 
+#ifndef LKV_MB_SPLIT_BELOW_BLOCKS
+#define LKV_MB_SPLIT_BELOW_BLOCKS 512
+#endif
+
 __device__ __forceinline__ float mb_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 __device__ __forceinline__ bf16x8_t mb_read_straight(const unsigned char* p) {
@@ -274,16 +278,23 @@ template <int kKB>
 __global__ void __launch_bounds__(kDkvThreads, 2)
 masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
                            const float* __restrict__ m, const float* __restrict__ lse, const float* __restrict__ dvec,
-                           const uint4* __restrict__ d_o, int T, int n_kv_heads, int G, float scale, float* __restrict__ dk,
-                           float* __restrict__ dv, float* __restrict__ dm) {
+                           const uint4* __restrict__ d_o, int T, int n_kv_heads, int G, int split, float scale,
+                           float* __restrict__ dk, float* __restrict__ dv, float* __restrict__ dm) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int kWaveK = 16 * kKB;
   constexpr int kBlockK = kDkvWaves * kWaveK;
   constexpr int kTileLds = kMbSteps * kDkvStepLds;
   constexpr int kRowSlots = 4 * kDkvWaves;               // staged rows covered by one pass of the block: 32, half a tile
-  // blocks in order of decreasing work: early keys have the most queries after them; key tile slow, head fast
-  const int h = (int)blockIdx.x % n_kv_heads;
-  const int k0 = (int)blockIdx.x / n_kv_heads * kBlockK;
+  // A block owns 128 keys of one KV head and the query heads g_lo .. g_lo + g_cnt - 1 of its group: all of them
+  // (split = 1, results go straight to dk, dv, dm) or one each (split = G: results are per-query-head partial sums,
+  // row `unit` of buffers the host passes in place of the outputs, added up by the reduce kernel).  Blocks in order
+  // of decreasing work: early keys have the most queries after them; key tile slow, unit fast.
+  const int n_units = n_kv_heads * split;
+  const int unit = (int)blockIdx.x % n_units;
+  const int h = unit / split;
+  const int g_cnt = G / split;
+  const int g_lo = (unit - h * split) * g_cnt;
+  const int k0 = (int)blockIdx.x / n_units * kBlockK;
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = tid >> 6;
@@ -319,7 +330,7 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
   // streamed items: for every query head of the group, the 64-query tiles from the one that holds query k0 on
   const int q_first = k0 / kMbTile * kMbTile;
   const int tiles_per_head = (T - q_first + kMbTile - 1) / kMbTile;
-  const int n_items = G * tiles_per_head;
+  const int n_items = g_cnt * tiles_per_head;
   const int srow = tid >> 4, spiece = tid & 15;
   uint4 q_s0, q_s1, g_s0, g_s1;   // thread (row slot tid / 16 in 0..31, piece tid % 16) moves rows slot and slot + 32
   float aux;   // threads 0..63: lse of query tid; threads 64..127: D of query tid - 64
@@ -334,7 +345,7 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
   {                                                                                 \
     const int g_ = (it_) / tiles_per_head;                                          \
     const int q0_ = q_first + ((it_) - g_ * tiles_per_head) * kMbTile;              \
-    const size_t base_ = ((size_t)h * G + g_) * T;                                  \
+    const size_t base_ = ((size_t)h * G + g_lo + g_) * T;                           \
     LKV_MB_LOAD_ROW(0, q_s0, g_s0, base_, q0_)                                      \
     LKV_MB_LOAD_ROW(1, q_s1, g_s1, base_, q0_)                                      \
     const int query_ = min(q0_ + (tid & (kMbTile - 1)), T - 1);                     \
@@ -447,19 +458,40 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
     s += __shfl_xor(s, 16, 64);
     s += __shfl_xor(s, 32, 64);
     const int key = kw0 + 16 * kb + c;
-    if (r == 0 && key < T) dm[(size_t)h * T + key] = s;
+    if (r == 0 && key < T) dm[(size_t)unit * T + key] = s;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int krow = kw0 + 16 * kb + 4 * r + e;
       if (krow < T) {
 #pragma unroll
         for (int ct = 0; ct < 8; ++ct) {
-          dv[((size_t)h * T + krow) * kHeadDim + 16 * ct + c] = acc_v[kb][ct][e];
-          dk[((size_t)h * T + krow) * kHeadDim + 16 * ct + c] = acc_k[kb][ct][e] * scale;
+          dv[((size_t)unit * T + krow) * kHeadDim + 16 * ct + c] = acc_v[kb][ct][e];
+          dk[((size_t)unit * T + krow) * kHeadDim + 16 * ct + c] = acc_k[kb][ct][e] * scale;
         }
       }
     }
   }
+}
+
+// out[h][i] = sum over the G query heads of the group of part[h * G + g][i]; `per_head` elements per head, in
+// units of float4 when kVec4 (dK and dV) and of floats otherwise (dm).  Fixed order: reproducible.
+template <typename Vec>
+__global__ void __launch_bounds__(256)
+masked_attn_bwd_reduce_kernel(const Vec* __restrict__ part, Vec* __restrict__ out, int64_t per_head, int G) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int h = blockIdx.y;
+  if (i >= per_head) return;
+  const Vec* src = part + (size_t)h * G * per_head + i;
+  Vec acc = src[0];
+  for (int g = 1; g < G; ++g) {
+    const Vec x = src[(size_t)g * per_head];
+    if constexpr (sizeof(Vec) == 16) {
+      acc.x += x.x; acc.y += x.y; acc.z += x.z; acc.w += x.w;
+    } else {
+      acc += x;
+    }
+  }
+  out[(size_t)h * per_head + i] = acc;
 }
 
 hipError_t masked_attn_bwd_prepare() {
@@ -470,9 +502,25 @@ hipError_t masked_attn_bwd_prepare() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, kDkvLds);
 }
 
-// workspace: D, one float per query row
-size_t masked_attn_bwd_workspace_bytes(int n_q_heads, int T) {
-  return ((size_t)n_q_heads * (size_t)T * sizeof(float) + 255) & ~(size_t)255;
+// One block per query head (partial sums + a reduce pass) pays when the blocks of a KV head's whole group would be
+// few and long: the longest of them walks G * T / 64 staged tiles one after the other.
+static bool dkv_split_by_query_head(int n_kv_heads, int G, int T) {
+#ifdef LKV_MB_SPLIT_ALWAYS
+  return G > 1;
+#else
+  return G > 1 && (int64_t)((T + 127) / 128) * n_kv_heads < LKV_MB_SPLIT_BELOW_BLOCKS;
+#endif
+}
+
+static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// workspace: D (one float per query row), then, when the dK/dV kernel is split by query head, the partial
+// dK, dV [n_q_heads, T, 128] and dm [n_q_heads, T]
+size_t masked_attn_bwd_workspace_bytes(int n_q_heads, int n_kv_heads, int T) {
+  size_t bytes = align256((size_t)n_q_heads * (size_t)T * sizeof(float));
+  if (n_kv_heads >= 1 && n_q_heads % n_kv_heads == 0 && dkv_split_by_query_head(n_kv_heads, n_q_heads / n_kv_heads, T))
+    bytes += 2 * align256((size_t)n_q_heads * T * kHeadDim * sizeof(float)) + align256((size_t)n_q_heads * T * sizeof(float));
+  return bytes;
 }
 
 void launch_masked_attn_bwd(const void* q, const void* k, const void* v, const float* m, const float* o,
@@ -482,12 +530,29 @@ void launch_masked_attn_bwd(const void* q, const void* k, const void* v, const f
   const int64_t n_rows = (int64_t)n_q_heads * T;
   hipLaunchKernelGGL(masked_attn_bwd_prep_kernel, dim3((unsigned)((n_rows + 15) / 16)), dim3(256), 0, stream,
                      reinterpret_cast<const float4*>(o), static_cast<const uint4*>(d_o), n_rows, workspace);
-  hipLaunchKernelGGL(masked_attn_bwd_dkv_kernel<1>, dim3((T + 127) / 128 * n_kv_heads), dim3(kDkvThreads), kDkvLds, stream,
+  const bool split = dkv_split_by_query_head(n_kv_heads, G, T);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(workspace);
+  float* dk_part = reinterpret_cast<float*>(ws + align256((size_t)n_rows * sizeof(float)));
+  float* dv_part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(dk_part) + align256((size_t)n_rows * kHeadDim * sizeof(float)));
+  float* dm_part = reinterpret_cast<float*>(reinterpret_cast<unsigned char*>(dv_part) + align256((size_t)n_rows * kHeadDim * sizeof(float)));
+  const int n_units = split ? n_q_heads : n_kv_heads;
+  hipLaunchKernelGGL(masked_attn_bwd_dkv_kernel<1>, dim3((T + 127) / 128 * n_units), dim3(kDkvThreads), kDkvLds, stream,
                      static_cast<const uint4*>(q), static_cast<const uint16_t*>(k), static_cast<const uint16_t*>(v), m,
-                     lse, workspace, static_cast<const uint4*>(d_o), T, n_kv_heads, G, scale, dk, dv, dm);
+                     lse, workspace, static_cast<const uint4*>(d_o), T, n_kv_heads, G, split ? G : 1, scale,
+                     split ? dk_part : dk, split ? dv_part : dv, split ? dm_part : dm);
   hipLaunchKernelGGL(masked_attn_bwd_dq_kernel<2>, dim3((T + 127) / 128 * n_q_heads), dim3(kMbThreads), kDqLds, stream,
                      static_cast<const uint16_t*>(q), static_cast<const uint4*>(k), static_cast<const uint4*>(v), m, lse,
                      workspace, static_cast<const uint16_t*>(d_o), T, n_q_heads, G, scale, dq);
+  if (split) {
+    const int64_t vec_per_head = (int64_t)T * kHeadDim / 4;
+    const dim3 grid_v((unsigned)((vec_per_head + 255) / 256), n_kv_heads);
+    hipLaunchKernelGGL(masked_attn_bwd_reduce_kernel<float4>, grid_v, dim3(256), 0, stream,
+                       reinterpret_cast<const float4*>(dk_part), reinterpret_cast<float4*>(dk), vec_per_head, G);
+    hipLaunchKernelGGL(masked_attn_bwd_reduce_kernel<float4>, grid_v, dim3(256), 0, stream,
+                       reinterpret_cast<const float4*>(dv_part), reinterpret_cast<float4*>(dv), vec_per_head, G);
+    hipLaunchKernelGGL(masked_attn_bwd_reduce_kernel<float>, dim3((unsigned)((T + 255) / 256), n_kv_heads), dim3(256), 0,
+                       stream, dm_part, dm, (int64_t)T, G);
+  }
 }
 
 }  // namespace lkv

@@ -115,7 +115,7 @@ def load_library() -> C.CDLL:
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_float, C.c_void_p, C.c_void_p,
                                             C.c_void_p]
     lib.lkv_masked_attn_forward.restype = C.c_int
-    lib.lkv_masked_attn_backward_workspace_bytes.argtypes = [C.c_int32, C.c_int32]
+    lib.lkv_masked_attn_backward_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32]
     lib.lkv_masked_attn_backward_workspace_bytes.restype = C.c_size_t
     lib.lkv_masked_attn_backward.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32] + [C.c_void_p] * 7 + [
         C.c_float] + [C.c_void_p] * 5 + [C.c_size_t, C.c_void_p]
@@ -359,8 +359,8 @@ def lkv_masked_attn_forward(ctx: Context, q, k, v, m, scale: float, o, lse, stre
                                                _ptr(o), _ptr(lse), _stream_ptr(stream)))
 
 
-def lkv_masked_attn_backward_workspace_bytes(n_q_heads: int, seq_len: int) -> int:
-    return int(load_library().lkv_masked_attn_backward_workspace_bytes(n_q_heads, seq_len))
+def lkv_masked_attn_backward_workspace_bytes(n_q_heads: int, n_kv_heads: int, seq_len: int) -> int:
+    return int(load_library().lkv_masked_attn_backward_workspace_bytes(n_q_heads, n_kv_heads, seq_len))
 
 
 def lkv_masked_attn_backward(ctx: Context, q, k, v, m, o, lse, d_o, scale: float, dq, dk, dv, dm, workspace,

@@ -31,10 +31,15 @@ def test_calls_that_need_no_gpu():
     assert n <= (256 + 1258291 // 128 + 1) * 4 * 130 * 4 + 256
     assert lkv.lkv_decode_workspace_bytes(256, 0, 32, 8) >= 256 * 4 * 130 * 4
     assert lkv.lkv_decode_workspace_bytes(-1, 10, 32, 8) == 0
-    # the backward pass of the training-time attention keeps one float per query row
-    assert lkv.lkv_masked_attn_backward_workspace_bytes(32, 16384) == 32 * 16384 * 4
-    assert lkv.lkv_masked_attn_backward_workspace_bytes(3, 5) == 256          # rounded up to 256 bytes
-    assert lkv.lkv_masked_attn_backward_workspace_bytes(0, 5) == 0
+    # the backward pass of the training-time attention keeps one float per query row and, when the key-side
+    # kernel is split by query head (grouped heads, short sequences), partial dK, dV and dm per query head
+    d_only = 32 * 16384 * 4
+    assert lkv.lkv_masked_attn_backward_workspace_bytes(32, 32, 16384) == d_only        # no groups: never split
+    n = lkv.lkv_masked_attn_backward_workspace_bytes(32, 8, 4096)
+    assert n in (32 * 4096 * 4, 32 * 4096 * 4 * (1 + 2 * 128 + 1))
+    assert lkv.lkv_masked_attn_backward_workspace_bytes(3, 3, 5) == 256                 # rounded up to 256 bytes
+    assert lkv.lkv_masked_attn_backward_workspace_bytes(0, 1, 5) == 0
+    assert lkv.lkv_masked_attn_backward_workspace_bytes(4, 3, 5) == 0                   # 4 query heads, 3 KV heads
     # calls that need a context refuse a null one without touching the GPU
     assert lib.lkv_masked_attn_forward(None, 4, 2, 8, 128, None, None, None, None, 1.0, None, None, None) == 1
     assert lib.lkv_last_error(None) == b"context is NULL"

@@ -70,7 +70,7 @@ def test_captured_training_attention_replays_to_the_eager_result(ctx):
             "dk": torch.empty((H, T, 128), dtype=torch.float32, device="cuda"),
             "dv": torch.empty((H, T, 128), dtype=torch.float32, device="cuda"),
             "dm": torch.empty((H, T), dtype=torch.float32, device="cuda")}
-    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(Hq, T), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(Hq, H, T), dtype=torch.uint8, device="cuda")
 
     def both():
         lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, tm, G.SCALE, outs["o"], outs["lse"])

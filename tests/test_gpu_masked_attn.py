@@ -118,7 +118,7 @@ def run_backward(ctx, q, k, v, m, d_o):
     dk = torch.full(tk.shape, nan, dtype=torch.float32, device="cuda")
     dv = torch.full(tk.shape, nan, dtype=torch.float32, device="cuda")
     dm = torch.full(tm.shape, nan, dtype=torch.float32, device="cuda")
-    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(tq.shape[0], tq.shape[1]), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(tq.shape[0], tk.shape[0], tq.shape[1]), dtype=torch.uint8, device="cuda")
     lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, o, lse, tg, SCALE, dq, dk, dv, dm, ws)
     torch.cuda.synchronize()
     return [x.cpu().numpy() for x in (dq, dk, dv, dm)]
@@ -208,7 +208,7 @@ def test_full_size_sampled(ctx, Hq, H, T):
     dk = torch.empty((H, T, 128), dtype=torch.float32, device="cuda")
     dv = torch.empty_like(dk)
     dm = torch.empty_like(tm)
-    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(Hq, T), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(lkv.lkv_masked_attn_backward_workspace_bytes(Hq, H, T), dtype=torch.uint8, device="cuda")
     lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, tm, o, lse, tg, SCALE, dq, dk, dv, dm, ws)
     torch.cuda.synchronize()
 
