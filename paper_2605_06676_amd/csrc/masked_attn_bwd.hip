@@ -12,12 +12,14 @@
 // sums over the causal pairs j <= i, and for K, V and m also over the query heads of the GQA group.
 // Queries whose prefix carries no weight (L_i = -inf) contribute nothing.
 //
-// Three kernels, no atomics, every output element written once:
+// Three kernels (four for short sequences), no atomics, every output element written once:
 //   masked_attn_bwd_prep_kernel   D_i for every query row.
 //   masked_attn_bwd_dkv_kernel    one block (eight waves, 16 keys each) per KV head and 128 keys: K and V rows of
 //                                 the block stay in registers as matrix operands, the Q and dO rows of all later queries
 //                                 (and of every query head of the group) stream through LDS; yields
 //                                 dK, dV and dm of its keys.
+//                                 For short sequences a block takes one query head only and a reduce kernel adds
+//                                 the per-query-head partial results in a fixed order.
 //   masked_attn_bwd_dq_kernel     one block per query head and 128 queries: Q and dO rows in registers,
 //                                 K and V rows of all earlier keys stream through LDS; yields dQ.
 // Both recompute s and dP with the 16x16x32 bf16 matrix instruction.  As in the forward kernel the
