@@ -9,17 +9,18 @@
 // taken.  Next to the output the kernel returns log sum_k e^{s_ik} m_k per query, which the
 // backward pass uses to rebuild p from s.
 //
-// Tiling (flash-attention style, for 64-wide waves and the 16x16x32 bf16 matrix instruction).  A block of four waves
-// owns one query head and 64 * kQB consecutive queries, 16 * kQB per wave; it walks the key
-// tiles of 32 up to its diagonal.  A tile's K and V rows (and its 32 mask weights) are staged
-// once per block in LDS, double buffered with one barrier per tile, and read back as operands
-// by all four waves.  Per wave and tile:
-//   S^T[key, query] = K[key, :] . Q[query, :]^T      (A = K tile from LDS, B = Q^T held in registers)
-//   O[query, ch]   += P[query, key] V[key, ch]       (A = P, B = V tile by the transposing LDS read)
-// The accumulator layout of S^T (lane (rb, query) holds keys 4 rb .. 4 rb + 3 of a 16-key
-// half) is the A-operand layout of P for one K-step over the 32 keys, so probabilities go from
-// the first product to the second without leaving their lanes.  Each K and V operand read is
-// shared by the kQB query blocks of the wave.
+// Tiling (flash-attention style, for 64-wide waves and the 16x16x32 bf16 matrix instruction).  A block of four
+// waves owns one query head and 64 * kQB consecutive queries, 16 * kQB per wave; it walks the keys up to its
+// diagonal in tiles of 32 * kSteps.  A tile's K and V rows and its mask weights are staged once per block in
+// LDS, double buffered with one barrier per tile, and read back as operands by all four waves.  Per wave and
+// 32-key step:
+//   S^T[key, query] = K[key, :] . Q[query, :]^T      (A = K rows from LDS, B = Q^T held in registers)
+//   O[query, ch]   += P[query, key] V[key, ch]       (A = P, B = V rows by the transposing LDS read)
+// The accumulator layout of S^T (lane (rb, query) holds keys 4 rb .. 4 rb + 3 of a 16-key half) is the
+// A-operand layout of P for one K-step over the 32 keys, so probabilities go from the first product to the
+// second without leaving their lanes.  Each K and V operand read is shared by the kQB query blocks of the wave.
+// The online softmax is updated once per tile.  The denominator that divides the output is one more output
+// column of the second product (P times a column of ones), see acc_l below.
 #include <type_traits>
 
 #include "lkv_common.h"
@@ -52,7 +53,7 @@ __device__ __forceinline__ s16x4_t ma_read_tr16(const unsigned char* p) {
 }  // namespace
 
 template <int kQB, int kSteps>
-__global__ void __launch_bounds__(kMaThreads, kQB >= 4 ? 1 : 2)
+__global__ void __launch_bounds__(kMaThreads, 2)
 masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ k, const uint4* __restrict__ v,
                        const float* __restrict__ m, int T, int n_heads, int G, float scale, float* __restrict__ o,
                        float* __restrict__ lse) {
