@@ -237,3 +237,14 @@ def test_full_size_sampled(ctx, Hq, H, T):
         assert_rows_close(dk[h:h + 1, keys].cpu().numpy(), rk[:, keys], f"full size head {h} dK")
         assert_rows_close(dv[h:h + 1, keys].cpu().numpy(), rv[:, keys], f"full size head {h} dV")
         assert_rows_close(dm[h:h + 1, keys].cpu().numpy(), rm[:, keys], f"full size head {h} dm")
+
+
+def test_random_shapes(ctx):
+    # seeded draws of head counts and lengths, forward and backward, every element against the oracle
+    rng = np.random.default_rng(7)
+    for case in range(12):
+        H = int(rng.integers(1, 4))
+        G = int(rng.choice([1, 2, 3, 4, 8]))
+        T = int(rng.integers(1, 420))
+        check_forward(ctx, H * G, H, T, seed=100 + case)
+        check_backward(ctx, H * G, H, T, seed=100 + case)
