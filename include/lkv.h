@@ -305,6 +305,7 @@ lkv_status lkv_masked_attn_forward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv
  *             bytes, 16-byte aligned (holds D and, for short sequences with grouped heads, per-query-head
  *             partial sums of dk, dv and dm that a last pass adds up in a fixed order).
  * Every output element is written exactly once (no atomics: results are reproducible bit for bit).
+ * Outputs and workspace must not overlap the inputs or each other.
  * Errors as for the forward call, plus LKV_ERR_WORKSPACE. */
 size_t lkv_masked_attn_backward_workspace_bytes(int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len);
 lkv_status lkv_masked_attn_backward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len,
