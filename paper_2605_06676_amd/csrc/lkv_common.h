@@ -10,6 +10,13 @@ constexpr int kHeadDim = 128;          // d; a K or V row is 128 bf16 = 256 byte
 constexpr int kChunksPerRow = 16;      // 16-byte pieces per row
 constexpr int kMaxSeqPerLaunch = 32;   // sequences described by one by-value launch table
 
+// Register types of the matrix instructions (v_mfma_f32_16x16x32_bf16: eight bf16 per lane for the A and B
+// operands, four fp32 per lane for the accumulator) and of the transposing LDS read.
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
 // Per-launch description of up to kMaxSeqPerLaunch sequences, passed by value
 // in the kernel arguments (about 1 KB) so that no device-side table has to be
 // uploaded.  `first[i]` is the first work unit (block or segment) of sequence

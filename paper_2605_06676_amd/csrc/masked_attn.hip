@@ -30,11 +30,6 @@ namespace lkv {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x8_t __attribute__((ext_vector_type(8)));
-
 constexpr int kMaThreads = 256;
 constexpr int kMaWaves = kMaThreads / 64;
 constexpr int kMaKeys = 32;                   // keys per tile: one K-step of the P.V product

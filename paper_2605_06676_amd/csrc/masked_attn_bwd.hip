@@ -37,11 +37,6 @@ namespace lkv {
 
 namespace {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-typedef short s16x4_t __attribute__((ext_vector_type(4)));
-typedef short s16x8_t __attribute__((ext_vector_type(8)));
-
 constexpr int kMbThreads = 256;
 constexpr int kMbWaves = kMbThreads / 64;
 constexpr int kMbStep = 32;                    // streamed rows per K-step of the second products

@@ -22,9 +22,6 @@
 
 namespace lkv {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
-typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-
 constexpr int kMlpThreads = 256;
 constexpr int kMlpWaves = kMlpThreads / 64;
 constexpr int kMlpTokTile = 16;                       // tokens per MFMA N tile
