@@ -50,3 +50,15 @@ def test_config_table_shapes():
     sc = W.draw_scorer(W.CONFIGS[2])
     assert sc["w1"].shape == (32, 1, 64, 256) and sc["w1"].dtype == np.uint16
     assert abs(W.bf16_bits_to_f32(sc["w1"]).std() - 0.02) < 1e-3
+
+
+def test_training_attention_draw():
+    q, k, v, m, d_o = W.draw_training_attention(8, 2, 500, seed=3)
+    assert q.shape == d_o.shape == (8, 500, 128) and k.shape == v.shape == (2, 500, 128) and m.shape == (2, 500)
+    assert q.dtype == np.uint16 and m.dtype == np.float32
+    again = W.draw_training_attention(8, 2, 500, seed=3)
+    assert all(np.array_equal(a, b) for a, b in zip((q, k, v, m, d_o), again))
+    assert not np.array_equal(m, W.draw_training_attention(8, 2, 500, seed=4)[3])
+    assert m.min() >= 0.0 and m.max() <= 1.0 and (m == 0).any() and (m == 1).any() and (m[:, 0] >= 0.25).all()
+    assert 0.1 < m.mean() < 0.35                       # most weights small, as late in the annealing
+    assert abs(W.bf16_bits_to_f32(k).std() - 1.0) < 0.02
