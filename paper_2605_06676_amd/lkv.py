@@ -353,8 +353,15 @@ def lkv_masked_decode_attn(ctx: Context, cache: Cache, q, mask: Sequence, scale:
 
 def lkv_masked_attn_forward(ctx: Context, q, k, v, m, scale: float, o, lse, stream=None) -> None:
     """q: bf16 [Hq, T, 128]; k, v: bf16 [H, T, 128]; m: fp32 [H, T]; o: fp32 [Hq, T, 128]; lse: fp32 [Hq, T]."""
+    import torch
+
     Hq, T, d = q.shape
     H = k.shape[0]
+    # what the library cannot see from pointers: element types and contiguity (sizes and head counts are its to check)
+    for t in (q, k, v):
+        assert t.dtype == torch.bfloat16 and t.is_cuda and t.is_contiguous()
+    for t in (m, o, lse):
+        assert t is None or (t.dtype == torch.float32 and t.is_cuda and t.is_contiguous())
     ctx._check(ctx.lib.lkv_masked_attn_forward(ctx.h, Hq, H, T, d, _ptr(q), _ptr(k), _ptr(v), _ptr(m), float(scale),
                                                _ptr(o), _ptr(lse), _stream_ptr(stream)))
 
@@ -367,8 +374,14 @@ def lkv_masked_attn_backward(ctx: Context, q, k, v, m, o, lse, d_o, scale: float
                              stream=None) -> None:
     """q, d_o: bf16 [Hq, T, 128]; k, v: bf16 [H, T, 128]; m: fp32 [H, T]; o: fp32 [Hq, T, 128]; lse: fp32 [Hq, T];
     dq fp32 [Hq, T, 128]; dk, dv fp32 [H, T, 128]; dm fp32 [H, T]."""
+    import torch
+
     Hq, T, d = q.shape
     H = k.shape[0]
+    for t in (q, k, v, d_o):
+        assert t.dtype == torch.bfloat16 and t.is_cuda and t.is_contiguous()
+    for t in (m, o, lse, dq, dk, dv, dm):
+        assert t is None or (t.dtype == torch.float32 and t.is_cuda and t.is_contiguous())
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     ctx._check(ctx.lib.lkv_masked_attn_backward(ctx.h, Hq, H, T, d, _ptr(q), _ptr(k), _ptr(v), _ptr(m), _ptr(o),
                                                 _ptr(lse), _ptr(d_o), float(scale), _ptr(dq), _ptr(dk), _ptr(dv),
