@@ -186,7 +186,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16 in, fp32 accumulate", "data": "synthetic",
+        "dtype": "bf16", "accumulate": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_seq": w.n_seq, "layers": w.L, "kv_heads": w.H, "q_heads": w.Hq,
                    "seq_len": Ts if len(set(Ts)) > 1 else Ts[0], "head_tokens": N, "kept": total,
                    "retention": rho, "scorer": w.scorer if w.scorer == "linear" else f"mlp256-{w.hidden}-{w.act}"},
@@ -332,7 +332,7 @@ def training_attention(ctx, lkv, w, T, dev, reps=10):
     t_fwd = timed(lambda: lkv.lkv_masked_attn_forward(ctx, q, k, v, m, scale, o, lse))
     t_bwd = timed(lambda: lkv.lkv_masked_attn_backward(ctx, q, k, v, m, o, lse, d_o, scale, dq, dk, dv, dm, ws))
     product = 2.0 * w.d * (T * (T + 1) / 2) * w.Hq      # one causal (query, key) product over d channels, all heads
-    out = {"tokens": T, "n_q_heads": w.Hq, "n_kv_heads": w.H, "dtype": "bf16 operands, fp32 accumulate"}
+    out = {"tokens": T, "n_q_heads": w.Hq, "n_kv_heads": w.H, "dtype": "bf16", "accumulate": "f32"}
     for name, t, n_products, executed in (("forward", t_fwd, 2, 2), ("backward", t_bwd, 5, 7)):
         tf = n_products * product / (t * 1e9)
         out[name] = {"ms": t, "roofline": {"bound": "mfma", "achieved": tf, "peak": MFMA_BF16_PEAK_TFLOPS,
