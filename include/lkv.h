@@ -319,7 +319,9 @@ lkv_status lkv_masked_attn_backward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_k
 /* Forward Soft-TopK operator ST_k of Sec. 3.2 (threshold in closed form, Eq. 2 and App. A.1):
  *   y_i = f(x_i / tau - lambda),  f(z) = (1 + sgn(z)(1 - e^{-|z|})) / 2,  sum_i y_i = k.
  * fp64 arithmetic, sums carried as logarithms (any tau > 0 is safe).  One workgroup sorts the
- * input in LDS, hence the size limit lkv_soft_topk_max_n (32768 for fp32 input, 16384 for fp64).
+ * input in LDS when it fits (32768 fp32 or 16384 fp64 values); longer inputs, up to
+ * lkv_soft_topk_max_n() = 2^22 values, take the same closed form after the split index has been
+ * found by bracketing the threshold with passes over the input (about 50 of them).
  * x    : DEVICE fp32 [n] (x_is_f64 = 0) or fp64 [n] (x_is_f64 = 1); finite values
  * k    : target sum, in the open interval (0, n)
  * tau  : temperature, > 0

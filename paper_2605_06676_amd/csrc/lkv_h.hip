@@ -187,6 +187,149 @@ soft_topk_kernel(const X* __restrict__ x, int n, int P, double k, double tau, do
   }
 }
 
+// ---- inputs too long to sort in LDS ---------------------------------------------------------------
+// The threshold is the root of g(v) = sum_i f(x_i / tau - v) - k, which decreases in v.  One workgroup
+// brackets it from the extremes of the input, then halves the bracket, one pass over the input per
+// step, until no input value lies inside: from then on the split index m is known, the sums S1 and
+// S2 take one more pass, and lambda comes out of the same closed form as above (App. A.1).  No sort,
+// any n; about 50 passes over an input that stays in the L2 cache.
+constexpr int kStLargeMaxN = 1 << 22;
+
+struct StLargeShared {
+  double d[4][16];
+  long long c[2][16];
+  double out_d[4];
+  long long out_c[2];
+};
+
+// block-wide sums of up to four doubles and two counters (fixed order: reproducible), result to every thread
+__device__ inline void st_block_sum(StLargeShared* sh, double (&v)[4], long long (&cnt)[2]) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] += __shfl_xor(v[i], off, 64);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) cnt[i] += __shfl_xor(cnt[i], off, 64);
+  }
+  __syncthreads();   // the previous round's results have been read
+  if (lane == 0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sh->d[i][wave] = v[i];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) sh->c[i][wave] = cnt[i];
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int i = 0; i < 4; ++i) {
+      double a = 0.0;
+      for (int w = 0; w < kStThreads / 64; ++w) a += sh->d[i][w];
+      sh->out_d[i] = a;
+    }
+    for (int i = 0; i < 2; ++i) {
+      long long a = 0;
+      for (int w = 0; w < kStThreads / 64; ++w) a += sh->c[i][w];
+      sh->out_c[i] = a;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < 4; ++i) v[i] = sh->out_d[i];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) cnt[i] = sh->out_c[i];
+}
+
+template <typename X>
+__global__ void __launch_bounds__(kStThreads)
+soft_topk_large_kernel(const X* __restrict__ x, int n, double k, double tau, double* __restrict__ y,
+                       double* __restrict__ info, int32_t* __restrict__ budgets, double t) {
+  __shared__ StLargeShared sh;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+
+  // extremes of z = x / tau
+  double zmin = INFINITY, zmax = -INFINITY;
+  for (int i = tid; i < n; i += kStThreads) {
+    const double z = (double)x[i] / tau;
+    zmin = fmin(zmin, z);
+    zmax = fmax(zmax, z);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    zmin = fmin(zmin, __shfl_xor(zmin, off, 64));
+    zmax = fmax(zmax, __shfl_xor(zmax, off, 64));
+  }
+  if (lane == 0) { sh.d[0][wave] = zmin; sh.d[1][wave] = zmax; }
+  __syncthreads();
+  for (int w = 0; w < kStThreads / 64; ++w) { zmin = fmin(zmin, sh.d[0][w]); zmax = fmax(zmax, sh.d[1][w]); }
+  // g > 0 at lo: every f is at least 1 - e^{-L} / 2 with L >= 1 + log(n / (2 (n - k))), so the sum exceeds
+  // n - (n - k) / e > k; g < 0 at hi: every f is at most e^{-U} / 2 with U >= 1 + log(n / (2 k)): sum <= k / e
+  double lo = zmin - 1.0 - fmax(0.0, log((double)n / (2.0 * ((double)n - k))));
+  double hi = zmax + 1.0 + fmax(0.0, log((double)n / (2.0 * k)));
+
+  for (int step = 0; step < 200; ++step) {
+    const double mid = 0.5 * (lo + hi);
+    if (!(mid > lo && mid < hi)) break;   // the bracket is down to neighbouring numbers: what is inside ties with the root
+    double v[4] = {0.0, 0.0, 0.0, 0.0};
+    long long cnt[2] = {0, 0};
+    for (int i = tid; i < n; i += kStThreads) {
+      const double z = (double)x[i] / tau;
+      const double d = z - mid;
+      v[0] += d >= 0.0 ? 1.0 - 0.5 * exp(-d) : 0.5 * exp(d);
+      cnt[0] += (z >= lo && z < mid) ? 1 : 0;
+      cnt[1] += (z >= mid && z < hi) ? 1 : 0;
+    }
+    st_block_sum(&sh, v, cnt);
+    long long inside;
+    if (v[0] - k > 0.0) { lo = mid; inside = cnt[1]; }
+    else { hi = mid; inside = cnt[0]; }
+    if (inside == 0) break;
+  }
+
+  // split: the head is {z >= hi}; log S1 = log sum_head e^{-z}, log S2 = log sum_rest e^{z}, each against its own maximum
+  double s1_ref = -INFINITY, s2_ref = -INFINITY;
+  for (int i = tid; i < n; i += kStThreads) {
+    const double z = (double)x[i] / tau;
+    if (z >= hi) s1_ref = fmax(s1_ref, -z);
+    else s2_ref = fmax(s2_ref, z);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    s1_ref = fmax(s1_ref, __shfl_xor(s1_ref, off, 64));
+    s2_ref = fmax(s2_ref, __shfl_xor(s2_ref, off, 64));
+  }
+  __syncthreads();
+  if (lane == 0) { sh.d[2][wave] = s1_ref; sh.d[3][wave] = s2_ref; }
+  __syncthreads();
+  for (int w = 0; w < kStThreads / 64; ++w) { s1_ref = fmax(s1_ref, sh.d[2][w]); s2_ref = fmax(s2_ref, sh.d[3][w]); }
+  double v[4] = {0.0, 0.0, 0.0, 0.0};
+  long long cnt[2] = {0, 0};
+  for (int i = tid; i < n; i += kStThreads) {
+    const double z = (double)x[i] / tau;
+    if (z >= hi) { v[0] += exp(-z - s1_ref); cnt[0] += 1; }
+    else v[1] += exp(z - s2_ref);
+  }
+  st_block_sum(&sh, v, cnt);
+  const int m = (int)cnt[0];
+  const double log_s1 = m > 0 ? s1_ref + log(v[0]) : -INFINITY;
+  const double log_s2 = m < n ? s2_ref + log(v[1]) : -INFINITY;
+  // closed form of App. A.1 for y = e^lambda: S1 y^2 + 2 (k - m) y - S2 = 0, positive root
+  const double d = k - (double)m;
+  double lambda;
+  if (m == 0) lambda = log_s2 - log(2.0 * k);
+  else if (m == n) lambda = log(2.0 * ((double)n - k)) - log_s1;
+  else if (d >= 0.0) lambda = log_s2 - log_root_plus(d, log_s1 + log_s2);
+  else lambda = log_root_plus(-d, log_s1 + log_s2) - log_s1;
+  if (tid == 0 && info != nullptr) {
+    info[0] = lambda;
+    info[1] = (double)m;
+  }
+  for (int i = tid; i < n; i += kStThreads) {
+    const double z = (double)x[i] / tau - lambda;
+    const double r = z >= 0.0 ? 1.0 - 0.5 * exp(-z) : 0.5 * exp(z);
+    if (y != nullptr) y[i] = r;
+    if (budgets != nullptr) budgets[i] = (int32_t)floor(r * t);
+  }
+}
+
 // s = w2 . SiLU(W1 e + b1) (+ b2) for one head per block
 __global__ void __launch_bounds__(256)
 head_scores_kernel(const float* __restrict__ emb, const float* __restrict__ w1, const float* __restrict__ b1,
@@ -223,7 +366,8 @@ size_t soft_topk_lds(int P, size_t key_bytes) {
 
 }  // namespace
 
-int soft_topk_max_n(bool is_f64) { return kStKeyBytes / (int)(is_f64 ? sizeof(uint64_t) : sizeof(uint32_t)); }
+int soft_topk_sorted_max_n(bool is_f64) { return kStKeyBytes / (int)(is_f64 ? sizeof(uint64_t) : sizeof(uint32_t)); }
+int soft_topk_max_n(bool) { return kStLargeMaxN; }
 int head_scores_max_hidden() { return 4096; }
 
 hipError_t lkv_h_prepare() {
@@ -238,6 +382,15 @@ hipError_t lkv_h_prepare() {
 // y, info and budgets may each be null; y may alias x when x is fp64
 void launch_soft_topk(const void* x, bool is_f64, int n, double k, double tau, double* y, double* info,
                       int32_t* budgets, double t, hipStream_t stream) {
+  if (n > soft_topk_sorted_max_n(is_f64)) {   // too long to sort in LDS: bracketing passes over the input
+    if (is_f64)
+      hipLaunchKernelGGL(soft_topk_large_kernel<double>, dim3(1), dim3(kStThreads), 0, stream,
+                         static_cast<const double*>(x), n, k, tau, y, info, budgets, t);
+    else
+      hipLaunchKernelGGL(soft_topk_large_kernel<float>, dim3(1), dim3(kStThreads), 0, stream,
+                         static_cast<const float*>(x), n, k, tau, y, info, budgets, t);
+    return;
+  }
   const int P = padded_size(n);
   if (is_f64)
     hipLaunchKernelGGL((soft_topk_kernel<double, uint64_t>), dim3(1), dim3(kStThreads), soft_topk_lds(P, 8), stream,

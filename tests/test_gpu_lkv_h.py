@@ -64,13 +64,52 @@ def test_soft_topk_sizes(ctx, n, dtype):
         _check(ctx, x, k, 1.0, f"n={n} k={k}")
 
 
-def test_soft_topk_largest_fp32_input(ctx):
-    n = lkv.lkv_soft_topk_max_n(False)
-    assert n == 32768
+def test_soft_topk_largest_sorted_fp32_input(ctx):
+    n = 32768                                   # the longest input that is sorted in LDS
     rng = np.random.default_rng(5)
     x = rng.standard_normal(n).astype(np.float32)
     _check(ctx, x, 0.02 * n, 1.0, "n=32768")
     _check(ctx, x, n - 40.5, 1.0, "n=32768 k near n")
+
+
+@pytest.mark.parametrize("n,dtype", [(32769, np.float32), (16385, np.float64), (131072, np.float32)])
+def test_soft_topk_long_inputs(ctx, n, dtype):
+    # beyond the sorted sizes the threshold is bracketed by passes over the input; same operator, same bounds
+    # (the oracle takes seconds per call at these sizes, hence few cases)
+    rng = np.random.default_rng(n)
+    x = (rng.standard_normal(n) * 1.5).astype(dtype)
+    _check(ctx, x, 0.1 * n, 1.0, f"n={n} k=0.1 n")
+    _check(ctx, x, n - 3.5, 1.0, f"n={n} k near n")
+    if n < 100000:
+        _check(ctx, x, 1.0, 1.0, f"n={n} k=1")
+        _check(ctx, x, 0.5 * n + 0.25, 30.0, f"n={n} hot")
+    _check(ctx, x, 0.15 * n, 1e-3, f"n={n} cold")
+
+
+def test_soft_topk_long_input_special_cases(ctx):
+    n = 50000
+    y, _, _ = _gpu_soft_topk(ctx, np.full(n, 0.75), 0.15 * n, 1.0)          # all equal: k / n everywhere
+    assert np.allclose(y, 0.15, rtol=1e-12)
+    xt = np.repeat(np.array([2.0, 1.0, 0.0, -1.0]), n // 4)                  # the threshold falls on a tie
+    _check(ctx, xt, 0.5 * n, 1.0, "long ties")
+    _check(ctx, xt.astype(np.float32), 0.3 * n, 0.5, "long ties inside a group")
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal(n)
+    y0, lam0, m0 = _gpu_soft_topk(ctx, x, 5000.5, 1.0)
+    y1, lam1, m1 = _gpu_soft_topk(ctx, x.copy(), 5000.5, 1.0, in_place=True)  # in place, and repeatable
+    assert np.array_equal(y0, y1) and lam0 == lam1 and m0 == m1
+
+
+def test_soft_topk_cold_limit_is_the_hard_topk_at_131072_tokens(ctx):
+    # Sec. 3.2 at the length of the long-context workload: ST_b(u / tau) -> TopK(u, b) as tau -> 0+
+    rng = np.random.default_rng(11)
+    T = 131072
+    u = rng.permutation(T).astype(np.float32) / np.float32(T)               # distinct scores
+    b = 13107
+    y, _, m = _gpu_soft_topk(ctx, u, float(b), 1e-7)
+    mask = np.zeros(T)
+    mask[O.select(u, b)] = 1.0
+    assert np.array_equal(np.round(y), mask) and m == b
 
 
 @pytest.mark.parametrize("tau", [10.0, 0.3, 1e-2, 1e-4])
@@ -135,9 +174,11 @@ def test_soft_topk_argument_errors(ctx):
         with pytest.raises(lkv.LkvError) as e:
             lkv.lkv_soft_topk(ctx, x, k, tau, y)
         assert e.value.status == 1
-    big = torch.zeros(16385, dtype=torch.float64, device="cuda")
+    limit = lkv.lkv_soft_topk_max_n(False)
+    assert limit == lkv.lkv_soft_topk_max_n(True) == 1 << 22
+    big = torch.zeros(limit + 1, dtype=torch.float32, device="cuda")
     with pytest.raises(lkv.LkvError) as e:
-        lkv.lkv_soft_topk(ctx, big, 5.0, 1.0, torch.empty_like(big))
+        lkv.lkv_soft_topk(ctx, big, 5.0, 1.0, torch.empty(limit + 1, dtype=torch.float64, device="cuda"))
     assert e.value.status == 2
     torch.cuda.synchronize()
 
