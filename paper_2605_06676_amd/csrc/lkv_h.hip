@@ -9,6 +9,8 @@
 // without trying every m: g(v) = sum_i f(x_i - v) - k decreases in v, so x_j >= lambda exactly
 // when g(x_j) <= 0, and g at the element of rank j needs only the prefix sum S1(j) and the suffix
 // sum S2(j).  All sums are carried as logarithms so that x / tau with a tiny tau cannot overflow.
+// Inputs too long for the LDS sort go through soft_topk_large_kernel further down (no sort: the
+// threshold is bracketed by passes over the input).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
