@@ -73,6 +73,27 @@ lkv_status check_cache(lkv_ctx* ctx, const lkv_cache* c, bool need_kv) {
   return LKV_OK;
 }
 
+// Scorer description: kinds, pointers, widths.  `mfma_widths`: the cache-wide scoring kernels take hidden widths
+// that are multiples of 16 up to 128; the one-token path of lkv_append takes any width up to 128.
+lkv_status check_scorer(lkv_ctx* ctx, const lkv_scorer* s, bool mfma_widths) {
+  if (s == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer is NULL");
+  if (s->kind != LKV_SCORER_LINEAR && s->kind != LKV_SCORER_MLP)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", s->kind);
+  if (s->w1 == nullptr || s->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
+  if (!aligned16(s->w1)) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 is not 16-byte aligned");
+  if (s->per_head != 0 && s->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
+  if (s->kind == LKV_SCORER_MLP) {
+    if (s->act != LKV_ACT_SILU && s->act != LKV_ACT_GELU_ERF)
+      return fail(ctx, LKV_ERR_INVALID_ARG, "unknown activation %d", s->act);
+    if (s->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
+    if (mfma_widths && (s->hidden < 16 || s->hidden > 128 || s->hidden % 16 != 0))
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must be a multiple of 16 in [16, 128]", s->hidden);
+    if (!mfma_widths && (s->hidden < 1 || s->hidden > 128))
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must lie in [1, 128]", s->hidden);
+  }
+  return LKV_OK;
+}
+
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 }  // namespace
@@ -126,19 +147,8 @@ lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* sco
                      void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, cache, true)) return st;
-  if (scorer == nullptr || scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer or scores is NULL");
-  if (scorer->kind != LKV_SCORER_LINEAR && scorer->kind != LKV_SCORER_MLP)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", scorer->kind);
-  if (scorer->w1 == nullptr || scorer->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
-  if (!aligned16(scorer->w1)) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 is not 16-byte aligned");
-  if (scorer->per_head != 0 && scorer->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
-  if (scorer->kind == LKV_SCORER_MLP) {
-    if (scorer->act != LKV_ACT_SILU && scorer->act != LKV_ACT_GELU_ERF)
-      return fail(ctx, LKV_ERR_INVALID_ARG, "unknown activation %d", scorer->act);
-    if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
-    if (scorer->hidden < 16 || scorer->hidden > 128 || scorer->hidden % 16 != 0)
-      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must be a multiple of 16 in [16, 128]", scorer->hidden);
-  }
+  if (scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores is NULL");
+  if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
   const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
   for (int s = 0; s < cache->n_seq; ++s) {
     if (scores[s] == nullptr || !aligned16(scores[s]))
@@ -395,19 +405,13 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   if (!aligned16(kp) || !aligned16(vp)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is not 16-byte aligned");
 
   // score: the scorer parameters of this layer
-  if (scorer->kind != LKV_SCORER_LINEAR && scorer->kind != LKV_SCORER_MLP)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", scorer->kind);
-  if (scorer->w1 == nullptr || scorer->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
-  if (scorer->per_head != 0 && scorer->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
+  if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
   lkv_scorer sl = *scorer;
   const size_t rows = (size_t)layer_index * (scorer->per_head ? H : 1);   // scorer rows ahead of this layer
   if (scorer->kind == LKV_SCORER_LINEAR) {
     sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * 2 * lkv::kHeadDim;
     sl.b1 = scorer->b1 + rows;
   } else {
-    if (scorer->hidden < 16 || scorer->hidden > 128 || scorer->hidden % 16 != 0)
-      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must be a multiple of 16 in [16, 128]", scorer->hidden);
-    if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
     sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * (size_t)scorer->hidden * 2 * lkv::kHeadDim;
     sl.b1 = scorer->b1 + rows * scorer->hidden;
     sl.w2 = scorer->w2 + rows * scorer->hidden;
@@ -495,18 +499,7 @@ lkv_status lkv_append(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_t n_k
     return fail(ctx, LKV_ERR_INVALID_ARG, "a required pointer is NULL");
   if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(kp) || !aligned16(vp))
     return fail(ctx, LKV_ERR_INVALID_ARG, "k_new, v_new, kp or vp is not 16-byte aligned");
-  if (scorer->kind != LKV_SCORER_LINEAR && scorer->kind != LKV_SCORER_MLP)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown scorer kind %d", scorer->kind);
-  if (scorer->w1 == nullptr || scorer->b1 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 or b1 is NULL");
-  if (!aligned16(scorer->w1)) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w1 is not 16-byte aligned");
-  if (scorer->per_head != 0 && scorer->per_head != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "per_head must be 0 or 1");
-  if (scorer->kind == LKV_SCORER_MLP) {
-    if (scorer->act != LKV_ACT_SILU && scorer->act != LKV_ACT_GELU_ERF)
-      return fail(ctx, LKV_ERR_INVALID_ARG, "unknown activation %d", scorer->act);
-    if (scorer->w2 == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scorer w2 is NULL");
-    if (scorer->hidden < 1 || scorer->hidden > 128)
-      return fail(ctx, LKV_ERR_UNSUPPORTED, "hidden = %d must lie in [1, 128]", scorer->hidden);
-  }
+  if (lkv_status st = check_scorer(ctx, scorer, false)) return st;
   lkv::launch_append((int)n_seg, n_layers * n_kv_heads, n_kv_heads, scorer->kind == LKV_SCORER_LINEAR ? 0 : 1,
                      scorer->act == LKV_ACT_SILU ? 0 : 1, scorer->hidden, scorer->per_head,
                      static_cast<const uint16_t*>(scorer->w1), scorer->b1, scorer->w2, scorer->b2, k_new, v_new, kp, vp,
