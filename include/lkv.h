@@ -52,6 +52,7 @@ typedef enum {
 
 typedef enum { LKV_SCORER_LINEAR = 0, LKV_SCORER_MLP = 1 } lkv_scorer_kind;
 typedef enum { LKV_ACT_SILU = 0, LKV_ACT_GELU_ERF = 1 } lkv_act;
+typedef enum { LKV_POOL_MAX = 0, LKV_POOL_AVG = 1 } lkv_pool;
 
 /* Geometry of a prefilled KV cache (Sec. 3.1 of the paper: per layer and KV
  * head, K and V are t x d matrices).  The struct and the arrays it points to
@@ -104,6 +105,41 @@ const char *lkv_version(void);
  * scores : HOST [n_seq] of DEVICE pointers, each fp32 [L, H, T_s]. */
 lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *scorer,
                      float *const *scores, void *stream);
+
+/* Observation-window token scoring: the attention-based selection policy that
+ * the ablation of Sec. 4.4 combines with the LKV-H budgets (complexity O(W T)
+ * in the table of Sec. 4.5).  The paper names the policy and cites its
+ * publication for the rule; the rule as implemented here, every parameter an
+ * argument:
+ *   the window is the last W = `window` positions of the prompt; its query row
+ *   i stands at position T - W + i and sees keys 0 .. T - W + i;
+ *   a[hq, i, :] = softmax over those keys of scale * q_win[l, hq, i, :] . K[l, h, j, :],
+ *                 h = hq / (Hq / H);
+ *   vote[l, h, j] = mean over the query heads of h's group of sum_i a[hq, i, j],
+ *                 for the prefix tokens j < T - W;
+ *   scores[l, h, j] = centred pooling of vote[l, h, :] of width `pool_width`
+ *                 (stride 1, same length): LKV_POOL_MAX takes the largest vote
+ *                 in the part of [j - c, j + c] inside the prefix, LKV_POOL_AVG
+ *                 the sum over that part divided by pool_width, c = (pool_width - 1) / 2;
+ *   scores[l, h, j] = +inf for the window tokens j >= T - W,
+ * so that lkv_select with a budget b >= W keeps the window and the b - W prefix
+ * tokens with the largest pooled votes.  bf16 inputs, fp32 accumulation and
+ * fp32 softmax; each key row is read twice (once for the normalisers, once
+ * for the weights) and cache->v is not read.
+ * q_win     : HOST [n_seq] of DEVICE pointers, bf16 [L, Hq, W, 128]: the queries
+ *             of the last W positions (as they met the keys in prefill, i.e.
+ *             position-encoded like the cached keys)
+ * window    : 1 <= W <= every T_s, and (Hq / H) * W <= 128 (else LKV_ERR_UNSUPPORTED)
+ * pool_width: odd, 1 .. 63 (1 = no pooling); pool_kind: lkv_pool
+ * scale     : positive, finite (1 / sqrt(d) in Eq. 1)
+ * scores    : HOST [n_seq] of DEVICE pointers, each fp32 [L, H, T_s]
+ * workspace : DEVICE, 256-byte aligned, at least lkv_score_window_workspace_bytes(cache)
+ *             bytes (votes and per-block normaliser pairs, 12 bytes per cached
+ *             key row and head at most); contents are scratch. */
+size_t lkv_score_window_workspace_bytes(const lkv_cache *cache);
+lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *const *q_win, int32_t window,
+                            int32_t pool_width, int32_t pool_kind, float scale, float *const *scores,
+                            void *workspace, size_t workspace_bytes, void *stream);
 
 /* Head-wise budgeted hard top-k (Sec. 3.4, inference: m = TopK(u, b); budgets
  * b = floor(r t) come from LKV-H, Sec. 3.3, and are an input here).

@@ -201,6 +201,91 @@ lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* sco
   return LKV_OK;
 }
 
+size_t lkv_score_window_workspace_bytes(const lkv_cache* cache) {
+  if (cache == nullptr || cache->seq_len == nullptr || cache->n_seq < 1 || cache->n_layers < 1 || cache->n_kv_heads < 1)
+    return 0;
+  const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
+  size_t need = 0;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    if (cache->seq_len[s] < 1) return 0;
+    need += lkv::score_window_votes_bytes(heads, cache->seq_len[s]) + lkv::score_window_pairs_bytes(heads, cache->seq_len[s]);
+  }
+  return need;
+}
+
+lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* const* q_win, int32_t window,
+                            int32_t pool_width, int32_t pool_kind, float scale, float* const* scores,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (q_win == nullptr || scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q_win or scores is NULL");
+  if (window < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "window = %d must be >= 1", window);
+  if (pool_width < 1 || pool_width % 2 == 0 || pool_width > 63)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "pool_width = %d must be odd and lie in [1, 63]", pool_width);
+  if (pool_kind != LKV_POOL_MAX && pool_kind != LKV_POOL_AVG)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "unknown pooling kind %d", pool_kind);
+  if (!(scale > 0.f) || !std::isfinite(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale must be positive and finite");
+  const int G = cache->n_q_heads / cache->n_kv_heads;
+  const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
+  int64_t cells = 0;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    if (window > cache->seq_len[s])
+      return fail(ctx, LKV_ERR_INVALID_ARG, "window = %d exceeds seq_len[%d] = %d", window, s, cache->seq_len[s]);
+    if (q_win[s] == nullptr || !aligned16(q_win[s]))
+      return fail(ctx, LKV_ERR_INVALID_ARG, "q_win[%d] is NULL or not 16-byte aligned", s);
+    if (scores[s] == nullptr || !aligned16(scores[s]))
+      return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL or not 16-byte aligned", s);
+    cells += heads * cache->seq_len[s];
+  }
+  if ((int64_t)G * window > lkv::score_window_max_rows())
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "group %d x window %d exceeds %d query rows per KV head", G, window,
+                lkv::score_window_max_rows());
+  const size_t need = lkv_score_window_workspace_bytes(cache);
+  if (workspace == nullptr || workspace_bytes < need)
+    return fail(ctx, LKV_ERR_WORKSPACE, "window scoring workspace: need %zu bytes, got %zu", need, workspace_bytes);
+  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
+    return fail(ctx, LKV_ERR_WORKSPACE, "window scoring workspace is not 256-byte aligned");
+  const int rpb = lkv::score_window_rows_per_block(cells);
+  hipStream_t st = as_stream(stream);
+
+  // every sequence's blocks must fit one grid before anything is launched
+  for (int s = 0; s < cache->n_seq; ++s)
+    if (heads * ((cache->seq_len[s] + 127) / 128) >= ((int64_t)1 << 31) - 1)
+      return fail(ctx, LKV_ERR_UNSUPPORTED, "sequence %d is too long for one launch", s);
+
+  unsigned char* ws = static_cast<unsigned char*>(workspace);
+  int s = 0;
+  while (s < cache->n_seq) {
+    lkv::WinTable tab;
+    memset(&tab, 0, sizeof(tab));
+    int64_t blocks = 0, pool_blocks = 0;
+    int n = 0;
+    while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
+      const int T = cache->seq_len[s];
+      const int64_t mine = heads * ((T + rpb - 1) / rpb), pool = heads * ((T + 1023) / 1024);
+      if (n > 0 && (blocks + mine >= ((int64_t)1 << 31) - 1 || pool_blocks + pool >= ((int64_t)1 << 31) - 1)) break;
+      tab.k[n] = static_cast<const uint16_t*>(cache->k[s]);
+      tab.q[n] = static_cast<const uint16_t*>(q_win[s]);
+      tab.scores[n] = scores[s];
+      tab.votes[n] = reinterpret_cast<float*>(ws);
+      ws += lkv::score_window_votes_bytes(heads, T);
+      tab.partial[n] = reinterpret_cast<float*>(ws);
+      ws += lkv::score_window_pairs_bytes(heads, T);
+      tab.T[n] = T;
+      tab.first[n] = (int32_t)blocks;
+      blocks += mine;
+      pool_blocks += pool;
+      ++n;
+      ++s;
+    }
+    tab.first[n] = (int32_t)blocks;
+    tab.n = n;
+    lkv::launch_score_window(tab, (int)heads, window, G, pool_width, pool_kind, rpb, scale, st);
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_score_window launch");
+  }
+  return LKV_OK;
+}
+
 lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
                       int32_t* idx, int32_t* offsets, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;

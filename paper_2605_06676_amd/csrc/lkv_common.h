@@ -30,6 +30,19 @@ struct SeqTable {
   int32_t n;
 };
 
+// The same for the observation-window scorer, which reads keys and window queries and needs two
+// workspace arrays per sequence.
+struct WinTable {
+  const uint16_t* k[kMaxSeqPerLaunch];
+  const uint16_t* q[kMaxSeqPerLaunch];           // window queries [L, Hq, W, 128]
+  float* scores[kMaxSeqPerLaunch];               // [L, H, T]
+  float* votes[kMaxSeqPerLaunch];                // workspace [L, H, T]
+  float* partial[kMaxSeqPerLaunch];              // workspace [L H, blocks per head, padded rows, 2]
+  int32_t T[kMaxSeqPerLaunch];
+  int32_t first[kMaxSeqPerLaunch + 1];
+  int32_t n;
+};
+
 // Index of the sequence that owns work unit `unit`.  `unit` is wave-uniform,
 // so this runs on the scalar unit.
 __device__ __forceinline__ int seq_of_unit(const SeqTable& tab, int unit) {

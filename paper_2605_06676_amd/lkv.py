@@ -17,9 +17,11 @@ LIB_PATH = os.environ.get("LKV_LIBRARY", os.path.join(_HERE, "liblkv.so"))   # L
 LKV_OK = 0
 SCORER_LINEAR, SCORER_MLP = 0, 1
 ACT_SILU, ACT_GELU_ERF = 0, 1
+POOL_MAX, POOL_AVG = 0, 1
 _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "LKV_ERR_WORKSPACE", 4: "LKV_ERR_HIP"}
 
-EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score", "lkv_select",
+EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score",
+           "lkv_score_window_workspace_bytes", "lkv_score_window", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
            "lkv_append", "lkv_decode_attn_grown", "lkv_reevict", "lkv_masked_decode_workspace_bytes",
@@ -70,6 +72,11 @@ def load_library() -> C.CDLL:
     lib.lkv_version.restype = C.c_char_p
     lib.lkv_score.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(_Scorer), C.POINTER(C.c_void_p), C.c_void_p]
     lib.lkv_score.restype = C.c_int
+    lib.lkv_score_window_workspace_bytes.argtypes = [C.POINTER(_Cache)]
+    lib.lkv_score_window_workspace_bytes.restype = C.c_size_t
+    lib.lkv_score_window.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
+                                     C.c_int32, C.c_float, C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lkv_score_window.restype = C.c_int
     lib.lkv_select.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.POINTER(C.c_int32),
                                C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lkv_select.restype = C.c_int
@@ -206,6 +213,25 @@ def lkv_score(ctx: Context, cache: Cache, scorer: dict, scores: Sequence, stream
     sc = _scorer_struct(scorer)
     sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
     ctx._check(ctx.lib.lkv_score(ctx.h, C.byref(cache.c), C.byref(sc), sp, _stream_ptr(stream)))
+
+
+def lkv_score_window_workspace_bytes(cache: Cache) -> int:
+    return int(load_library().lkv_score_window_workspace_bytes(C.byref(cache.c)))
+
+
+def lkv_score_window(ctx: Context, cache: Cache, q_win: Sequence, window: int, pool_width: int, pool_kind: int,
+                     scale: float, scores: Sequence, workspace, stream=None) -> None:
+    """q_win: per-sequence bf16 [L, Hq, window, 128] GPU tensors (the queries of the last `window` positions);
+    scores: per-sequence fp32 [L, H, T_s] GPU tensors, written in place."""
+    import torch
+
+    assert all(q.dtype == torch.bfloat16 and q.is_contiguous() for q in q_win)
+    assert all(s.dtype == torch.float32 and s.is_contiguous() for s in scores)
+    qp = (C.c_void_p * cache.n_seq)(*[q.data_ptr() for q in q_win])
+    sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    ctx._check(ctx.lib.lkv_score_window(ctx.h, C.byref(cache.c), qp, int(window), int(pool_width), int(pool_kind),
+                                        float(scale), sp, _ptr(workspace), ws_bytes, _stream_ptr(stream)))
 
 
 def lkv_select(ctx: Context, cache: Cache, scores: Sequence, budgets, idx, offsets, stream=None) -> None:

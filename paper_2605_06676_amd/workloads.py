@@ -35,6 +35,11 @@ Recipe
   which is not available); soft mask m = x^4 with x ~ U(0,1) (mean 0.2, most weights small, as
   late in the annealing of Sec. 3.4), 10 % of the weights set to exactly 0 and 5 % to exactly 1,
   the first key of every head kept above 0.25 so that every causal prefix carries weight.
+* Observation-window queries (``draw_window_queries``): i.i.d. N(0,1) in bf16 like the decode
+  queries; on top, per (layer, query head) four "needle" positions of the prefix are drawn and each
+  window row, with probability 1/2, gets half of one needle's key row added before rounding (a logit
+  about 5.7 above the rest), so that the votes have the few-heavy-tokens shape attention over a
+  prompt has and the pooling has peaks to spread.
 * Sub-streams are keyed by (seed, config id, tensor tag, sequence, layer) so
   that any single layer can be regenerated on its own.
 """
@@ -48,7 +53,7 @@ import numpy as np
 
 D_HEAD = 128
 
-_TAGS = {"kv": 1, "q": 2, "scorer": 3, "budget": 4, "seqlen": 5, "chan": 6, "noise": 7, "headpred": 8, "train": 9}
+_TAGS = {"kv": 1, "q": 2, "scorer": 3, "budget": 4, "seqlen": 5, "chan": 6, "noise": 7, "headpred": 8, "train": 9, "win": 10}
 
 
 @dataclasses.dataclass(frozen=True)
@@ -253,6 +258,25 @@ def draw_q(w: Workload, seq: int = 0, seed: int = 0) -> np.ndarray:
     """Decode-step query vectors of one sequence: uint16(bf16) [L, Hq, d]."""
     rng = _rng(seed, w.cid, "q", seq)
     return f32_to_bf16_bits(rng.standard_normal(size=(w.L, w.Hq, w.d), dtype=np.float32))
+
+
+def draw_window_queries(w: Workload, K: np.ndarray, window: int, seq: int = 0, seed: int = 0) -> np.ndarray:
+    """Queries of the last `window` prompt positions of one sequence: uint16(bf16) [L, Hq, window, d].
+    K is the sequence's key cache as bf16 bit patterns [L, H, T, d] (the needles are rows of it)."""
+    L, H, T, d = K.shape
+    G = w.Hq // H
+    rng = _rng(seed, w.cid, "win", seq, window)
+    q = rng.standard_normal(size=(L, w.Hq, window, d), dtype=np.float32)
+    prefix = T - window
+    if prefix > 0:
+        needles = rng.integers(0, prefix, size=(L, w.Hq, 4))
+        which = rng.integers(0, 4, size=(L, w.Hq, window))
+        planted = rng.uniform(size=(L, w.Hq, window)) < 0.5
+        for l in range(L):
+            for hq in range(w.Hq):
+                rows = bf16_bits_to_f32(K[l, hq // G, needles[l, hq, which[l, hq]]])     # [window, d]
+                q[l, hq] += np.float32(0.5) * rows * planted[l, hq][:, None]
+    return f32_to_bf16_bits(q)
 
 
 # --------------------------------------------------------------------------

@@ -1,0 +1,172 @@
+"""GPU parity of the observation-window scorer (lkv_score_window) against oracle/window_score.py, and of the
+selection it feeds: the same seeded keys and window queries go to both sides; the scores are compared to a
+tolerance, the window tokens must be +inf exactly, and the hard top-k on the GPU's own scores must be the
+oracle's top-k on those scores, bit for bit.
+
+Tolerance.  Both sides multiply the same bf16 values; the GPU accumulates the 128-term dot products and the
+softmax sums in fp32 and uses the hardware exp2 / log2 (about 1 ulp).  A weight exp2(x - lse) with |x|, |lse| up
+to a few tens carries a relative error of a few 1e-6 from the rounding of its exponent, the normaliser the
+same, so a vote is good to about 1e-5 relative; the test asks for 1e-3 of max(|score|, rms of the head's
+scores), a tenth of the 1e-2 the LKV-T scores are held to.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lkv_oracle as O
+from oracle import window_score as WS
+from paper_2605_06676_amd import lkv
+from paper_2605_06676_amd import workloads as W
+
+import gpu_util as G
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = lkv.Context(0)
+    yield c
+    c.close()
+
+
+def run_gpu(ctx, Kbits, Qbits, Hq, window, pool, kind, scale=G.SCALE):
+    """Kbits: list of uint16 [L, H, T, d]; Qbits: list of uint16 [L, Hq, window, d].  Returns the scores as numpy."""
+    k = [G.bits_to_bf16_gpu(x) for x in Kbits]
+    cache = lkv.Cache(k, k, Hq)                                   # the value cache is not read
+    q = [G.bits_to_bf16_gpu(x) for x in Qbits]
+    scores = [torch.full(x.shape[:3], float("nan"), dtype=torch.float32, device="cuda") for x in Kbits]
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    lkv.lkv_score_window(ctx, cache, q, window, pool, kind, scale, scores, ws)
+    torch.cuda.synchronize()
+    return cache, scores
+
+
+def check_against_oracle(s_gpu, Kbits, Qbits, window, pool, kind, scale=G.SCALE, what=""):
+    L, H, T, _ = Kbits.shape
+    worst = 0.0
+    for l in range(L):
+        ref = WS.window_scores(O.bf16_bits_to_f64(Qbits[l]), O.bf16_bits_to_f64(Kbits[l]), scale, pool,
+                               "max" if kind == lkv.POOL_MAX else "avg")
+        got = s_gpu[l]
+        assert np.isposinf(got[:, T - window:]).all(), f"{what}: window tokens must score +inf"
+        if T > window:
+            r, g = ref[:, :T - window], got[:, :T - window].astype(np.float64)
+            assert np.isfinite(g).all() and (g >= 0).all(), what
+            rms = np.sqrt((r ** 2).mean(axis=-1, keepdims=True))
+            ratio = np.abs(g - r) / (RTOL * np.maximum(np.abs(r), rms))
+            assert ratio.max() <= 1.0, f"{what}: layer {l}: worst error {ratio.max():.3g} of the tolerance"
+            worst = max(worst, float(ratio.max()))
+    return worst
+
+
+SHAPES = [
+    # L, H, Hq, T, window, pool, kind
+    (2, 2, 8, 700, 32, 7, lkv.POOL_MAX),      # 128 query rows per KV head: the full fragment set, several blocks
+    (1, 2, 6, 333, 5, 5, lkv.POOL_AVG),       # 15 rows: one M tile with a padding row, second wave all padding
+    (1, 1, 8, 1025, 16, 1, lkv.POOL_MAX),     # group of 8, no pooling
+    (2, 3, 6, 257, 40, 13, lkv.POOL_AVG),     # 80 rows: three M tiles per wave, the last half padding
+    (1, 2, 2, 130, 64, 3, lkv.POOL_MAX),      # one query head per KV head, window longer than 4 tiles
+    (1, 1, 4, 40, 7, 63, lkv.POOL_AVG),       # pooling wider than the prefix
+    (1, 2, 4, 33, 32, 3, lkv.POOL_MAX),       # a prefix of one token
+    (1, 1, 4, 32, 32, 3, lkv.POOL_MAX),       # the window is the whole prompt
+    (1, 1, 1, 1, 1, 1, lkv.POOL_MAX),         # one token
+    (1, 1, 16, 100, 8, 5, lkv.POOL_MAX),      # group of 16
+]
+
+
+@pytest.mark.parametrize("L,H,Hq,T,window,pool,kind", SHAPES)
+def test_scores_match_the_oracle(ctx, L, H, Hq, T, window, pool, kind):
+    w = W.scaled(W.CONFIGS[0], L=L, H=H, Hq=Hq, T=T, b_min=1)
+    K, _ = W.draw_kv(w, T, 0, 3)
+    Q = W.draw_window_queries(w, K, window, 0, 3)
+    _, scores = run_gpu(ctx, [K], [Q], Hq, window, pool, kind)
+    check_against_oracle(scores[0].cpu().numpy(), K, Q, window, pool, kind, what=f"T={T} W={window}")
+
+
+def test_several_sequences_and_selection(ctx):
+    # three sequences of different lengths in one call; then the hard top-k under per-head budgets
+    w = W.scaled(W.CONFIGS[0], L=2, H=2, Hq=8, T=900, b_min=1)
+    lens = [900, 129, 2051]
+    window = 32
+    Ks = [W.draw_kv(w, T, s, 4)[0] for s, T in enumerate(lens)]
+    Qs = [W.draw_window_queries(w, K, window, s, 4) for s, K in enumerate(Ks)]
+    cache, scores = run_gpu(ctx, Ks, Qs, w.Hq, window, 7, lkv.POOL_MAX)
+    for s, T in enumerate(lens):
+        check_against_oracle(scores[s].cpu().numpy(), Ks[s], Qs[s], window, 7, lkv.POOL_MAX, what=f"sequence {s}")
+    rng = np.random.default_rng(5)
+    budgets = np.concatenate([rng.integers(window, T // 2, size=w.L * w.H) for T in lens]).astype(np.int32)
+    idx = torch.empty(int(budgets.sum()), dtype=torch.int32, device="cuda")
+    offsets = torch.empty(budgets.size + 1, dtype=torch.int32, device="cuda")
+    lkv.lkv_select(ctx, cache, scores, budgets, idx, offsets)
+    torch.cuda.synchronize()
+    idx_h, off_h = idx.cpu().numpy(), offsets.cpu().numpy()
+    seg = 0
+    for s, T in enumerate(lens):
+        u = scores[s].cpu().numpy().reshape(-1, T)
+        for lh in range(w.L * w.H):
+            kept = idx_h[off_h[seg]:off_h[seg + 1]]
+            assert np.array_equal(kept, O.select(u[lh], int(budgets[seg])))
+            assert np.array_equal(kept[-window:], np.arange(T - window, T))       # the window survives
+            seg += 1
+
+
+def test_runaway_logits_move_the_references(ctx):
+    # logits spread over hundreds of binary orders of magnitude, largest ones late in the prefix: the first pass
+    # has to move its references many times, and the weights still have to come out right
+    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=8, T=1500, b_min=1)
+    T, window = 1500, 32
+    K, _ = W.draw_kv(w, T, 0, 6)
+    Q = W.draw_window_queries(w, K, window, 0, 6)
+    ramp = np.linspace(0.05, 3.0, T, dtype=np.float32)[None, None, :, None]
+    K = W.f32_to_bf16_bits(W.bf16_bits_to_f32(K) * ramp)
+    for scale in (G.SCALE * 40.0, G.SCALE * 4.0):
+        _, scores = run_gpu(ctx, [K], [Q], w.Hq, window, 1, lkv.POOL_MAX, scale)
+        check_against_oracle(scores[0].cpu().numpy(), K, Q, window, 1, lkv.POOL_MAX, scale, what=f"scale {scale:.3g}")
+
+
+def test_reproducible_and_workspace_is_scratch(ctx):
+    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=8, T=777, b_min=1)
+    K, _ = W.draw_kv(w, 777, 0, 7)
+    Q = W.draw_window_queries(w, K, 32, 0, 7)
+    k = G.bits_to_bf16_gpu(K)
+    cache = lkv.Cache([k], [k], w.Hq)
+    q = G.bits_to_bf16_gpu(Q)
+    outs = []
+    for fill in (0, 255):
+        ws = torch.full((lkv.lkv_score_window_workspace_bytes(cache),), fill, dtype=torch.uint8, device="cuda")
+        s = torch.empty((1, 2, 777), dtype=torch.float32, device="cuda")
+        lkv.lkv_score_window(ctx, cache, [q], 32, 7, lkv.POOL_AVG, G.SCALE, [s], ws)
+        torch.cuda.synchronize()
+        outs.append(s.cpu().numpy())
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_argument_errors(ctx):
+    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=8, T=200, b_min=1)
+    K, _ = W.draw_kv(w, 200, 0, 8)
+    k = G.bits_to_bf16_gpu(K)
+    cache = lkv.Cache([k], [k], w.Hq)
+    q = torch.zeros((1, 8, 64, 128), dtype=torch.bfloat16, device="cuda")
+    s = torch.empty((1, 2, 200), dtype=torch.float32, device="cuda")
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+
+    def status(**kw):
+        a = dict(window=32, pool=7, kind=lkv.POOL_MAX, scale=G.SCALE, ws=ws)
+        a.update(kw)
+        with pytest.raises(lkv.LkvError) as e:
+            lkv.lkv_score_window(ctx, cache, [q], a["window"], a["pool"], a["kind"], a["scale"], [s], a["ws"])
+        return e.value.status
+
+    assert status(window=0) == 1
+    assert status(window=201) == 1
+    assert status(window=33) == 2                      # 4 x 33 query rows per KV head
+    assert status(pool=4) == 1 and status(pool=65) == 1 and status(pool=0) == 1
+    assert status(kind=2) == 1
+    assert status(scale=0.0) == 1 and status(scale=float("inf")) == 1
+    assert status(ws=None) == 3 and status(ws=ws[:ws.numel() - 256]) == 3
+    assert status(ws=ws[1:]) == 3                      # misaligned
+    lkv.lkv_score_window(ctx, cache, [q], 32, 7, lkv.POOL_MAX, G.SCALE, [s], ws)    # and the good call goes through
+    torch.cuda.synchronize()
