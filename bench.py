@@ -49,6 +49,8 @@ def parse():
     ap.add_argument("--train-attn", type=int, nargs="?", const=16384, default=0, metavar="T",
                     help="also time the training-time attention with the multiplicative mask (forward and backward) "
                          "over T tokens (default 16384) for the workload's head counts; adds the key `training_attention`")
+    ap.add_argument("--window-score", type=int, nargs="?", const=32, default=0, metavar="W",
+                    help="also time the observation-window scorer (window W, default 32) and the eviction it feeds")
     ap.add_argument("--layerwise", action="store_true",
                     help="also measure layer-by-layer eviction during prefill; adds the key `layerwise`")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -286,6 +288,9 @@ def main():
         result["growth"] = growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev)
     if args.train_attn:
         result["training_attention"] = training_attention(ctx, lkv, w, args.train_attn, dev)
+    if args.window_score:
+        result["window_scorer"] = window_scorer(ctx, lkv, w, cache, scores, budgets_flat, idx, offsets, total, kp, vp,
+                                                Ts, args.window_score, scale, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
     print(json.dumps(result))
@@ -339,6 +344,60 @@ def training_attention(ctx, lkv, w, T, dev, reps=10):
                                            "unit": "TFLOP/s", "frac": tf / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
                      "executed_TFLOPs": executed * product / (t * 1e9)}
     return out
+
+
+def window_scorer(ctx, lkv, w, cache, scores, budgets_flat, idx, offsets, total, kp, vp, Ts, window, scale, dev, reps=10):
+    """The observation-window scorer (the attention-based selection policy of the ablation, Sec. 4.4) on the
+    workload's cache with the workload's budgets: the scoring call alone, and scoring + top-k + compaction.
+    Algorithmic bytes: every key row once (the kernels read them twice, once per softmax pass), the window
+    queries, the scores; the eviction adds the index and packed-cache traffic of the main path."""
+    import torch
+
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1)
+    q_win = [torch.randn((w.L, w.Hq, window, w.d), device=dev, generator=gen).to(torch.bfloat16) for _ in Ts]
+    ws = torch.empty((lkv.lkv_score_window_workspace_bytes(cache),), dtype=torch.uint8, device=dev)
+    budgets = np.maximum(budgets_flat, window).astype(np.int32)      # the rule keeps the window on top of its picks
+    budgets = np.minimum(budgets, np.repeat(np.asarray(Ts, dtype=np.int32), w.L * w.H))
+    extra = int(budgets.sum()) - total
+    if extra > 0:
+        kp = torch.empty((total + extra, w.d), dtype=torch.bfloat16, device=dev)
+        vp = torch.empty_like(kp)
+        idx = torch.empty((total + extra,), dtype=torch.int32, device=dev)
+
+    def score():
+        lkv.lkv_score_window(ctx, cache, q_win, window, 7, lkv.POOL_MAX, scale, scores, ws)
+
+    def evict():
+        score()
+        lkv.lkv_select(ctx, cache, scores, budgets, idx, offsets)
+        lkv.lkv_compact(ctx, cache, idx, offsets, int(budgets.sum()), kp, vp)
+
+    def timed(fn):
+        for _ in range(2):
+            fn()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        torch.cuda.synchronize()
+        ev[0].record()
+        for _ in range(reps):
+            fn()
+        ev[1].record()
+        torch.cuda.synchronize()
+        return ev[0].elapsed_time(ev[1]) / reps
+
+    t_score, t_evict = timed(score), timed(evict)
+    N = sum(w.L * w.H * T for T in Ts)
+    kept = int(budgets.sum())
+    score_bytes = N * (2 * w.d + 4) + len(Ts) * w.L * w.Hq * window * w.d * 2
+    evict_bytes = score_bytes + N * 4 + kept * 4 + kept * 2 * w.d * 2 * 2
+    return {"window": window, "pool": "max, width 7", "dtype": "bf16", "accumulate": "f32",
+            "score_ms": t_score, "evict_ms": t_evict,
+            "roofline": {"bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS, "traffic": None},
+            "keys_read_twice_GBps": (score_bytes + N * 2 * w.d) / (t_score * 1e6),
+            "evict_GBps": evict_bytes / (t_evict * 1e6),
+            "note": "the two softmax passes are bound by vector and matrix issue (one exponential per logit and "
+                    "pass), not by HBM"}
 
 
 def growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total, Ts, q, scale, dev, slack=128, n_new=64):

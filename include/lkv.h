@@ -6,8 +6,9 @@
  * path one layer at a time during prefill, the growth of the packed cache
  * during decoding with re-eviction, attention with a multiplicative mask over
  * the uncompacted cache, the training-time attention kernel with that mask
- * (forward and backward), and the LKV-H budget allocation with the forward
- * Soft-TopK operator.
+ * (forward and backward), the LKV-H budget allocation with the forward
+ * Soft-TopK operator, and the observation-window scorer that the paper's
+ * ablation runs under the same budgets (lkv_score_window).
  *
  * General conventions
  * -------------------
@@ -134,8 +135,8 @@ lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *sco
  * scale     : positive, finite (1 / sqrt(d) in Eq. 1)
  * scores    : HOST [n_seq] of DEVICE pointers, each fp32 [L, H, T_s]
  * workspace : DEVICE, 256-byte aligned, at least lkv_score_window_workspace_bytes(cache)
- *             bytes (votes and per-block normaliser pairs, 12 bytes per cached
- *             key row and head at most); contents are scratch. */
+ *             bytes (votes and per-block normaliser pairs, about 16 bytes per
+ *             cached key row and head); contents are scratch. */
 size_t lkv_score_window_workspace_bytes(const lkv_cache *cache);
 lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *const *q_win, int32_t window,
                             int32_t pool_width, int32_t pool_kind, float scale, float *const *scores,

@@ -36,7 +36,7 @@ struct WinTable {
   const uint16_t* k[kMaxSeqPerLaunch];
   const uint16_t* q[kMaxSeqPerLaunch];           // window queries [L, Hq, W, 128]
   float* scores[kMaxSeqPerLaunch];               // [L, H, T]
-  float* votes[kMaxSeqPerLaunch];                // workspace [L, H, T]
+  float* votes[kMaxSeqPerLaunch];                // workspace [2, L H, T]
   float* partial[kMaxSeqPerLaunch];              // workspace [L H, blocks per head, padded rows, 2]
   int32_t T[kMaxSeqPerLaunch];
   int32_t first[kMaxSeqPerLaunch + 1];

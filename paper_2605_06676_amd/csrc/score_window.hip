@@ -12,7 +12,8 @@
 // so the keys are read twice:
 //   pass 1  per window row, the log-sum-exp of its logits over one block's keys (causal inside
 //           the window), written as a (reference, sum) pair per block;
-//   pass 2  merges the pairs of all blocks of the head into the row's log-normaliser, recomputes
+//   merge   the pairs of all blocks of a head into each row's log-normaliser (a small kernel);
+//   pass 2  recomputes
 //           the logits and adds exp(logit - normaliser) over the rows: the token's vote;
 //   pool    smooths the votes and writes the scores.
 // Keeping the logits instead would cost as many bytes as reading the keys again (G W = 128
@@ -33,7 +34,15 @@ constexpr int kWinThreads = 128;
 constexpr int kWinTokTile = 16;                  // keys per MFMA N tile
 constexpr int kWinRowStride = 256 + 32;          // bytes per staged key row in LDS
 constexpr int kWinTileLds = kWinTokTile * kWinRowStride;
-constexpr int kWinMaxRowsPerBlock = 1024;
+#ifndef LKV_WIN_NT
+#define LKV_WIN_NT 2
+#endif
+constexpr int kWinTilesPerStep = LKV_WIN_NT;     // tiles staged, multiplied and finished between two barriers
+constexpr int kWinStepLds = kWinTilesPerStep * kWinTileLds;
+#ifndef LKV_WIN_ROWS
+#define LKV_WIN_ROWS 1024
+#endif
+constexpr int kWinMaxRowsPerBlock = LKV_WIN_ROWS;
 constexpr float kWinRebase = 64.f;               // log2 distance at which pass 1 moves a reference
 constexpr float kWinNoRef = -1e30f;              // reference of a row that has seen no key yet
 
@@ -51,11 +60,11 @@ __device__ __forceinline__ float row16_allreduce_max(float x) {
   return x;
 }
 
-// kPass 1: partial log-sum-exp pairs.  kPass 2: votes.  MTW: 16-row M tiles per wave; the rows past
+// kPass 1: partial log-sum-exp pairs.  kPass 2: votes (the merged normalisers are read from the workspace).  MTW: 16-row M tiles per wave; the rows past
 // n_rows = G W are padding (zero queries, never counted).
 template <int MTW, int kPass>
 __global__ void __launch_bounds__(kWinThreads, 2)
-score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, float log2_scale, float inv_group) {
+score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_per_block, float log2_scale) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int RP = 32 * MTW;                      // padded rows of the block
 
@@ -77,10 +86,9 @@ score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, fl
   const int half = threadIdx.x >> 6;
   const int r = lane >> 4;
   const int c = lane & 15;
-  // LDS: two staged tiles, then (pass 2) the block's votes of either wave, then the rows' log-normalisers
-  unsigned char* x_lds = smem;
-  float* vote_lds = reinterpret_cast<float*>(smem + 2 * kWinTileLds);   // [2][rows_per_block]
-  float* lse_lds = vote_lds + 2 * rows_per_block;                        // [RP]
+  unsigned char* x_lds = smem;   // the staged keys of two steps
+  // pass 2: this wave's share of the votes (its rows only) goes to its own half of the workspace
+  float* votes = tab.votes[seq] + ((size_t)half * heads + lh) * T;
 
   // A fragments: window row 16 (half MTW + mw) + c, features 32 ks + 8 r .. +7
   bf16x8_t qfrag[MTW][4];
@@ -111,26 +119,11 @@ score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, fl
 
   const size_t part_row0 = ((size_t)lh * chunks) * RP;
   if (kPass == 2) {
-    // log-normaliser of every row: merge the pairs that pass 1 left for each block of this head
-    const float* part = tab.partial[seq] + part_row0 * 2;
-    for (int row = threadIdx.x; row < RP; row += kWinThreads) {
-      float lse = INFINITY;                          // padding rows: weight exp2(-inf) = 0
-      if (row < n_rows) {
-        float m = kWinNoRef;
-        for (int ch = 0; ch < chunks; ++ch) m = fmaxf(m, part[((size_t)ch * RP + row) * 2]);
-        float l = 0.f;
-        for (int ch = 0; ch < chunks; ++ch) {
-          const float* p = part + ((size_t)ch * RP + row) * 2;
-          l += p[1] * __builtin_amdgcn_exp2f(p[0] - m);
-        }
-        lse = m + __log2f(l);
-      }
-      lse_lds[row] = lse;
-    }
-    __syncthreads();
+    // log-normaliser of every row, merged from the pairs of pass 1 by the kernel in between
+    const float* lse = tab.partial[seq] + (size_t)heads * chunks * RP * 2 + (size_t)lh * RP;
 #pragma unroll
     for (int mw = 0; mw < MTW; ++mw) {
-      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(lse_lds + 16 * (half * MTW + mw) + 4 * r);
+      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(lse + 16 * (half * MTW + mw) + 4 * r);
 #pragma unroll
       for (int e = 0; e < 4; ++e) ref[mw][e] = v[e];
     }
@@ -138,25 +131,25 @@ score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, fl
 
   const uint4* Kh = reinterpret_cast<const uint4*>(tab.k[seq]) + (size_t)lh * (size_t)T * kChunksPerRow;
 
-  // Staging: thread (half, r, c) brings piece c of rows 8 half + r and 8 half + 4 + r of each tile.
-  uint4 xa[2], xb[2];
-  auto load_tile = [&](uint4 (&xx)[2], int i) {
+  // Staging: thread (half, r, c) brings piece c of rows 16 nt + 8 half + r and 16 nt + 8 half + 4 + r of each step.
+  constexpr int NT = kWinTilesPerStep;
+  uint4 xa[2 * NT], xb[2 * NT];
+  auto load_step = [&](uint4 (&xx)[2 * NT], int i) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      int row = block_row0 + 16 * i + 8 * half + 4 * j + r;
+    for (int j = 0; j < 2 * NT; ++j) {
+      int row = block_row0 + 16 * NT * i + 16 * (j >> 1) + 8 * half + 4 * (j & 1) + r;
       row = row < T ? row : T - 1;   // ragged tail: re-read the last row, masked below
       xx[j] = load_stream16(Kh + (size_t)row * kChunksPerRow + c);
     }
   };
-  auto stage_tile = [&](const uint4 (&xx)[2], int buf) {
+  auto stage_step = [&](const uint4 (&xx)[2 * NT], int buf) {
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
-      *reinterpret_cast<uint4*>(x_lds + buf * kWinTileLds + (8 * half + 4 * j + r) * kWinRowStride + c * 16) = xx[j];
+    for (int j = 0; j < 2 * NT; ++j)
+      *reinterpret_cast<uint4*>(x_lds + buf * kWinStepLds + (16 * (j >> 1) + 8 * half + 4 * (j & 1) + r) * kWinRowStride + c * 16) = xx[j];
   };
-  auto products = [&](f32x4_t (&acc)[MTW], int buf) {
+  auto products = [&](f32x4_t (&acc)[MTW], const unsigned char* xt) {
 #pragma unroll
     for (int mw = 0; mw < MTW; ++mw) acc[mw] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const unsigned char* xt = x_lds + buf * kWinTileLds;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const uint4 x = *reinterpret_cast<const uint4*>(xt + c * kWinRowStride + ks * 64 + r * 16);
@@ -166,8 +159,8 @@ score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, fl
         acc[mw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qfrag[mw][ks], xv, acc[mw], 0, 0, 0);
     }
   };
-  auto finish = [&](const f32x4_t (&acc)[MTW], int i) {
-    const int row0 = block_row0 + 16 * i;
+  auto finish = [&](const f32x4_t (&acc)[MTW], int tile) {   // tile: 16-key tile of the block
+    const int row0 = block_row0 + 16 * tile;
     if (kPass == 1) {
       float x[MTW][4];
       float top = -INFINITY;
@@ -210,31 +203,35 @@ score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, fl
         for (int e = 0; e < 4; ++e) part += __builtin_amdgcn_exp2f(fmaf(acc[mw][e], log2_scale, -ref[mw][e]));
       part += __shfl_xor(part, 16, 64);
       part += __shfl_xor(part, 32, 64);
-      if (r == 0) vote_lds[half * rows_per_block + 16 * i + c] = part;   // 16 i + c < rows_per_block
+      if (r == 0 && row0 + c < prefix) votes[row0 + c] = part;
     }
   };
 
-  // Barrier i makes tile i visible and means both waves have finished reading tile i - 1.
-  // One step: products and arithmetic of tile i, staging of tile i + 1 (fetching tile i + 3 behind it).
-  f32x4_t acc[MTW];
-  auto step = [&](uint4 (&x_next)[2], int i) {
-    products(acc, i & 1);
-    if (i + 1 < n_tiles) {
-      stage_tile(x_next, (i + 1) & 1);
-      if (i + 3 < n_tiles) load_tile(x_next, i + 3);
+  // Barrier i makes the keys of step i visible and means both waves have finished reading those of step i - 1.
+  // One step: products and arithmetic of its NT tiles, staging of step i + 1 (fetching step i + 3 behind it).
+  const int n_steps = (n_tiles + NT - 1) / NT;
+  f32x4_t acc[NT][MTW];
+  auto step = [&](uint4 (&x_next)[2 * NT], int i) {
+    const unsigned char* xt = x_lds + (i & 1) * kWinStepLds;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) products(acc[nt], xt + nt * kWinTileLds);
+    if (i + 1 < n_steps) {
+      stage_step(x_next, (i + 1) & 1);
+      if (i + 3 < n_steps) load_step(x_next, i + 3);
     }
-    finish(acc, i);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) finish(acc[nt], NT * i + nt);
     __syncthreads();
   };
-  load_tile(xa, 0);
-  if (1 < n_tiles) load_tile(xb, 1);
-  stage_tile(xa, 0);
-  if (2 < n_tiles) load_tile(xa, 2);
+  load_step(xa, 0);
+  if (1 < n_steps) load_step(xb, 1);
+  stage_step(xa, 0);
+  if (2 < n_steps) load_step(xa, 2);
   __syncthreads();
 #pragma unroll 1
-  for (int i = 0; i < n_tiles; i += 2) {
-    step(xb, i);                                   // stages the odd tile i + 1
-    if (i + 1 < n_tiles) step(xa, i + 1);          // uniform condition around the barrier
+  for (int i = 0; i < n_steps; i += 2) {
+    step(xb, i);                                   // stages the odd step i + 1
+    if (i + 1 < n_steps) step(xa, i + 1);          // uniform condition around the barrier
   }
 
   if (kPass == 1) {
@@ -253,18 +250,41 @@ score_window_kernel(WinTable tab, int window, int n_rows, int rows_per_block, fl
           part[row * 2 + 1] = l;
         }
       }
-  } else {
-    // the last barrier of the loop ordered the votes; mean over the group's query heads
-    float* votes = tab.votes[seq] + (size_t)lh * T + block_row0;
-    for (int t = threadIdx.x; t < block_rows; t += kWinThreads)
-      votes[t] = (vote_lds[t] + vote_lds[rows_per_block + t]) * inv_group;
   }
+}
+
+// Between the passes: the log-normaliser (log2 units) of every window row of every head, from the pairs
+// the blocks of pass 1 left; +inf for the padding rows, whose weights then vanish.  One block per head.
+__global__ void __launch_bounds__(128)
+score_window_merge_kernel(WinTable tab, int heads, int n_rows, int rows_per_block, int padded_rows) {
+  const int seq = blockIdx.x / heads;
+  const int lh = blockIdx.x - seq * heads;
+  const int chunks = (tab.T[seq] + rows_per_block - 1) / rows_per_block;
+  const float* part = tab.partial[seq] + (size_t)lh * chunks * padded_rows * 2;
+  float* lse = tab.partial[seq] + (size_t)heads * chunks * padded_rows * 2 + (size_t)lh * padded_rows;
+  const int row = threadIdx.x;
+  if (row >= padded_rows) return;
+  float out = INFINITY;
+  if (row < n_rows) {
+    const float2* pairs = reinterpret_cast<const float2*>(part) + row;
+    float m = kWinNoRef;
+#pragma unroll 8
+    for (int ch = 0; ch < chunks; ++ch) m = fmaxf(m, pairs[(size_t)ch * padded_rows].x);
+    float l = 0.f;
+#pragma unroll 8
+    for (int ch = 0; ch < chunks; ++ch) {
+      const float2 p = pairs[(size_t)ch * padded_rows];
+      l += p.y * __builtin_amdgcn_exp2f(p.x - m);
+    }
+    out = m + __log2f(l);
+  }
+  lse[row] = out;
 }
 
 // Scores from votes: centred pooling of width 2 c + 1 over the prefix, +inf on the window tokens.
 // kind 0: maximum over the part of the span inside the prefix; kind 1: sum over it divided by the width.
 __global__ void __launch_bounds__(256)
-score_window_pool_kernel(WinTable tab, int window, int reach, int kind) {
+score_window_pool_kernel(WinTable tab, int heads, int window, int reach, int kind, float inv_group) {
   const int seq = win_seq_of_unit(tab, blockIdx.x);
   const int local = blockIdx.x - tab.first[seq];
   const int T = tab.T[seq];
@@ -272,20 +292,29 @@ score_window_pool_kernel(WinTable tab, int window, int reach, int kind) {
   const int lh = local / tiles;
   const int tile = local - lh * tiles;
   const int prefix = T - window;
-  const float* votes = tab.votes[seq] + (size_t)lh * T;
+  const float* va = tab.votes[seq] + (size_t)lh * T;               // the two waves' shares of the votes
+  const float* vb = tab.votes[seq] + ((size_t)heads + lh) * T;
   float* out = tab.scores[seq] + (size_t)lh * T;
   const float inv_width = 1.f / (float)(2 * reach + 1);
-  for (int j = tile * 1024 + threadIdx.x; j < min(T, tile * 1024 + 1024); j += 256) {
+  // the summed votes of the tile and of `reach` neighbours on either side, once, through LDS
+  __shared__ float v_lds[1024 + 64];
+  const int base = tile * 1024 - reach;
+  for (int t = threadIdx.x; t < 1024 + 2 * reach; t += 256) {
+    const int j = base + t;
+    v_lds[t] = j >= 0 && j < prefix ? va[j] + vb[j] : 0.f;     // votes are non-negative: zeros change neither rule
+  }
+  __syncthreads();
+  for (int t = threadIdx.x; t < min(1024, T - tile * 1024); t += 256) {
+    const int j = tile * 1024 + t;
     float s = INFINITY;
     if (j < prefix) {
-      const int lo = max(0, j - reach), hi = min(prefix - 1, j + reach);
+      s = 0.f;
       if (kind == 0) {
-        s = votes[lo];
-        for (int t = lo + 1; t <= hi; ++t) s = fmaxf(s, votes[t]);
+        for (int u = 0; u <= 2 * reach; ++u) s = fmaxf(s, v_lds[t + u]);
+        s *= inv_group;
       } else {
-        s = 0.f;
-        for (int t = lo; t <= hi; ++t) s += votes[t];
-        s *= inv_width;
+        for (int u = 0; u <= 2 * reach; ++u) s += v_lds[t + u];
+        s *= inv_width * inv_group;
       }
     }
     out[j] = s;
@@ -302,23 +331,25 @@ int score_window_rows_per_block(int64_t tokens_times_heads) {
   return rows;
 }
 
-// Workspace of one sequence: votes [heads, T] then pairs [heads, ceil(T / 128), 128, 2] (the largest the
-// pairs can get: the smallest block and the most padded rows), each 256-byte aligned.
-size_t score_window_votes_bytes(int64_t heads, int T) { return ((size_t)heads * T * sizeof(float) + 255) & ~(size_t)255; }
+// Workspace of one sequence: votes [2, heads, T] (one share per wave of a block), then pairs [heads, ceil(T / 128), 128, 2] (the largest the
+// pairs can get: the smallest block and the most padded rows) followed by the merged normalisers
+// [heads, 128]; both parts 256-byte aligned.
+size_t score_window_votes_bytes(int64_t heads, int T) { return ((size_t)2 * heads * T * sizeof(float) + 255) & ~(size_t)255; }
 size_t score_window_pairs_bytes(int64_t heads, int T) {
-  return ((size_t)heads * ((T + 127) / 128) * 128 * 2 * sizeof(float) + 255) & ~(size_t)255;
+  return ((size_t)heads * (((T + 127) / 128) * 2 + 1) * 128 * sizeof(float) + 255) & ~(size_t)255;
 }
 
 template <int MTW>
-static void launch_passes(const WinTable& tab, int window, int n_rows, int rows_per_block, float log2_scale,
-                          float inv_group, hipStream_t stream) {
+static void launch_passes(const WinTable& tab, int heads, int window, int n_rows, int rows_per_block, float log2_scale,
+                          hipStream_t stream) {
   const int blocks = tab.first[tab.n];
-  const size_t lds1 = 2 * kWinTileLds;
-  const size_t lds2 = 2 * kWinTileLds + (2 * (size_t)rows_per_block + 32 * MTW) * sizeof(float);
-  hipLaunchKernelGGL((score_window_kernel<MTW, 1>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, window,
-                     n_rows, rows_per_block, log2_scale, inv_group);
-  hipLaunchKernelGGL((score_window_kernel<MTW, 2>), dim3(blocks), dim3(kWinThreads), lds2, stream, tab, window,
-                     n_rows, rows_per_block, log2_scale, inv_group);
+  const size_t lds1 = 2 * kWinStepLds;   // both passes
+  hipLaunchKernelGGL((score_window_kernel<MTW, 1>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
+                     n_rows, rows_per_block, log2_scale);
+  hipLaunchKernelGGL(score_window_merge_kernel, dim3(tab.n * heads), dim3(128), 0, stream, tab, heads, n_rows,
+                     rows_per_block, 32 * MTW);
+  hipLaunchKernelGGL((score_window_kernel<MTW, 2>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
+                     n_rows, rows_per_block, log2_scale);
 }
 
 // `tab.first` counts the blocks of the two passes; the pooling kernel derives its own grid.
@@ -329,10 +360,10 @@ void launch_score_window(const WinTable& tab, int heads, int window, int group, 
   const float log2_scale = scale * 1.44269504088896340736f;
   const float inv_group = 1.f / (float)group;
   switch ((n_rows + 31) / 32) {
-    case 1: launch_passes<1>(tab, window, n_rows, rows_per_block, log2_scale, inv_group, stream); break;
-    case 2: launch_passes<2>(tab, window, n_rows, rows_per_block, log2_scale, inv_group, stream); break;
-    case 3: launch_passes<3>(tab, window, n_rows, rows_per_block, log2_scale, inv_group, stream); break;
-    case 4: launch_passes<4>(tab, window, n_rows, rows_per_block, log2_scale, inv_group, stream); break;
+    case 1: launch_passes<1>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
+    case 2: launch_passes<2>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
+    case 3: launch_passes<3>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
+    case 4: launch_passes<4>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
     default: return;
   }
   WinTable pool = tab;
@@ -342,8 +373,8 @@ void launch_score_window(const WinTable& tab, int heads, int window, int group, 
     blocks += (int64_t)heads * ((tab.T[i] + 1023) >> 10);
   }
   pool.first[tab.n] = (int32_t)blocks;
-  hipLaunchKernelGGL(score_window_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, pool, window,
-                     (pool_width - 1) / 2, pool_kind);
+  hipLaunchKernelGGL(score_window_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, pool, heads, window,
+                     (pool_width - 1) / 2, pool_kind, inv_group);
 }
 
 }  // namespace lkv

@@ -170,3 +170,40 @@ def test_argument_errors(ctx):
     assert status(ws=ws[1:]) == 3                      # misaligned
     lkv.lkv_score_window(ctx, cache, [q], 32, 7, lkv.POOL_MAX, G.SCALE, [s], ws)    # and the good call goes through
     torch.cuda.synchronize()
+
+
+def test_full_size_sampled_heads(ctx):
+    # the 32k workload (32 layers x 8 KV heads, 32 query heads, T = 32768), window 32, in the launch configuration
+    # the benchmark times: three heads against the oracle, every head against what holds at any size
+    w = W.CONFIGS[1]
+    T, window = 32768, 32
+    k, _ = W.device_kv(w, T, 0, "cuda")
+    cache = lkv.Cache([k], [k], w.Hq)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(12)
+    q = torch.randn((w.L, w.Hq, window, w.d), device="cuda", generator=gen)
+    # plant needles: some window rows lean towards a prefix key of their KV head
+    grp = w.Hq // w.H
+    for l, hq, row, j in ((0, 0, 3, 17), (5, 9, 31, 30000), (31, 31, 0, 32735), (17, 14, 8, 12345)):
+        q[l, hq, row] += 0.5 * k[l, hq // grp, j].float()
+    q = q.to(torch.bfloat16).contiguous()
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    plain = torch.empty((w.L, w.H, T), dtype=torch.float32, device="cuda")
+    pooled = torch.empty_like(plain)
+    lkv.lkv_score_window(ctx, cache, [q], window, 1, lkv.POOL_MAX, G.SCALE, [plain], ws)
+    lkv.lkv_score_window(ctx, cache, [q], window, 7, lkv.POOL_MAX, G.SCALE, [pooled], ws)
+    torch.cuda.synchronize()
+    # any size: +inf exactly on the window; unpooled votes are non-negative and a head cannot hand out more than the
+    # W units of attention mass its window rows have; max pooling never lowers a score and is the max of 7 neighbours
+    assert torch.isposinf(plain[:, :, T - window:]).all() and torch.isposinf(pooled[:, :, T - window:]).all()
+    v = plain[:, :, :T - window]
+    assert torch.isfinite(v).all() and (v >= 0).all()
+    mass = v.double().sum(-1)
+    assert (mass <= window * (1 + 1e-4)).all() and (mass > 0).all()
+    ref_pool = torch.nn.functional.max_pool1d(v.reshape(1, -1, T - window), 7, stride=1, padding=3).reshape(v.shape)
+    assert torch.equal(pooled[:, :, :T - window], ref_pool)
+    for l, h in ((0, 0), (5, 2), (31, 7)):
+        Kb = G.bf16_gpu_to_bits(k[l, h])[None, None]
+        Qb = G.bf16_gpu_to_bits(q[l, h * grp:(h + 1) * grp])[None]
+        check_against_oracle(pooled[l, h][None, None].cpu().numpy(), Kb, Qb, window, 7, lkv.POOL_MAX, what=f"layer {l} head {h}")
+        check_against_oracle(plain[l, h][None, None].cpu().numpy(), Kb, Qb, window, 1, lkv.POOL_MAX, what=f"layer {l} head {h}, unpooled")

@@ -62,3 +62,19 @@ def test_training_attention_draw():
     assert m.min() >= 0.0 and m.max() <= 1.0 and (m == 0).any() and (m == 1).any() and (m[:, 0] >= 0.25).all()
     assert 0.1 < m.mean() < 0.35                       # most weights small, as late in the annealing
     assert abs(W.bf16_bits_to_f32(k).std() - 1.0) < 0.02
+
+
+def test_window_queries_draw():
+    w = W.scaled(W.CONFIGS[0], L=2, H=2, Hq=8, T=300, b_min=1)
+    K, _ = W.draw_kv(w, 300, 0, 3)
+    q = W.draw_window_queries(w, K, 32, 0, 3)
+    assert q.shape == (2, 8, 32, 128) and q.dtype == np.uint16
+    assert np.array_equal(q, W.draw_window_queries(w, K, 32, 0, 3))
+    assert not np.array_equal(q, W.draw_window_queries(w, K, 32, 0, 4))
+    # about half of the rows carry a needle: their norm is above that of a plain N(0, 1) row
+    qf, kf = W.bf16_bits_to_f32(q), W.bf16_bits_to_f32(K)
+    logits = np.einsum("lgwd,lgtd->lgwt", qf.reshape(2, 2, 4 * 32, 128), kf[:, :, :268]) / np.sqrt(128.0)
+    peaked = (logits.max(-1) > 4.0).mean()
+    assert 0.3 < peaked < 0.7
+    # a window as long as the prompt has no prefix to plant needles in
+    assert W.draw_window_queries(w, K, 300, 0, 3).shape == (2, 8, 300, 128)
