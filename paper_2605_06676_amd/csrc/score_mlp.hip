@@ -9,7 +9,7 @@
 //  * W1 fragments (A operand) stay in registers for the whole block:
 //    lane (i, kb) holds W1[16 mt + i][32 ks + 8 kb .. +7].
 //  * Token rows are read from HBM once, coalesced (16 lanes x 16 bytes per
-//    row), staged in a wave-private LDS tile whose row stride of 528 bytes
+//    row), staged in a wave-private LDS tile whose row stride of 544 bytes
 //    makes the fragment reads conflict free, and read back as B fragments:
 //    lane (n, kb) holds X[token n][32 ks + 8 kb .. +7].
 //  * The accumulator layout leaves each lane with 4 hidden units of one token
@@ -25,7 +25,7 @@ namespace lkv {
 constexpr int kMlpThreads = 256;
 constexpr int kMlpWaves = kMlpThreads / 64;
 constexpr int kMlpTokTile = 16;                       // tokens per MFMA N tile
-constexpr int kMlpRowStride = 2 * 256 + 16;           // bytes per staged [k ; v] row in LDS
+constexpr int kMlpRowStride = 2 * 256 + 32;           // bytes per staged [k ; v] row in LDS
 constexpr int kMlpWaveLds = kMlpTokTile * kMlpRowStride;
 constexpr int kMlpKSteps = 8;                         // 256 features / 32 per MFMA
 
