@@ -34,15 +34,9 @@ constexpr int kWinThreads = 128;
 constexpr int kWinTokTile = 16;                  // keys per MFMA N tile
 constexpr int kWinRowStride = 256 + 32;          // bytes per staged key row in LDS
 constexpr int kWinTileLds = kWinTokTile * kWinRowStride;
-#ifndef LKV_WIN_NT
-#define LKV_WIN_NT 2
-#endif
-constexpr int kWinTilesPerStep = LKV_WIN_NT;     // tiles staged, multiplied and finished between two barriers
+constexpr int kWinTilesPerStep = 2;     // tiles staged, multiplied and finished between two barriers
 constexpr int kWinStepLds = kWinTilesPerStep * kWinTileLds;
-#ifndef LKV_WIN_ROWS
-#define LKV_WIN_ROWS 1024
-#endif
-constexpr int kWinMaxRowsPerBlock = LKV_WIN_ROWS;
+constexpr int kWinMaxRowsPerBlock = 1024;
 constexpr float kWinRebase = 64.f;               // log2 distance at which pass 1 moves a reference
 constexpr float kWinNoRef = -1e30f;              // reference of a row that has seen no key yet
 
@@ -208,8 +202,8 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
   };
 
   // Barrier i makes the keys of step i visible and means both waves have finished reading those of step i - 1.
-  // One step: products and arithmetic of its NT tiles, staging of step i + 1 (fetching step i + 3 behind it).
   const int n_steps = (n_tiles + NT - 1) / NT;
+  // One step: products and arithmetic of its NT tiles, staging of step i + 1 (fetching step i + 3 behind it).
   f32x4_t acc[NT][MTW];
   auto step = [&](uint4 (&x_next)[2 * NT], int i) {
     const unsigned char* xt = x_lds + (i & 1) * kWinStepLds;

@@ -98,3 +98,45 @@ def test_captured_training_attention_replays_to_the_eager_result(ctx):
         torch.cuda.synchronize()
         for name, t in outs.items():
             assert torch.equal(t, want[name]), f"replay {rep}: {name}"
+
+
+def test_captured_window_scoring_replays_to_the_eager_result(ctx):
+    # the observation-window scorer is four kernel launches and no copy: captured together with the top-k it feeds,
+    # every replay must give the bits of the eager run
+    w = W.scaled(W.CONFIGS[0], L=2, H=2, Hq=8, b_min=8)
+    T, window = 1900, 32
+    K, _ = W.draw_kv(w, T, 0, 2)
+    Q = W.draw_window_queries(w, K, window, 0, 2)
+    tk, tq = G.bits_to_bf16_gpu(K), G.bits_to_bf16_gpu(Q)
+    cache = lkv.Cache([tk], [tk], w.Hq)
+    budgets = np.full(w.L * w.H, 300, dtype=np.int32)
+    scores = torch.empty((w.L, w.H, T), dtype=torch.float32, device="cuda")
+    idx = torch.empty(int(budgets.sum()), dtype=torch.int32, device="cuda")
+    offsets = torch.empty(budgets.size + 1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+
+    def both():
+        lkv.lkv_score_window(ctx, cache, [tq], window, 7, lkv.POOL_MAX, G.SCALE, [scores], ws)
+        lkv.lkv_select(ctx, cache, [scores], budgets, idx, offsets)
+
+    both()
+    torch.cuda.synchronize()
+    want = (scores.clone(), idx.clone(), offsets.clone())
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        both()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            both()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        scores.fill_(float("nan"))
+        idx.fill_(-3)
+        offsets.fill_(-3)
+        ws.fill_(255)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(scores, want[0]) and torch.equal(idx, want[1]) and torch.equal(offsets, want[2]), f"replay {rep}"
