@@ -1,4 +1,4 @@
-"""Soft-TopK operator ST_k of Sec. 3.2 / App. A.1, forward only, fp64, CPU.
+"""Soft-TopK operator ST_k of Sec. 3.2 / App. A, forward and backward, fp64, CPU.
 
 TEST INFRASTRUCTURE, NOT PRODUCT.  The hot path uses the hard top-k; this
 operator is kept because the paper states that it converges to the hard top-k
@@ -19,6 +19,16 @@ softmax probability is at most 1/2.
 
 Everything is evaluated in log space (log S1, log S2) so that x / tau with a
 tiny tau does not overflow.
+
+Backward (App. A.2).  The threshold is defined implicitly by sum_i f(x_i - lambda) = k, so
+    d lambda / d x_j = f'(x_j - lambda) / sum_i f'(x_i - lambda),
+    d lambda / d k   = -1 / sum_i f'(x_i - lambda),          f'(z) = e^{-|z|} / 2,
+and the outputs y_i = f(x_i / tau - lambda(x / tau, k)) follow by the chain rule.
+``soft_topk_backward`` applies the transposed Jacobian to an upstream gradient g = dL/dy:
+    dL/dx_j = (f'(z_j) / tau) (g_j - gbar),   dL/dk = gbar,   gbar = sum_i g_i w_i,
+with z = x / tau - lambda and w_i = f'(z_i) / sum f'(z) the first of the two derivatives above.
+The weights w are formed relative to the smallest |z| so that a cold temperature, where every
+f'(z_i) underflows, still gives the finite ratios the formulas define.
 """
 from __future__ import annotations
 
@@ -89,3 +99,26 @@ def soft_topk(x: np.ndarray, k: float, tau: float = 1.0) -> np.ndarray:
     xt = x / tau
     lam, _ = soft_topk_lambda(xt, k)
     return laplace_cdf(xt - lam)
+
+
+def laplace_pdf(z: np.ndarray) -> np.ndarray:
+    """f'(z): the density of the Laplace distribution (App. A.2)."""
+    return 0.5 * np.exp(-np.abs(np.asarray(z, dtype=np.float64)))
+
+
+def threshold_weights(z: np.ndarray) -> np.ndarray:
+    """w_j = f'(z_j) / sum_i f'(z_i) = d lambda / d x_j (App. A.2), without underflow of the sum."""
+    a = np.abs(np.asarray(z, dtype=np.float64))
+    e = np.exp(a.min() - a)
+    return e / e.sum()
+
+
+def soft_topk_backward(x: np.ndarray, k: float, tau: float, g: np.ndarray):
+    """(dL/dx, dL/dk) of y = ST_k(x / tau) for the upstream gradient g = dL/dy (App. A.2)."""
+    x = np.asarray(x, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    xt = x / tau
+    lam, _ = soft_topk_lambda(xt, k)
+    z = xt - lam
+    gbar = float((g * threshold_weights(z)).sum())
+    return laplace_pdf(z) * (g - gbar) / tau, gbar

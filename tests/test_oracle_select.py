@@ -4,6 +4,7 @@ import math
 
 import numpy as np
 import pytest
+import torch
 
 from oracle import lkv_oracle as O
 from oracle import soft_topk as ST
@@ -198,3 +199,94 @@ def test_total_budget_is_a_floor():
     assert O.total_budget(0.10, 32, 8, 131072) == 3355443          # 3355443.2
     assert O.total_budget(0.5, 1, 1, 7) == 3                       # 3.5
     assert np.array_equal(O.integer_budgets(np.array([0.5, 0.999, 0.25]), 7), [3, 6, 1])
+
+
+# ---- Soft-TopK backward (App. A.2) ----------------------------------------------------------------
+
+def _torch_closed_form(x, k, m):
+    """y = f(x - lambda) with lambda from the closed form of App. A.1 at a fixed split index m, in torch (fp64):
+    differentiating this expression is the route App. A.2 says it avoids, so autograd through it is independent
+    of the implicit-function formulas the oracle uses."""
+    xs, _ = torch.sort(x, descending=True)
+    s1 = torch.exp(-xs[:m]).sum()
+    s2 = torch.exp(xs[m:]).sum()
+    d = k - m
+    lam = torch.log((torch.sqrt(d * d + s1 * s2) - d) / s1)
+    z = x - lam
+    e = 0.5 * torch.exp(-z.abs())
+    return torch.where(z >= 0, 1.0 - e, e), lam
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_soft_topk_backward_against_autograd_of_the_closed_form(seed):
+    rng = np.random.default_rng(seed)
+    n = 23
+    x = rng.standard_normal(n) * 2.0
+    k = float(rng.uniform(1.5, n - 1.5))
+    g = rng.standard_normal(n)
+    lam, m = ST.soft_topk_lambda(x, k)
+    assert 1 <= m < n
+    tx = torch.from_numpy(x).requires_grad_(True)
+    tk = torch.tensor(k, dtype=torch.float64, requires_grad=True)
+    y, tlam = _torch_closed_form(tx, tk, m)
+    assert abs(float(tlam.detach()) - lam) < 1e-12
+    (y * torch.from_numpy(g)).sum().backward()
+    dx, dk = ST.soft_topk_backward(x, k, 1.0, g)
+    assert np.allclose(dx, tx.grad.numpy(), rtol=0, atol=1e-12)
+    assert abs(dk - float(tk.grad)) < 1e-12
+
+
+def test_threshold_derivatives_of_app_a2_by_finite_differences():
+    rng = np.random.default_rng(7)
+    x = rng.standard_normal(17) * 1.5
+    k = 5.3
+    lam, _ = ST.soft_topk_lambda(x, k)
+    w = ST.threshold_weights(x - lam)
+    assert np.isclose(w.sum(), 1.0, rtol=0, atol=1e-14) and (w > 0).all()
+    h = 1e-6
+    for j in range(x.size):
+        up, dn = x.copy(), x.copy()
+        up[j] += h
+        dn[j] -= h
+        fd = (ST.soft_topk_lambda(up, k)[0] - ST.soft_topk_lambda(dn, k)[0]) / (2 * h)
+        assert abs(fd - w[j]) < 1e-8                                     # d lambda / d x_j
+    fd_k = (ST.soft_topk_lambda(x, k + h)[0] - ST.soft_topk_lambda(x, k - h)[0]) / (2 * h)
+    assert abs(fd_k + 1.0 / ST.laplace_pdf(x - lam).sum()) < 1e-8        # d lambda / d k
+
+
+@pytest.mark.parametrize("tau", [1.0, 0.3, 0.05])
+def test_soft_topk_backward_by_finite_differences_and_identities(tau):
+    rng = np.random.default_rng(11)
+    n = 19
+    x = rng.standard_normal(n)
+    k, g = 6.25, rng.standard_normal(n)
+    dx, dk = ST.soft_topk_backward(x, k, tau, g)
+    h = 1e-6 * tau
+
+    def loss(xx, kk):
+        return float((ST.soft_topk(xx, kk, tau) * g).sum())
+
+    for j in range(n):
+        up, dn = x.copy(), x.copy()
+        up[j] += h
+        dn[j] -= h
+        assert abs((loss(up, k) - loss(dn, k)) / (2 * h) - dx[j]) < 2e-7 / tau
+    assert abs((loss(x, k + 1e-6) - loss(x, k - 1e-6)) / 2e-6 - dk) < 1e-7
+    # the outputs always sum to k: a constant upstream gradient gives no input gradient and dL/dk = that constant
+    dx1, dk1 = ST.soft_topk_backward(x, k, tau, np.full(n, 2.5))
+    assert np.allclose(dx1, 0.0, atol=1e-15 / tau) and abs(dk1 - 2.5) < 1e-14
+    # translation invariance of the forward: the input gradient sums to zero
+    assert abs(dx.sum()) < 1e-12 / tau
+    # linear in g
+    dx2, dk2 = ST.soft_topk_backward(x, k, tau, 3.0 * g)
+    assert np.allclose(dx2, 3.0 * dx, rtol=1e-13) and np.isclose(dk2, 3.0 * dk, rtol=1e-13)
+
+
+def test_soft_topk_backward_cold_limit_stays_finite():
+    # tau -> 0+: every f'(z) underflows, the hard top-k has zero gradient, and dL/dk is g at the element(s) nearest the threshold
+    x = np.array([3.0, -1.0, 0.5, 2.0, -2.5])
+    g = np.array([1.0, 2.0, 3.0, 4.0, 5.0])
+    dx, dk = ST.soft_topk_backward(x, 2.0, 1e-4, g)
+    assert np.isfinite(dx).all() and np.isfinite(dk) and np.allclose(dx, 0.0, atol=1e-300)
+    # k = 2 puts the threshold midway (in x / tau) between the 2nd and 3rd largest inputs, 2.0 and 0.5: both weigh 1/2
+    assert abs(dk - 0.5 * (4.0 + 3.0)) < 1e-9
