@@ -7,7 +7,7 @@
  * during decoding with re-eviction, attention with a multiplicative mask over
  * the uncompacted cache, the training-time attention kernel with that mask
  * (forward and backward), the LKV-H budget allocation with the forward
- * Soft-TopK operator, and the observation-window scorer that the paper's
+ * Soft-TopK operator and its backward pass, and the observation-window scorer that the paper's
  * ablation runs under the same budgets (lkv_score_window).
  *
  * General conventions
@@ -368,6 +368,21 @@ lkv_status lkv_masked_attn_backward(lkv_ctx *ctx, int32_t n_q_heads, int32_t n_k
 int32_t lkv_soft_topk_max_n(int32_t x_is_f64);
 lkv_status lkv_soft_topk(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t n, double k, double tau,
                          double *y, double *info, void *stream);
+
+/* Backward of the Soft-TopK operator (App. A.2).  The threshold is an implicit function of the
+ * inputs; with z_i = x_i / tau - lambda and f'(z) = e^{-|z|} / 2,
+ *   d lambda / d x_j = f'(z_j) / sum_i f'(z_i),   d lambda / d k = -1 / sum_i f'(z_i),
+ * and for an upstream gradient g = dL/dy of y = ST_k(x / tau):
+ *   dx_j = (f'(z_j) / tau) (g_j - gbar),   dk = gbar = sum_i g_i f'(z_i) / sum_i f'(z_i).
+ * fp64 arithmetic, sums in a fixed order (reproducible); the ratios are formed relative to the
+ * smallest |z|, so a temperature so cold that every f'(z_i) underflows gives dx = 0 and a finite dk.
+ * x, x_is_f64, n, tau : as given to lkv_soft_topk
+ * info : DEVICE fp64 [2] as written by that call (info[0] = lambda is read)
+ * g    : DEVICE fp64 [n]
+ * dx   : DEVICE fp64 [n]; may be the same buffer as g
+ * dk   : DEVICE fp64 [1] or NULL */
+lkv_status lkv_soft_topk_backward(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t n, double tau,
+                                  const double *info, const double *g, double *dx, double *dk, void *stream);
 
 /* Shared head predictor of LKV-H (Sec. 3.3; Table 5: 128 -> 64 -> 1, SiLU, hidden bias, no
  * output bias).  All pointers DEVICE fp32; b2 may be NULL. */

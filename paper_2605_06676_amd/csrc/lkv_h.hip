@@ -1,5 +1,5 @@
-// LKV-H at inference time (Sec. 3.3) and the forward Soft-TopK operator ST_k (Sec. 3.2, Eq. 2,
-// App. A.1), in fp64.  Both are tiny next to the cache kernels (L * H <= a few hundred heads,
+// LKV-H at inference time (Sec. 3.3) and the Soft-TopK operator ST_k (Sec. 3.2, Eq. 2, App. A.1;
+// its backward pass, App. A.2, at the end), in fp64.  Both are tiny next to the cache kernels (L * H <= a few hundred heads,
 // computed once and frozen), so one workgroup does the whole operator and the arithmetic is
 // double precision throughout: the ratios decide integer budgets floor(r t).
 //
@@ -332,6 +332,44 @@ soft_topk_large_kernel(const X* __restrict__ x, int n, double k, double tau, dou
   }
 }
 
+// Backward of ST_k (App. A.2).  With z_i = x_i / tau - lambda and f'(z) = e^{-|z|} / 2 the implicit
+// function theorem gives d lambda / d x_j = f'(z_j) / sum_i f'(z_i) = w_j and d lambda / d k =
+// -1 / sum_i f'(z_i), hence for an upstream gradient g = dL/dy
+//   dL/dx_j = (f'(z_j) / tau) (g_j - gbar),   dL/dk = gbar = sum_i g_i w_i.
+// One workgroup, three passes over the input: the smallest |z| (the weights are formed relative to
+// it, so a cold temperature at which every f'(z) underflows still yields the ratios), the two sums,
+// the output.  lambda is read from the forward call's `info`.  Sums in a fixed order.
+template <typename X>
+__global__ void __launch_bounds__(kStThreads)
+soft_topk_backward_kernel(const X* __restrict__ x, int n, double tau, const double* __restrict__ info,
+                          const double* __restrict__ g, double* __restrict__ dx, double* __restrict__ dk) {
+  __shared__ StLargeShared sh;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const double lambda = info[0];
+  double amin = INFINITY;
+  for (int i = tid; i < n; i += kStThreads) amin = fmin(amin, fabs((double)x[i] / tau - lambda));
+  for (int off = 32; off > 0; off >>= 1) amin = fmin(amin, __shfl_xor(amin, off, 64));
+  if (lane == 0) sh.d[0][wave] = amin;
+  __syncthreads();
+  for (int w = 0; w < kStThreads / 64; ++w) amin = fmin(amin, sh.d[0][w]);
+  double v[4] = {0.0, 0.0, 0.0, 0.0};
+  long long cnt[2] = {0, 0};
+  for (int i = tid; i < n; i += kStThreads) {
+    const double e = exp(amin - fabs((double)x[i] / tau - lambda));
+    v[0] += e;
+    v[1] += g[i] * e;
+  }
+  st_block_sum(&sh, v, cnt);
+  const double gbar = v[1] / v[0];
+  if (tid == 0 && dk != nullptr) dk[0] = gbar;
+  const double inv_tau = 1.0 / tau;
+  for (int i = tid; i < n; i += kStThreads) {
+    const double a = fabs((double)x[i] / tau - lambda);
+    dx[i] = 0.5 * exp(-a) * (g[i] - gbar) * inv_tau;
+  }
+}
+
 // s = w2 . SiLU(W1 e + b1) (+ b2) for one head per block
 __global__ void __launch_bounds__(256)
 head_scores_kernel(const float* __restrict__ emb, const float* __restrict__ w1, const float* __restrict__ b1,
@@ -400,6 +438,16 @@ void launch_soft_topk(const void* x, bool is_f64, int n, double k, double tau, d
   else
     hipLaunchKernelGGL((soft_topk_kernel<float, uint32_t>), dim3(1), dim3(kStThreads), soft_topk_lds(P, 4), stream,
                        static_cast<const float*>(x), n, P, k, tau, y, info, budgets, t);
+}
+
+void launch_soft_topk_backward(const void* x, bool is_f64, int n, double tau, const double* info, const double* g,
+                               double* dx, double* dk, hipStream_t stream) {
+  if (is_f64)
+    hipLaunchKernelGGL(soft_topk_backward_kernel<double>, dim3(1), dim3(kStThreads), 0, stream,
+                       static_cast<const double*>(x), n, tau, info, g, dx, dk);
+  else
+    hipLaunchKernelGGL(soft_topk_backward_kernel<float>, dim3(1), dim3(kStThreads), 0, stream,
+                       static_cast<const float*>(x), n, tau, info, g, dx, dk);
 }
 
 void launch_head_scores(const float* emb, const float* w1, const float* b1, const float* w2, const float* b2,

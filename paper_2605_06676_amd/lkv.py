@@ -23,7 +23,7 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score",
            "lkv_score_window_workspace_bytes", "lkv_score_window", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
-           "lkv_soft_topk", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
+           "lkv_soft_topk", "lkv_soft_topk_backward", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
            "lkv_append", "lkv_decode_attn_grown", "lkv_reevict", "lkv_masked_decode_workspace_bytes",
            "lkv_masked_decode_attn", "lkv_masked_attn_forward",
            "lkv_masked_attn_backward_workspace_bytes", "lkv_masked_attn_backward")
@@ -132,6 +132,9 @@ def load_library() -> C.CDLL:
     lib.lkv_soft_topk.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_double, C.c_void_p,
                                   C.c_void_p, C.c_void_p]
     lib.lkv_soft_topk.restype = C.c_int
+    lib.lkv_soft_topk_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.lkv_soft_topk_backward.restype = C.c_int
     lib.lkv_head_budgets.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_HeadPredictor), C.c_int32, C.c_double,
                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lkv_head_budgets.restype = C.c_int
@@ -275,6 +278,18 @@ def lkv_soft_topk(ctx: Context, x, k: float, tau: float, y, info=None, stream=No
     assert info is None or (info.dtype == torch.float64 and info.numel() >= 2)
     ctx._check(ctx.lib.lkv_soft_topk(ctx.h, _ptr(x), 1 if x.dtype == torch.float64 else 0, int(x.numel()), float(k),
                                      float(tau), _ptr(y), _ptr(info), _stream_ptr(stream)))
+
+
+def lkv_soft_topk_backward(ctx: Context, x, tau: float, info, g, dx, dk=None, stream=None) -> None:
+    """x: the forward call's input; info: GPU fp64 [2] as that call wrote it; g, dx: GPU fp64 [n]; dk: GPU fp64 [1] or None."""
+    import torch
+
+    assert x.dtype in (torch.float32, torch.float64) and x.is_contiguous()
+    assert info.dtype == torch.float64 and info.numel() >= 2
+    assert all(t.dtype == torch.float64 and t.numel() == x.numel() and t.is_contiguous() for t in (g, dx))
+    assert dk is None or (dk.dtype == torch.float64 and dk.numel() >= 1)
+    ctx._check(ctx.lib.lkv_soft_topk_backward(ctx.h, _ptr(x), 1 if x.dtype == torch.float64 else 0, int(x.numel()),
+                                              float(tau), _ptr(info), _ptr(g), _ptr(dx), _ptr(dk), _stream_ptr(stream)))
 
 
 def lkv_head_budgets(ctx: Context, emb, predictor: dict, R: float, t: int, r, b=None, stream=None) -> None:

@@ -1,5 +1,5 @@
-"""GPU parity of the LKV-H inference side and the forward Soft-TopK (Sec. 3.2, Sec. 3.3, App. A.1)
-against the CPU oracle.  Both sides compute in fp64; the differences left are summation order."""
+"""GPU parity of the LKV-H inference side and the Soft-TopK operator, forward and backward (Sec. 3.2, Sec. 3.3,
+App. A) against the CPU oracle.  Both sides compute in fp64; the differences left are summation order."""
 import math
 
 import numpy as np
@@ -180,6 +180,80 @@ def test_soft_topk_argument_errors(ctx):
     with pytest.raises(lkv.LkvError) as e:
         lkv.lkv_soft_topk(ctx, big, 5.0, 1.0, torch.empty(limit + 1, dtype=torch.float64, device="cuda"))
     assert e.value.status == 2
+    torch.cuda.synchronize()
+
+
+# ---- Soft-TopK backward (App. A.2) ----------------------------------------------------------------
+
+def _gpu_soft_topk_backward(ctx, x, k, tau, g, in_place=False):
+    xt = torch.from_numpy(np.ascontiguousarray(x)).cuda()
+    y = torch.empty(x.size, dtype=torch.float64, device="cuda")
+    info = torch.empty(2, dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk(ctx, xt, k, tau, y, info)
+    gt = torch.from_numpy(np.ascontiguousarray(g, dtype=np.float64)).cuda()
+    dx = gt if in_place else torch.full((x.size,), float("nan"), dtype=torch.float64, device="cuda")
+    dk = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk_backward(ctx, xt, tau, info, gt, dx, dk)
+    torch.cuda.synchronize()
+    return dx.cpu().numpy(), float(dk.cpu()[0])
+
+
+@pytest.mark.parametrize("n,dtype,tau", [(1, np.float64, 1.0), (2, np.float32, 1.0), (65, np.float64, 0.3), (1024, np.float32, 1.0),
+                                         (1025, np.float64, 0.05), (4097, np.float32, 2.0), (3000, np.float64, 1e-2)])
+def test_soft_topk_backward_matches_the_oracle(ctx, n, dtype, tau):
+    # both sides in fp64 on the same inputs; each side uses its own threshold (they agree to 1e-9), so the
+    # gradients agree to that times the slope f' / tau <= 1 / (2 tau), with the size of g as the scale
+    rng = np.random.default_rng(n)
+    x = rng.standard_normal(n).astype(dtype)
+    k = float(rng.uniform(0.2, 0.8)) * n if n > 1 else 0.4
+    g = rng.standard_normal(n)
+    dx, dk = _gpu_soft_topk_backward(ctx, x, k, tau, g)
+    dx_ref, dk_ref = ST.soft_topk_backward(x.astype(np.float64), k, tau, g)
+    scale = max(1.0, float(np.abs(g).max()))
+    assert np.abs(dx - dx_ref).max() <= 1e-8 * scale / tau, f"worst {np.abs(dx - dx_ref).max():.3g}"
+    assert abs(dk - dk_ref) <= 1e-8 * scale
+    assert abs(dx.sum()) <= 1e-9 * scale * n / tau                      # translation invariance of the forward
+
+
+def test_soft_topk_backward_identities_on_a_long_input(ctx):
+    # 131072 values (the sort-free forward): a constant upstream gradient gives no input gradient and dL/dk equal to
+    # the constant; the gradient is linear in g; a second call gives the same bits; dx may overwrite g
+    rng = np.random.default_rng(3)
+    n = 131072
+    x = rng.standard_normal(n).astype(np.float32)
+    k, tau = 0.15 * n, 0.7
+    dx1, dk1 = _gpu_soft_topk_backward(ctx, x, k, tau, np.full(n, 2.5))
+    assert np.abs(dx1).max() <= 1e-12 and abs(dk1 - 2.5) <= 1e-12
+    g = rng.standard_normal(n)
+    dx, dk = _gpu_soft_topk_backward(ctx, x, k, tau, g)
+    dx3, dk3 = _gpu_soft_topk_backward(ctx, x, k, tau, 3.0 * g)
+    assert np.allclose(dx3, 3.0 * dx, rtol=1e-12, atol=1e-15) and np.isclose(dk3, 3.0 * dk, rtol=1e-12)
+    dx_again, dk_again = _gpu_soft_topk_backward(ctx, x, k, tau, g, in_place=True)
+    assert np.array_equal(dx, dx_again) and dk == dk_again
+    assert abs(dx.sum()) <= 1e-9 and np.isfinite(dx).all()
+    # against the formula, with the GPU's own outputs: y_i = f(z_i) gives f'(z_i) = min(y_i, 1 - y_i)
+    y = torch.empty(n, dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk(ctx, torch.from_numpy(x).cuda(), k, tau, y)
+    p = torch.minimum(y, 1.0 - y).cpu().numpy()
+    gbar = float((g * p).sum() / p.sum())
+    assert abs(dk - gbar) <= 1e-10
+    assert np.abs(dx - p * (g - gbar) / tau).max() <= 1e-10
+
+
+def test_soft_topk_backward_cold_limit_and_errors(ctx):
+    # a temperature at which every f'(z) underflows: zero input gradient, finite dL/dk (the mean of g over the two
+    # inputs nearest the threshold, which sits midway between them)
+    x = np.array([3.0, -1.0, 0.5, 2.0, -2.5])
+    g = np.array([1.0, 2.0, 3.0, 4.0, 5.0])
+    dx, dk = _gpu_soft_topk_backward(ctx, x, 2.0, 1e-4, g)
+    assert np.array_equal(dx, np.zeros(5)) and abs(dk - 3.5) <= 1e-9
+    xt = torch.zeros(10, dtype=torch.float64, device="cuda")
+    info = torch.zeros(2, dtype=torch.float64, device="cuda")
+    buf = torch.zeros(10, dtype=torch.float64, device="cuda")
+    for tau in (0.0, -1.0, float("inf"), float("nan")):
+        with pytest.raises(lkv.LkvError) as e:
+            lkv.lkv_soft_topk_backward(ctx, xt, tau, info, buf, buf)
+        assert e.value.status == 1
     torch.cuda.synchronize()
 
 
