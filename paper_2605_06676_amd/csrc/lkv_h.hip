@@ -1,5 +1,5 @@
 // LKV-H at inference time (Sec. 3.3) and the Soft-TopK operator ST_k (Sec. 3.2, Eq. 2, App. A.1;
-// its backward pass, App. A.2, at the end), in fp64.  Both are tiny next to the cache kernels (L * H <= a few hundred heads,
+// its backward pass, App. A.2, further down), in fp64.  Both are tiny next to the cache kernels (L * H <= a few hundred heads,
 // computed once and frozen), so one workgroup does the whole operator and the arithmetic is
 // double precision throughout: the ratios decide integer budgets floor(r t).
 //

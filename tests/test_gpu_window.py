@@ -207,3 +207,16 @@ def test_full_size_sampled_heads(ctx):
         Qb = G.bf16_gpu_to_bits(q[l, h * grp:(h + 1) * grp])[None]
         check_against_oracle(pooled[l, h][None, None].cpu().numpy(), Kb, Qb, window, 7, lkv.POOL_MAX, what=f"layer {l} head {h}")
         check_against_oracle(plain[l, h][None, None].cpu().numpy(), Kb, Qb, window, 1, lkv.POOL_MAX, what=f"layer {l} head {h}, unpooled")
+
+
+def test_more_sequences_than_one_launch_table_holds(ctx):
+    # 35 short sequences of different lengths: the call splits them over two launch tables and walks the workspace on
+    w = W.scaled(W.CONFIGS[0], L=1, H=2, Hq=4, T=64, b_min=1)
+    rng = np.random.default_rng(9)
+    lens = [int(t) for t in rng.integers(9, 140, size=35)]
+    window = 8
+    Ks = [W.draw_kv(w, T, s, 9)[0] for s, T in enumerate(lens)]
+    Qs = [W.draw_window_queries(w, K, window, s, 9) for s, K in enumerate(Ks)]
+    _, scores = run_gpu(ctx, Ks, Qs, w.Hq, window, 3, lkv.POOL_AVG)
+    for s in range(len(lens)):
+        check_against_oracle(scores[s].cpu().numpy(), Ks[s], Qs[s], window, 3, lkv.POOL_AVG, what=f"sequence {s}")
