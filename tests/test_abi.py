@@ -43,3 +43,20 @@ def test_calls_that_need_no_gpu():
     # calls that need a context refuse a null one without touching the GPU
     assert lib.lkv_masked_attn_forward(None, 4, 2, 8, 128, None, None, None, None, 1.0, None, None, None) == 1
     assert lib.lkv_last_error(None) == b"context is NULL"
+
+
+def test_header_is_plain_c_and_links_from_c(tmp_path):
+    # the header must compile as strict C99 and as C++; a C client built against it links with the library and runs
+    import subprocess
+
+    inc = os.path.join(ROOT, "include")
+    hdr = os.path.join(inc, "lkv.h")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-x", "c", hdr], check=True)
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-x", "c++", hdr], check=True)
+    lkv.load_library()                                    # raises if the library has not been built
+    libdir = os.path.dirname(lkv.LIB_PATH)
+    exe = str(tmp_path / "c_abi_check")
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-I", inc, os.path.join(ROOT, "tests", "c_abi_check.c"),
+                    "-L", libdir, "-llkv", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-o", exe], check=True)
+    out = subprocess.run([exe], check=True, capture_output=True, text=True)
+    assert "c abi ok" in out.stdout
