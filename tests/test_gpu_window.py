@@ -220,3 +220,24 @@ def test_more_sequences_than_one_launch_table_holds(ctx):
     _, scores = run_gpu(ctx, Ks, Qs, w.Hq, window, 3, lkv.POOL_AVG)
     for s in range(len(lens)):
         check_against_oracle(scores[s].cpu().numpy(), Ks[s], Qs[s], window, 3, lkv.POOL_AVG, what=f"sequence {s}")
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_random_shapes(ctx, seed):
+    # groups, windows, lengths, pooling and logit scales drawn at random; now and then the window is the whole prompt
+    rng = np.random.default_rng(500 + seed)
+    L, H = int(rng.integers(1, 3)), int(rng.integers(1, 4))
+    g = int(rng.choice([1, 2, 3, 4, 5, 8, 16]))
+    window = int(rng.integers(1, 128 // g + 1))
+    n_seq = int(rng.integers(1, 4))
+    Ts = [int(rng.integers(window, 3000)) for _ in range(n_seq)]
+    if rng.random() < 0.15:
+        Ts[0] = window
+    pool, kind = int(rng.choice([1, 3, 5, 7, 9, 13, 31, 63])), int(rng.integers(0, 2))
+    scale = G.SCALE * float(rng.choice([1.0, 1.0, 3.0, 12.0]))
+    w = W.scaled(W.CONFIGS[0], L=L, H=H, Hq=H * g, n_seq=n_seq, T=64, b_min=1)
+    Ks = [W.draw_kv(w, T, s, seed)[0] for s, T in enumerate(Ts)]
+    Qs = [W.draw_window_queries(w, K, window, s, seed) for s, K in enumerate(Ks)]
+    _, scores = run_gpu(ctx, Ks, Qs, w.Hq, window, pool, kind, scale)
+    for s in range(n_seq):
+        check_against_oracle(scores[s].cpu().numpy(), Ks[s], Qs[s], window, pool, kind, scale, what=f"random {seed}, sequence {s}")
