@@ -126,7 +126,7 @@ lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *sco
  * so that lkv_select with a budget b >= W keeps the window and the b - W prefix
  * tokens with the largest pooled votes.  bf16 inputs, fp32 accumulation and
  * fp32 softmax; each key row is read twice (once for the normalisers, once
- * for the weights) and cache->v is not read.
+ * for the weights); cache->v is not read and may be NULL.
  * q_win     : HOST [n_seq] of DEVICE pointers, bf16 [L, Hq, W, 128]: the queries
  *             of the last W positions (as they met the keys in prefill, i.e.
  *             position-encoded like the cached keys)

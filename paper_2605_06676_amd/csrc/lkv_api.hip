@@ -217,7 +217,8 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
                             int32_t pool_width, int32_t pool_kind, float scale, float* const* scores,
                             void* workspace, size_t workspace_bytes, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
-  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (lkv_status st = check_cache(ctx, cache, false)) return st;   // only the keys are read
+  if (cache->k == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "k table is NULL");
   if (q_win == nullptr || scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q_win or scores is NULL");
   if (window < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "window = %d must be >= 1", window);
   if (pool_width < 1 || pool_width % 2 == 0 || pool_width > 63)
@@ -231,6 +232,8 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
   for (int s = 0; s < cache->n_seq; ++s) {
     if (window > cache->seq_len[s])
       return fail(ctx, LKV_ERR_INVALID_ARG, "window = %d exceeds seq_len[%d] = %d", window, s, cache->seq_len[s]);
+    if (cache->k[s] == nullptr || !aligned16(cache->k[s]))
+      return fail(ctx, LKV_ERR_INVALID_ARG, "k[%d] is NULL or not 16-byte aligned", s);
     if (q_win[s] == nullptr || !aligned16(q_win[s]))
       return fail(ctx, LKV_ERR_INVALID_ARG, "q_win[%d] is NULL or not 16-byte aligned", s);
     if (scores[s] == nullptr || !aligned16(scores[s]))

@@ -170,6 +170,12 @@ def test_argument_errors(ctx):
     assert status(ws=ws[1:]) == 3                      # misaligned
     lkv.lkv_score_window(ctx, cache, [q], 32, 7, lkv.POOL_MAX, G.SCALE, [s], ws)    # and the good call goes through
     torch.cuda.synchronize()
+    want = s.clone()
+    cache.c.v = None                                   # the value table is not read and may be absent
+    s.fill_(float("nan"))
+    lkv.lkv_score_window(ctx, cache, [q], 32, 7, lkv.POOL_MAX, G.SCALE, [s], ws)
+    torch.cuda.synchronize()
+    assert torch.equal(s, want)
 
 
 def test_full_size_sampled_heads(ctx):
