@@ -126,7 +126,10 @@ lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *sco
  * so that lkv_select with a budget b >= W keeps the window and the b - W prefix
  * tokens with the largest pooled votes.  bf16 inputs, fp32 accumulation and
  * fp32 softmax; each key row is read twice (once for the normalisers, once
- * for the weights); cache->v is not read and may be NULL.
+ * for the weights); cache->v is not read and may be NULL.  Results are reproducible bit for bit
+ * for the same call; the keys are split into blocks by the size of the whole call, so a layer
+ * scored alone and the same layer scored inside a whole-cache call can differ in the last bits
+ * (the order of the fp32 sums), never in more.
  * q_win     : HOST [n_seq] of DEVICE pointers, bf16 [L, Hq, W, 128]: the queries
  *             of the last W positions (as they met the keys in prefill, i.e.
  *             position-encoded like the cached keys)
@@ -213,10 +216,12 @@ lkv_status lkv_plan_offsets(lkv_ctx *ctx, int64_t n_segments, const int32_t *bud
  * layer       : a cache description with n_layers = 1 whose k[s], v[s] point at bf16 [H, T_s, d] of
  *               this layer; at most 32 sequences
  * layer_index : which layer of the model this is, in [0, n_layers)
- * scorer      : the whole model's scorer (parameters of all layers), as for lkv_score
+ * scorer      : the whole model's scorer (parameters of all layers), as for lkv_score; or NULL:
+ *               `scores` already holds this layer's scores (from any scorer, for example
+ *               lkv_score_window on the same layer view) and only the top-k and the compaction run
  * budgets     : HOST int32 [n_seq, n_layers, H], the same table lkv_plan_offsets was given
  * offsets     : DEVICE int32 [n_seq * n_layers * H + 1] written by lkv_plan_offsets
- * scores      : HOST [n_seq] of DEVICE fp32 [H, T_s]: scratch, overwritten
+ * scores      : HOST [n_seq] of DEVICE fp32 [H, T_s]: scratch, overwritten (an input when scorer is NULL)
  * idx         : DEVICE int32 [total_kept], the global index buffer (this layer's part is written)
  * kp, vp      : DEVICE bf16 [total_kept, d], the global packed cache (this layer's rows are written) */
 lkv_status lkv_evict_layer(lkv_ctx *ctx, const lkv_cache *layer, int32_t layer_index, int32_t n_layers,

@@ -464,8 +464,11 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   if (layer->n_layers != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "the layer view must have n_layers = 1, got %d", layer->n_layers);
   if (n_layers < 1 || layer_index < 0 || layer_index >= n_layers)
     return fail(ctx, LKV_ERR_INVALID_ARG, "layer_index %d is outside [0, %d)", layer_index, n_layers);
-  if (scorer == nullptr || budgets == nullptr || offsets == nullptr || scores == nullptr)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "scorer, budgets, offsets or scores is NULL");
+  if (budgets == nullptr || offsets == nullptr || scores == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "budgets, offsets or scores is NULL");
+  for (int s = 0; s < layer->n_seq; ++s)
+    if (scores[s] == nullptr || !aligned16(scores[s]))
+      return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL or not 16-byte aligned", s);
   const int H = layer->n_kv_heads;
   const int heads_all = n_layers * H;
   const int64_t n_seg = (int64_t)heads_all * layer->n_seq;
@@ -492,20 +495,22 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   if (layer_rows > 0 && (idx == nullptr || kp == nullptr || vp == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "idx, kp or vp is NULL");
   if (!aligned16(kp) || !aligned16(vp)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is not 16-byte aligned");
 
-  // score: the scorer parameters of this layer
-  if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
-  lkv_scorer sl = *scorer;
-  const size_t rows = (size_t)layer_index * (scorer->per_head ? H : 1);   // scorer rows ahead of this layer
-  if (scorer->kind == LKV_SCORER_LINEAR) {
-    sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * 2 * lkv::kHeadDim;
-    sl.b1 = scorer->b1 + rows;
-  } else {
-    sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * (size_t)scorer->hidden * 2 * lkv::kHeadDim;
-    sl.b1 = scorer->b1 + rows * scorer->hidden;
-    sl.w2 = scorer->w2 + rows * scorer->hidden;
-    sl.b2 = scorer->b2 != nullptr ? scorer->b2 + rows : nullptr;
+  // score with this layer's scorer parameters, unless the caller has already scored the layer
+  if (scorer != nullptr) {
+    if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
+    lkv_scorer sl = *scorer;
+    const size_t rows = (size_t)layer_index * (scorer->per_head ? H : 1);   // scorer rows ahead of this layer
+    if (scorer->kind == LKV_SCORER_LINEAR) {
+      sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * 2 * lkv::kHeadDim;
+      sl.b1 = scorer->b1 + rows;
+    } else {
+      sl.w1 = static_cast<const uint16_t*>(scorer->w1) + rows * (size_t)scorer->hidden * 2 * lkv::kHeadDim;
+      sl.b1 = scorer->b1 + rows * scorer->hidden;
+      sl.w2 = scorer->w2 + rows * scorer->hidden;
+      sl.b2 = scorer->b2 != nullptr ? scorer->b2 + rows : nullptr;
+    }
+    if (lkv_status st = lkv_score(ctx, layer, &sl, scores, stream)) return st;
   }
-  if (lkv_status st = lkv_score(ctx, layer, &sl, scores, stream)) return st;
 
   hipStream_t st = as_stream(stream);
   lkv::SeqTable tab;

@@ -330,9 +330,9 @@ def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int,
 
     b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
     assert b.size == layer.n_seq * n_layers * layer.H
-    sc = _scorer_struct(scorer)
+    sc = None if scorer is None else C.byref(_scorer_struct(scorer))     # None: `scores` is an input
     sp = (C.c_void_p * layer.n_seq)(*[s.data_ptr() for s in scores])
-    ctx._check(ctx.lib.lkv_evict_layer(ctx.h, C.byref(layer.c), layer_index, n_layers, C.byref(sc),
+    ctx._check(ctx.lib.lkv_evict_layer(ctx.h, C.byref(layer.c), layer_index, n_layers, sc,
                                        b.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(offsets), sp, _ptr(idx), _ptr(kp),
                                        _ptr(vp), _stream_ptr(stream)))
 

@@ -247,3 +247,52 @@ def test_random_shapes(ctx, seed):
     _, scores = run_gpu(ctx, Ks, Qs, w.Hq, window, pool, kind, scale)
     for s in range(n_seq):
         check_against_oracle(scores[s].cpu().numpy(), Ks[s], Qs[s], window, pool, kind, scale, what=f"random {seed}, sequence {s}")
+
+
+def test_layer_by_layer_eviction_with_window_scores(ctx):
+    # the prefill-time flow with this scorer: per layer, score the layer view, then lkv_evict_layer without a scorer
+    # (top-k and compaction of given scores); the packed cache must equal what the whole-cache top-k and compaction
+    # make of the same scores, bit for bit
+    w = W.scaled(W.CONFIGS[0], L=3, H=2, Hq=8, T=64, b_min=1)
+    lens, window = [1500, 260], 32
+    Ks, Vs = zip(*[W.draw_kv(w, T, s, 13) for s, T in enumerate(lens)])
+    Qs = [W.draw_window_queries(w, K, window, s, 13) for s, K in enumerate(Ks)]
+    tk, tv = [G.bits_to_bf16_gpu(x) for x in Ks], [G.bits_to_bf16_gpu(x) for x in Vs]
+    tq = [G.bits_to_bf16_gpu(x) for x in Qs]
+    rng = np.random.default_rng(13)
+    budgets = np.concatenate([rng.integers(window, T // 2, size=w.L * w.H) for T in lens]).astype(np.int32)
+    total = int(budgets.sum())
+    n_seg = budgets.size
+
+    def buffers():
+        return (torch.full((total,), -1, dtype=torch.int32, device="cuda"), torch.full((n_seg + 1,), -1, dtype=torch.int32, device="cuda"),
+                torch.zeros((total, 128), dtype=torch.bfloat16, device="cuda"), torch.zeros((total, 128), dtype=torch.bfloat16, device="cuda"))
+
+    cache = lkv.Cache(tk, tv, w.Hq)
+    whole_scores = [torch.empty((w.L, w.H, T), dtype=torch.float32, device="cuda") for T in lens]
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    lkv.lkv_score_window(ctx, cache, tq, window, 7, lkv.POOL_MAX, G.SCALE, whole_scores, ws)
+    # layer by layer, in some order
+    idx2, offsets2, kp2, vp2 = buffers()
+    assert lkv.lkv_plan_offsets(ctx, budgets, offsets2) == total
+    layer_scores = [torch.empty((w.H, T), dtype=torch.float32, device="cuda") for T in lens]
+    scores = [torch.empty((w.L, w.H, T), dtype=torch.float32, device="cuda") for T in lens]
+    for l in (2, 0, 1):
+        view = lkv.Cache([k[l:l + 1] for k in tk], [v[l:l + 1] for v in tv], w.Hq)
+        lkv.lkv_score_window(ctx, view, [q[l:l + 1].contiguous() for q in tq], window, 7, lkv.POOL_MAX, G.SCALE,
+                             [s[None] for s in layer_scores], ws)
+        lkv.lkv_evict_layer(ctx, view, l, w.L, None, budgets, offsets2, layer_scores, idx2, kp2, vp2)
+        torch.cuda.synchronize()
+        for s in range(len(lens)):
+            scores[s][l].copy_(layer_scores[s])
+            # a launch over one layer may split the keys into other blocks than a launch over all of them, which
+            # changes the order of the fp32 sums and nothing else
+            pre = slice(0, lens[s] - window)
+            assert torch.allclose(layer_scores[s][:, pre], whole_scores[s][l][:, pre], rtol=1e-5, atol=1e-9)
+    # the whole-cache top-k and compaction of the same scores
+    idx, offsets, kp, vp = buffers()
+    lkv.lkv_select(ctx, cache, scores, budgets, idx, offsets)
+    lkv.lkv_compact(ctx, cache, idx, offsets, total, kp, vp)
+    torch.cuda.synchronize()
+    assert torch.equal(offsets2, offsets) and torch.equal(idx2, idx)
+    assert torch.equal(kp2.view(torch.int16), kp.view(torch.int16)) and torch.equal(vp2.view(torch.int16), vp.view(torch.int16))
