@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=1, help="workload 0..5 (1 = the Llama-3-8B-shaped 32k cache)")
+    ap.add_argument("--seq-len", type=int, default=0, metavar="T",
+                    help="override the context length of a fixed-length workload (the paper's overhead run is at 200k, Sec. 4.5)")
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
                     help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -78,6 +80,11 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = W.CONFIGS[args.config]
+    if args.seq_len:
+        if not isinstance(w.T, int):
+            print("bench.py: --seq-len needs a workload with one fixed length", file=sys.stderr)
+            sys.exit(2)
+        w = W.scaled(w, T=args.seq_len, name=f"{w.name}-T{args.seq_len}")
     ctx = lkv.Context(0)
     layerwise_result = None
 
@@ -203,7 +210,7 @@ def main():
                      else ("score_mlp_kernel" if w.hidden <= 64 else "score_mlp_wide_kernel"),
                      "bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS,
-                     "traffic": MEASURED_SCORE_TRAFFIC_BYTES.get(args.config),
+                     "traffic": None if args.seq_len else MEASURED_SCORE_TRAFFIC_BYTES.get(args.config),
                      "launches_per_step": 1 if w.n_seq <= 32 else math.ceil(w.n_seq / 32),
                      "bytes_per_launch": score_bytes},
     }
