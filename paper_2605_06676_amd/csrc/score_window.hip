@@ -13,9 +13,9 @@
 //   pass 1  per window row, the log-sum-exp of its logits over one block's keys (causal inside
 //           the window), written as a (reference, sum) pair per block;
 //   merge   the pairs of all blocks of a head into each row's log-normaliser (a small kernel);
-//   pass 2  recomputes
-//           the logits and adds exp(logit - normaliser) over the rows: the token's vote;
-//   pool    smooths the votes and writes the scores.
+//   pass 2  recomputes the logits and adds exp(logit - normaliser) over the rows: the token's vote,
+//           each wave of a block writing the share of its own rows;
+//   pool    adds the two shares, takes the group mean, smooths and writes the scores.
 // Keeping the logits instead would cost as many bytes as reading the keys again (G W = 128
 // logits per 128-element key).
 //
@@ -24,8 +24,10 @@
 // binary orders of magnitude, which costs one exponential per logit instead of two.  Any
 // reference within that distance of the true maximum gives the same sum to fp32 rounding.
 //
-// A block is a pair of waves that share each staged tile of 16 keys; the window rows are split
-// between the two (at most 64 rows, 64 fragment registers, per wave).
+// A block is a pair of waves that share the staged keys (two tiles of 16 between barriers); the
+// window rows are split between the two (at most 64 rows, 64 fragment registers, per wave).
+// Both passes are bound by instruction issue rather than by HBM: per key and row one exponential
+// (quarter rate) next to the matrix work, which the hardware overlaps only in part.
 #include "lkv_common.h"
 
 namespace lkv {
@@ -54,8 +56,9 @@ __device__ __forceinline__ float row16_allreduce_max(float x) {
   return x;
 }
 
-// kPass 1: partial log-sum-exp pairs.  kPass 2: votes (the merged normalisers are read from the workspace).  MTW: 16-row M tiles per wave; the rows past
-// n_rows = G W are padding (zero queries, never counted).
+// kPass 1: partial log-sum-exp pairs.  kPass 2: votes (the merged normalisers are read from the
+// workspace).  MTW: 16-row M tiles per wave; the rows past n_rows = G W are padding (zero queries,
+// never counted).
 template <int MTW, int kPass>
 __global__ void __launch_bounds__(kWinThreads, 2)
 score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_per_block, float log2_scale) {
