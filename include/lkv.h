@@ -389,6 +389,19 @@ lkv_status lkv_soft_topk(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t 
 lkv_status lkv_soft_topk_backward(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t n, double tau,
                                   const double *info, const double *g, double *dx, double *dk, void *stream);
 
+/* The two calls above for n_vec vectors of n values at once, one workgroup per vector: what the
+ * relaxed forward of Sec. 3.4 needs, one soft mask m = ST_b((u + g) / tau) per head of a layer.
+ * x, y, g, dx : DEVICE [n_vec, n], row-major; info : DEVICE fp64 [n_vec, 2]; dk : DEVICE fp64 [n_vec] or NULL
+ * k    : DEVICE fp64 [n_vec], the target sum of every vector (for example r_h * t from
+ *        lkv_head_budgets' ratios); values are clamped into [1e-6, n - 1e-6], the open interval
+ *        the paper keeps the budget in (App. A.1)
+ * n    : >= 2 for the forward call (the interval above is empty otherwise) */
+lkv_status lkv_soft_topk_batched(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t n_vec, int32_t n,
+                                 const double *k, double tau, double *y, double *info, void *stream);
+lkv_status lkv_soft_topk_backward_batched(lkv_ctx *ctx, const void *x, int32_t x_is_f64, int32_t n_vec, int32_t n,
+                                          double tau, const double *info, const double *g, double *dx,
+                                          double *dk, void *stream);
+
 /* Shared head predictor of LKV-H (Sec. 3.3; Table 5: 128 -> 64 -> 1, SiLU, hidden bias, no
  * output bias).  All pointers DEVICE fp32; b2 may be NULL. */
 typedef struct lkv_head_predictor {

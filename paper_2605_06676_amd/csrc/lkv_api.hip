@@ -825,6 +825,40 @@ lkv_status lkv_soft_topk_backward(lkv_ctx* ctx, const void* x, int32_t x_is_f64,
   return LKV_OK;
 }
 
+lkv_status lkv_soft_topk_batched(lkv_ctx* ctx, const void* x, int32_t x_is_f64, int32_t n_vec, int32_t n, const double* k,
+                                 double tau, double* y, double* info, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (x == nullptr || y == nullptr || k == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "x, y or k is NULL");
+  if (n < 2) return fail(ctx, LKV_ERR_INVALID_ARG, "n = %d must be >= 2", n);
+  if (n_vec < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n_vec = %d must be >= 1", n_vec);
+  if (!(tau > 0.0) || std::isinf(tau)) return fail(ctx, LKV_ERR_INVALID_ARG, "tau = %g must be positive and finite", tau);
+  if (n > lkv::soft_topk_max_n(x_is_f64 != 0))
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "n = %d exceeds the limit %d", n, lkv::soft_topk_max_n(x_is_f64 != 0));
+  if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, LKV_ERR_HIP, "hipSetDevice failed");
+  lkv::launch_soft_topk(x, x_is_f64 != 0, n, 0.0, tau, y, info, nullptr, 0.0, as_stream(stream), n_vec, k);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e, "batched soft top-k launch");
+  return LKV_OK;
+}
+
+lkv_status lkv_soft_topk_backward_batched(lkv_ctx* ctx, const void* x, int32_t x_is_f64, int32_t n_vec, int32_t n,
+                                          double tau, const double* info, const double* g, double* dx, double* dk,
+                                          void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (x == nullptr || info == nullptr || g == nullptr || dx == nullptr)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "x, info, g or dx is NULL");
+  if (n < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n = %d must be >= 1", n);
+  if (n_vec < 1) return fail(ctx, LKV_ERR_INVALID_ARG, "n_vec = %d must be >= 1", n_vec);
+  if (!(tau > 0.0) || std::isinf(tau)) return fail(ctx, LKV_ERR_INVALID_ARG, "tau = %g must be positive and finite", tau);
+  if (n > lkv::soft_topk_max_n(x_is_f64 != 0))
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "n = %d exceeds the limit %d", n, lkv::soft_topk_max_n(x_is_f64 != 0));
+  if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, LKV_ERR_HIP, "hipSetDevice failed");
+  lkv::launch_soft_topk_backward(x, x_is_f64 != 0, n, tau, info, g, dx, dk, as_stream(stream), n_vec);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return hip_fail(ctx, e, "batched soft top-k backward launch");
+  return LKV_OK;
+}
+
 lkv_status lkv_head_budgets(lkv_ctx* ctx, const float* emb, const lkv_head_predictor* p, int32_t n_heads, double R,
                             int32_t t, double* r, int32_t* b, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;

@@ -64,6 +64,19 @@ __device__ inline double constraint_at(double v, int j, double log_s1, double lo
   return ((double)j - k) - 0.5 * exp(v + log_s1) + 0.5 * exp(log_s2 - v);
 }
 
+// In a batched launch block b works on vector b: rows of x, y and info, and its own target sum, which the paper
+// keeps strictly inside (0, n) (App. A.1, "Numerical Stability at Boundaries"); the same is enforced here by clamping.
+template <typename X>
+__device__ inline void select_vector(const X* __restrict__& x, double* __restrict__& y, double* __restrict__& info,
+                                     double& k, const double* __restrict__ k_vec, int n) {
+  if (k_vec == nullptr) return;
+  const size_t b = blockIdx.x;
+  x += b * n;
+  if (y != nullptr) y += b * n;
+  if (info != nullptr) info += 2 * b;
+  k = fmin(fmax(k_vec[b], 1e-6), (double)n - 1e-6);
+}
+
 struct StShared {
   double lambda;
   int m;
@@ -73,8 +86,9 @@ struct StShared {
 template <typename X, typename Key>
 __global__ void __launch_bounds__(kStThreads)
 soft_topk_kernel(const X* __restrict__ x, int n, int P, double k, double tau, double* __restrict__ y,
-                 double* __restrict__ info, int32_t* __restrict__ budgets, double t) {
+                 double* __restrict__ info, int32_t* __restrict__ budgets, double t, const double* __restrict__ k_vec) {
   extern __shared__ __align__(16) unsigned char smem[];
+  select_vector(x, y, info, k, k_vec, n);   // batched call: this block's vector and target
   Key* keys = reinterpret_cast<Key*>(smem);                                  // [P]
   double* pre = reinterpret_cast<double*>(smem + (size_t)P * sizeof(Key));  // [1024] prefix of log S1
   double* suf = pre + kStThreads;                                            // [1024] suffix of log S2
@@ -244,8 +258,10 @@ __device__ inline void st_block_sum(StLargeShared* sh, double (&v)[4], long long
 template <typename X>
 __global__ void __launch_bounds__(kStThreads)
 soft_topk_large_kernel(const X* __restrict__ x, int n, double k, double tau, double* __restrict__ y,
-                       double* __restrict__ info, int32_t* __restrict__ budgets, double t) {
+                       double* __restrict__ info, int32_t* __restrict__ budgets, double t,
+                       const double* __restrict__ k_vec) {
   __shared__ StLargeShared sh;
+  select_vector(x, y, info, k, k_vec, n);   // batched call: this block's vector and target
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
 
@@ -344,6 +360,14 @@ __global__ void __launch_bounds__(kStThreads)
 soft_topk_backward_kernel(const X* __restrict__ x, int n, double tau, const double* __restrict__ info,
                           const double* __restrict__ g, double* __restrict__ dx, double* __restrict__ dk) {
   __shared__ StLargeShared sh;
+  {   // one vector per block
+    const size_t b = blockIdx.x;
+    x += b * n;
+    g += b * n;
+    dx += b * n;
+    info += 2 * b;
+    if (dk != nullptr) dk += b;
+  }
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const double lambda = info[0];
@@ -419,34 +443,35 @@ hipError_t lkv_h_prepare() {
                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)soft_topk_lds(kStKeyBytes / 8, 8));
 }
 
-// y, info and budgets may each be null; y may alias x when x is fp64
+// y, info and budgets may each be null; y may alias x when x is fp64.  k_vec != nullptr: n_vec vectors of n values,
+// one block each, targets read from the device.
 void launch_soft_topk(const void* x, bool is_f64, int n, double k, double tau, double* y, double* info,
-                      int32_t* budgets, double t, hipStream_t stream) {
+                      int32_t* budgets, double t, hipStream_t stream, int n_vec, const double* k_vec) {
   if (n > soft_topk_sorted_max_n(is_f64)) {   // too long to sort in LDS: bracketing passes over the input
     if (is_f64)
-      hipLaunchKernelGGL(soft_topk_large_kernel<double>, dim3(1), dim3(kStThreads), 0, stream,
-                         static_cast<const double*>(x), n, k, tau, y, info, budgets, t);
+      hipLaunchKernelGGL(soft_topk_large_kernel<double>, dim3(n_vec), dim3(kStThreads), 0, stream,
+                         static_cast<const double*>(x), n, k, tau, y, info, budgets, t, k_vec);
     else
-      hipLaunchKernelGGL(soft_topk_large_kernel<float>, dim3(1), dim3(kStThreads), 0, stream,
-                         static_cast<const float*>(x), n, k, tau, y, info, budgets, t);
+      hipLaunchKernelGGL(soft_topk_large_kernel<float>, dim3(n_vec), dim3(kStThreads), 0, stream,
+                         static_cast<const float*>(x), n, k, tau, y, info, budgets, t, k_vec);
     return;
   }
   const int P = padded_size(n);
   if (is_f64)
-    hipLaunchKernelGGL((soft_topk_kernel<double, uint64_t>), dim3(1), dim3(kStThreads), soft_topk_lds(P, 8), stream,
-                       static_cast<const double*>(x), n, P, k, tau, y, info, budgets, t);
+    hipLaunchKernelGGL((soft_topk_kernel<double, uint64_t>), dim3(n_vec), dim3(kStThreads), soft_topk_lds(P, 8), stream,
+                       static_cast<const double*>(x), n, P, k, tau, y, info, budgets, t, k_vec);
   else
-    hipLaunchKernelGGL((soft_topk_kernel<float, uint32_t>), dim3(1), dim3(kStThreads), soft_topk_lds(P, 4), stream,
-                       static_cast<const float*>(x), n, P, k, tau, y, info, budgets, t);
+    hipLaunchKernelGGL((soft_topk_kernel<float, uint32_t>), dim3(n_vec), dim3(kStThreads), soft_topk_lds(P, 4), stream,
+                       static_cast<const float*>(x), n, P, k, tau, y, info, budgets, t, k_vec);
 }
 
 void launch_soft_topk_backward(const void* x, bool is_f64, int n, double tau, const double* info, const double* g,
-                               double* dx, double* dk, hipStream_t stream) {
+                               double* dx, double* dk, hipStream_t stream, int n_vec) {
   if (is_f64)
-    hipLaunchKernelGGL(soft_topk_backward_kernel<double>, dim3(1), dim3(kStThreads), 0, stream,
+    hipLaunchKernelGGL(soft_topk_backward_kernel<double>, dim3(n_vec), dim3(kStThreads), 0, stream,
                        static_cast<const double*>(x), n, tau, info, g, dx, dk);
   else
-    hipLaunchKernelGGL(soft_topk_backward_kernel<float>, dim3(1), dim3(kStThreads), 0, stream,
+    hipLaunchKernelGGL(soft_topk_backward_kernel<float>, dim3(n_vec), dim3(kStThreads), 0, stream,
                        static_cast<const float*>(x), n, tau, info, g, dx, dk);
 }
 

@@ -79,9 +79,9 @@ hipError_t lkv_h_prepare();
 int soft_topk_max_n(bool is_f64);
 int head_scores_max_hidden();
 void launch_soft_topk(const void* x, bool is_f64, int n, double k, double tau, double* y, double* info,
-                      int32_t* budgets, double t, hipStream_t stream);
+                      int32_t* budgets, double t, hipStream_t stream, int n_vec = 1, const double* k_vec = nullptr);
 void launch_soft_topk_backward(const void* x, bool is_f64, int n, double tau, const double* info, const double* g,
-                               double* dx, double* dk, hipStream_t stream);
+                               double* dx, double* dk, hipStream_t stream, int n_vec = 1);
 void launch_head_scores(const float* emb, const float* w1, const float* b1, const float* w2, const float* b2,
                         int n_heads, int d_e, int hidden, double* s, hipStream_t stream);
 

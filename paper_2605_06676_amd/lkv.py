@@ -23,7 +23,8 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score",
            "lkv_score_window_workspace_bytes", "lkv_score_window", "lkv_select",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
-           "lkv_soft_topk", "lkv_soft_topk_backward", "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
+           "lkv_soft_topk", "lkv_soft_topk_backward", "lkv_soft_topk_batched", "lkv_soft_topk_backward_batched",
+           "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
            "lkv_append", "lkv_decode_attn_grown", "lkv_reevict", "lkv_masked_decode_workspace_bytes",
            "lkv_masked_decode_attn", "lkv_masked_attn_forward",
            "lkv_masked_attn_backward_workspace_bytes", "lkv_masked_attn_backward")
@@ -135,6 +136,12 @@ def load_library() -> C.CDLL:
     lib.lkv_soft_topk_backward.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_double, C.c_void_p,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lkv_soft_topk_backward.restype = C.c_int
+    lib.lkv_soft_topk_batched.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_double,
+                                          C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.lkv_soft_topk_batched.restype = C.c_int
+    lib.lkv_soft_topk_backward_batched.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_double,
+                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.lkv_soft_topk_backward_batched.restype = C.c_int
     lib.lkv_head_budgets.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(_HeadPredictor), C.c_int32, C.c_double,
                                      C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lkv_head_budgets.restype = C.c_int
@@ -290,6 +297,31 @@ def lkv_soft_topk_backward(ctx: Context, x, tau: float, info, g, dx, dk=None, st
     assert dk is None or (dk.dtype == torch.float64 and dk.numel() >= 1)
     ctx._check(ctx.lib.lkv_soft_topk_backward(ctx.h, _ptr(x), 1 if x.dtype == torch.float64 else 0, int(x.numel()),
                                               float(tau), _ptr(info), _ptr(g), _ptr(dx), _ptr(dk), _stream_ptr(stream)))
+
+
+def lkv_soft_topk_batched(ctx: Context, x, k, tau: float, y, info=None, stream=None) -> None:
+    """x: GPU fp32 or fp64 [n_vec, n]; k: GPU fp64 [n_vec]; y: GPU fp64 [n_vec, n]; info: GPU fp64 [n_vec, 2] or None."""
+    import torch
+
+    assert x.dim() == 2 and x.dtype in (torch.float32, torch.float64) and x.is_contiguous()
+    assert k.dtype == torch.float64 and k.numel() == x.shape[0] and k.is_contiguous()
+    assert y.dtype == torch.float64 and y.shape == x.shape and y.is_contiguous()
+    assert info is None or (info.dtype == torch.float64 and info.numel() == 2 * x.shape[0] and info.is_contiguous())
+    ctx._check(ctx.lib.lkv_soft_topk_batched(ctx.h, _ptr(x), 1 if x.dtype == torch.float64 else 0, int(x.shape[0]),
+                                             int(x.shape[1]), _ptr(k), float(tau), _ptr(y), _ptr(info), _stream_ptr(stream)))
+
+
+def lkv_soft_topk_backward_batched(ctx: Context, x, tau: float, info, g, dx, dk=None, stream=None) -> None:
+    """x [n_vec, n] as given to the forward call; info: GPU fp64 [n_vec, 2]; g, dx: GPU fp64 [n_vec, n]; dk: GPU fp64 [n_vec] or None."""
+    import torch
+
+    assert x.dim() == 2 and x.dtype in (torch.float32, torch.float64) and x.is_contiguous()
+    assert info.dtype == torch.float64 and info.numel() == 2 * x.shape[0] and info.is_contiguous()
+    assert all(t.dtype == torch.float64 and t.shape == x.shape and t.is_contiguous() for t in (g, dx))
+    assert dk is None or (dk.dtype == torch.float64 and dk.numel() == x.shape[0] and dk.is_contiguous())
+    ctx._check(ctx.lib.lkv_soft_topk_backward_batched(ctx.h, _ptr(x), 1 if x.dtype == torch.float64 else 0, int(x.shape[0]),
+                                                      int(x.shape[1]), float(tau), _ptr(info), _ptr(g), _ptr(dx), _ptr(dk),
+                                                      _stream_ptr(stream)))
 
 
 def lkv_head_budgets(ctx: Context, emb, predictor: dict, R: float, t: int, r, b=None, stream=None) -> None:

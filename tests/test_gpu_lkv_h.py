@@ -257,6 +257,84 @@ def test_soft_topk_backward_cold_limit_and_errors(ctx):
     torch.cuda.synchronize()
 
 
+# ---- batched calls: one vector per workgroup ------------------------------------------------------
+
+@pytest.mark.parametrize("n_vec,n,dtype", [(1, 2, np.float64), (7, 333, np.float32), (16, 4096, np.float32), (3, 16385, np.float64),
+                                           (5, 40000, np.float32)])
+def test_batched_calls_equal_the_single_vector_calls(ctx, n_vec, n, dtype):
+    # every row of a batched launch must give the bits of the one-vector call on that row, forward and backward
+    rng = np.random.default_rng(n_vec * 1000 + n)
+    x = (rng.standard_normal((n_vec, n)) * rng.uniform(0.5, 3.0, size=(n_vec, 1))).astype(dtype)
+    k = rng.uniform(0.05, 0.9, size=n_vec) * n
+    g = rng.standard_normal((n_vec, n))
+    tau = 0.4
+    xt, kt, gt = torch.from_numpy(x).cuda(), torch.from_numpy(k).cuda(), torch.from_numpy(g).cuda()
+    y = torch.empty((n_vec, n), dtype=torch.float64, device="cuda")
+    info = torch.empty((n_vec, 2), dtype=torch.float64, device="cuda")
+    dx = torch.empty_like(y)
+    dk = torch.empty(n_vec, dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk_batched(ctx, xt, kt, tau, y, info)
+    lkv.lkv_soft_topk_backward_batched(ctx, xt, tau, info, gt, dx, dk)
+    torch.cuda.synchronize()
+    y1 = torch.empty(n, dtype=torch.float64, device="cuda")
+    info1 = torch.empty(2, dtype=torch.float64, device="cuda")
+    dx1 = torch.empty(n, dtype=torch.float64, device="cuda")
+    dk1 = torch.empty(1, dtype=torch.float64, device="cuda")
+    for b in range(n_vec):
+        lkv.lkv_soft_topk(ctx, xt[b], float(k[b]), tau, y1, info1)
+        lkv.lkv_soft_topk_backward(ctx, xt[b], tau, info1, gt[b], dx1, dk1)
+        torch.cuda.synchronize()
+        assert torch.equal(y[b], y1) and torch.equal(info[b], info1), f"row {b} forward"
+        assert torch.equal(dx[b], dx1) and torch.equal(dk[b:b + 1], dk1), f"row {b} backward"
+    assert np.allclose(y.sum(dim=1).cpu().numpy(), k, rtol=1e-10)
+
+
+def test_batched_soft_masks_of_a_layer_against_the_oracle(ctx):
+    # the relaxed forward's use (Sec. 3.4): one soft mask per head from noisy scores, budgets r_h t on the device
+    rng = np.random.default_rng(12)
+    H, T, tau = 8, 1500, 0.2
+    u = rng.standard_normal((H, T)).astype(np.float32)
+    r = rng.uniform(0.02, 0.6, size=H)
+    y = torch.empty((H, T), dtype=torch.float64, device="cuda")
+    info = torch.empty((H, 2), dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk_batched(ctx, torch.from_numpy(u).cuda(), torch.from_numpy(r * T).cuda(), tau, y, info)
+    g = rng.standard_normal((H, T))
+    dx = torch.empty_like(y)
+    dk = torch.empty(H, dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk_backward_batched(ctx, torch.from_numpy(u).cuda(), tau, info, torch.from_numpy(g).cuda(), dx, dk)
+    torch.cuda.synchronize()
+    for h in range(H):
+        y_ref = ST.soft_topk(u[h].astype(np.float64), float(r[h] * T), tau)
+        assert np.abs(y[h].cpu().numpy() - y_ref).max() <= Y_ATOL
+        dx_ref, dk_ref = ST.soft_topk_backward(u[h].astype(np.float64), float(r[h] * T), tau, g[h])
+        scale = float(np.abs(g[h]).max())
+        assert np.abs(dx[h].cpu().numpy() - dx_ref).max() <= 1e-8 * scale / tau
+        assert abs(float(dk[h]) - dk_ref) <= 1e-8 * scale
+
+
+def test_batched_targets_are_clamped_into_the_open_interval(ctx):
+    # targets at or beyond the ends of (0, n), and a NaN, are pulled to 1e-6 from the nearer end (App. A.1 keeps the
+    # budget strictly inside); the outputs then sum to the clamped target
+    n = 50
+    x = torch.from_numpy(np.random.default_rng(1).standard_normal((4, n))).cuda()
+    k = torch.tensor([0.0, float(n), -3.0, 2.0 * n], dtype=torch.float64, device="cuda")
+    y = torch.empty((4, n), dtype=torch.float64, device="cuda")
+    lkv.lkv_soft_topk_batched(ctx, x, k, 1.0, y)
+    torch.cuda.synchronize()
+    sums = y.sum(dim=1).cpu().numpy()
+    assert np.allclose(sums, [1e-6, n - 1e-6, 1e-6, n - 1e-6], rtol=1e-9, atol=1e-12)
+    assert torch.isfinite(y).all() and (y > 0).all() and (y < 1).all()
+    for bad_tau in (0.0, float("nan")):
+        with pytest.raises(lkv.LkvError) as e:
+            lkv.lkv_soft_topk_batched(ctx, x, k, bad_tau, y)
+        assert e.value.status == 1
+    one = torch.zeros((3, 1), dtype=torch.float64, device="cuda")
+    with pytest.raises(lkv.LkvError) as e:
+        lkv.lkv_soft_topk_batched(ctx, one, k[:3].contiguous(), 1.0, torch.empty_like(one))
+    assert e.value.status == 1
+    torch.cuda.synchronize()
+
+
 def _predictor_to_gpu(mlp):
     out = {k: torch.from_numpy(np.ascontiguousarray(mlp[k], dtype=np.float32)).cuda() for k in ("w1", "b1", "w2")}
     out["b2"] = None if mlp.get("b2") is None else torch.tensor([mlp["b2"]], dtype=torch.float32, device="cuda")

@@ -1,7 +1,7 @@
 """The relaxed forward of one layer as LKV trains it (Sec. 3.4, 3.5), composed from library calls only:
-token scores (lkv_score) -> noisy scores -> per-head soft masks m = ST_b((u + g) / tau) (lkv_soft_topk) ->
+token scores (lkv_score) -> noisy scores -> per-head soft masks m = ST_b((u + g) / tau) (lkv_soft_topk_batched) ->
 causal attention with the multiplicative mask (lkv_masked_attn_forward), its backward pass, and the backward pass of
-the Soft-TopK operator (lkv_soft_topk_backward), which turns the mask gradient into a gradient of the scores.  Checked
+the Soft-TopK operator (lkv_soft_topk_backward_batched), which turns the mask gradient into a gradient of the scores.  Checked
 against the same chain of oracle functions.  As for the hard selection, the oracle's mask is taken on the
 GPU's own fp32 scores, so that the comparison is about each step, not about score rounding shifting the
 threshold.  The Gumbel noise is an input (a seeded draw), added with a plain torch / numpy addition."""
@@ -48,8 +48,8 @@ def test_relaxed_layer_forward_and_backward(ctx, tau):
     noisy = scores[0][0] + torch.from_numpy(gumbel).cuda()
     m64 = torch.empty((H, T), dtype=torch.float64, device="cuda")
     st_info = torch.empty((H, 2), dtype=torch.float64, device="cuda")
-    for h in range(H):
-        lkv.lkv_soft_topk(ctx, noisy[h].contiguous(), float(r[h] * T), tau, m64[h], st_info[h])
+    soft_budgets = torch.from_numpy(r * T).cuda()          # fp64 [H], on the device as LKV-H would leave them
+    lkv.lkv_soft_topk_batched(ctx, noisy.contiguous(), soft_budgets, tau, m64, st_info)   # all heads in one launch
     m = m64.to(torch.float32)
     tq, tg = G.bits_to_bf16_gpu(q), G.bits_to_bf16_gpu(d_o)
     o = torch.empty((Hq, T, 128), dtype=torch.float32, device="cuda")
@@ -63,9 +63,8 @@ def test_relaxed_layer_forward_and_backward(ctx, tau):
     lkv.lkv_masked_attn_backward(ctx, tq, tk, tv, m, o, lse, tg, G.SCALE, dq, dk, dv, dm, ws)
     dm64 = dm.to(torch.float64)
     du = torch.empty((H, T), dtype=torch.float64, device="cuda")           # gradient of the noisy scores
-    d_budget = torch.empty((H, 1), dtype=torch.float64, device="cuda")     # gradient of the soft budgets r t
-    for h in range(H):
-        lkv.lkv_soft_topk_backward(ctx, noisy[h].contiguous(), tau, st_info[h], dm64[h], du[h], d_budget[h])
+    d_budget = torch.empty((H,), dtype=torch.float64, device="cuda")       # gradient of the soft budgets r t
+    lkv.lkv_soft_topk_backward_batched(ctx, noisy.contiguous(), tau, st_info, dm64.contiguous(), du, d_budget)
     torch.cuda.synchronize()
 
     # ---- oracle, step by step ----
@@ -93,4 +92,4 @@ def test_relaxed_layer_forward_and_backward(ctx, tau):
         du_ref, db_ref = ST.soft_topk_backward(noisy_host[h], float(r[h] * T), tau, dm_host[h])
         scale = max(1.0, float(np.abs(dm_host[h]).max()))
         assert np.abs(du[h].cpu().numpy() - du_ref).max() <= 1e-8 * scale / tau
-        assert abs(float(d_budget[h, 0]) - db_ref) <= 1e-8 * scale
+        assert abs(float(d_budget[h]) - db_ref) <= 1e-8 * scale
