@@ -128,7 +128,7 @@ def _sample(r, seq, n_layers_sample=2):
     return sorted(heads)
 
 
-@pytest.mark.parametrize("cid", [1, 2])
+@pytest.mark.parametrize("cid", [1, 2, 5])      # 5: the paper's own scorer shape (one 256 -> 128 -> 1 SiLU network per head)
 def test_full_size_single_sequence(cid):
     w = W.CONFIGS[cid]
     r = _run_full(w)
