@@ -393,6 +393,26 @@ def window_scorer(ctx, lkv, w, cache, scores, budgets_flat, idx, offsets, total,
         return ev[0].elapsed_time(ev[1]) / reps
 
     t_score, t_evict = timed(score), timed(evict)
+    # the same with the window rows' log-normalisers supplied, as a serving engine would have them from the prefill's
+    # attention kernel (computed here with torch, outside the timed region): the keys are then read once
+    G = w.Hq // w.H
+    lse_win = []
+    for s_i, T in enumerate(Ts):
+        lse = torch.empty((w.L, w.Hq, window), dtype=torch.float32, device=dev)
+        causal = (torch.arange(T, device=dev)[None, :] > (T - window + torch.arange(window, device=dev))[:, None])
+        for l in range(w.L):
+            kl = cache.k[s_i][l].float()                                                  # [H, T, d]
+            ql = q_win[s_i][l].float().reshape(w.H, G * window, w.d)                      # [H, G W, d]
+            logits = torch.einsum("hrd,htd->hrt", ql, kl) * scale
+            logits = logits.reshape(w.H, G, window, T).masked_fill(causal[None, None], float("-inf"))
+            lse[l] = torch.logsumexp(logits, dim=-1).reshape(w.Hq, window)
+        lse_win.append(lse)
+    del logits, kl, ql
+
+    def score_given_lse():
+        lkv.lkv_score_window(ctx, cache, q_win, window, 7, lkv.POOL_MAX, scale, scores, ws, lse_win=lse_win)
+
+    t_score_lse = timed(score_given_lse)
     N = sum(w.L * w.H * T for T in Ts)
     kept = int(budgets.sum())
     score_bytes = N * (2 * w.d + 4) + len(Ts) * w.L * w.Hq * window * w.d * 2
@@ -402,6 +422,9 @@ def window_scorer(ctx, lkv, w, cache, scores, budgets_flat, idx, offsets, total,
             "roofline": {"bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                          "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS, "traffic": None},
             "keys_read_twice_GBps": (score_bytes + N * 2 * w.d) / (t_score * 1e6),
+            "given_prefill_normalisers": {"score_ms": t_score_lse, "GBps": score_bytes / (t_score_lse * 1e6),
+                                          "frac": score_bytes / (t_score_lse * 1e6) / HBM_PEAK_GBS,
+                                          "note": "log-normalisers of the window rows passed in: one pass over the keys"},
             "evict_GBps": evict_bytes / (t_evict * 1e6),
             "note": "the two softmax passes are bound by vector and matrix issue (one exponential per logit and "
                     "pass), not by HBM"}

@@ -126,13 +126,18 @@ lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *sco
  * so that lkv_select with a budget b >= W keeps the window and the b - W prefix
  * tokens with the largest pooled votes.  bf16 inputs, fp32 accumulation and
  * fp32 softmax; each key row is read twice (once for the normalisers, once
- * for the weights); cache->v is not read and may be NULL.  Results are reproducible bit for bit
+ * for the weights), once if the caller supplies the normalisers; cache->v is not read and may be NULL.  Results are reproducible bit for bit
  * for the same call; the keys are split into blocks by the size of the whole call, so a layer
  * scored alone and the same layer scored inside a whole-cache call can differ in the last bits
  * (the order of the fp32 sums), never in more.
  * q_win     : HOST [n_seq] of DEVICE pointers, bf16 [L, Hq, W, 128]: the queries
  *             of the last W positions (as they met the keys in prefill, i.e.
  *             position-encoded like the cached keys)
+ * lse_win   : NULL, or HOST [n_seq] of DEVICE pointers, fp32 [L, Hq, W]: the natural-log normalisers
+ *             log sum_{j <= T - W + i} exp(scale * q . k_j) of the window rows, which the prefill's
+ *             attention kernel has already computed for these queries.  With them the keys are
+ *             read once instead of twice (the normaliser pass is skipped); the scores are then as
+ *             accurate as the normalisers given.
  * window    : 1 <= W <= every T_s, and (Hq / H) * W <= 128 (else LKV_ERR_UNSUPPORTED)
  * pool_width: odd, 1 .. 63 (1 = no pooling); pool_kind: lkv_pool
  * scale     : positive, finite (1 / sqrt(d) in Eq. 1)
@@ -141,9 +146,10 @@ lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *sco
  *             bytes (votes and per-block normaliser pairs, about 16 bytes per
  *             cached key row and head); contents are scratch. */
 size_t lkv_score_window_workspace_bytes(const lkv_cache *cache);
-lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *const *q_win, int32_t window,
-                            int32_t pool_width, int32_t pool_kind, float scale, float *const *scores,
-                            void *workspace, size_t workspace_bytes, void *stream);
+lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *const *q_win,
+                            const float *const *lse_win, int32_t window, int32_t pool_width, int32_t pool_kind,
+                            float scale, float *const *scores, void *workspace, size_t workspace_bytes,
+                            void *stream);
 
 /* Head-wise budgeted hard top-k (Sec. 3.4, inference: m = TopK(u, b); budgets
  * b = floor(r t) come from LKV-H, Sec. 3.3, and are an input here).

@@ -61,6 +61,22 @@ def window_attention(Qw: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
     return a
 
 
+def window_log_normalisers(Qw: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
+    """lse [Hq, W]: natural logarithm of the softmax denominators of the window rows, i.e. what a causal
+    attention kernel returns next to its output for these queries."""
+    Qw = np.asarray(Qw, dtype=np.float64)
+    K = np.asarray(K, dtype=np.float64)
+    Hq, W, _ = Qw.shape
+    H, T, _ = K.shape
+    G = Hq // H
+    lse = np.empty((Hq, W))
+    for hq in range(Hq):
+        for i in range(W):
+            s = scale * (K[hq // G, :T - W + i + 1] @ Qw[hq, i])
+            lse[hq, i] = s.max() + np.log(np.exp(s - s.max()).sum())
+    return lse
+
+
 def window_votes(Qw: np.ndarray, K: np.ndarray, scale: float) -> np.ndarray:
     """vote [H, T - W]: attention mass each prefix token receives from the window, summed over the
     window rows and averaged over the query heads of the group."""

@@ -213,9 +213,10 @@ size_t lkv_score_window_workspace_bytes(const lkv_cache* cache) {
   return need;
 }
 
-lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* const* q_win, int32_t window,
-                            int32_t pool_width, int32_t pool_kind, float scale, float* const* scores,
-                            void* workspace, size_t workspace_bytes, void* stream) {
+lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* const* q_win,
+                            const float* const* lse_win, int32_t window, int32_t pool_width, int32_t pool_kind,
+                            float scale, float* const* scores, void* workspace, size_t workspace_bytes,
+                            void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, cache, false)) return st;   // only the keys are read
   if (cache->k == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "k table is NULL");
@@ -238,6 +239,7 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
       return fail(ctx, LKV_ERR_INVALID_ARG, "q_win[%d] is NULL or not 16-byte aligned", s);
     if (scores[s] == nullptr || !aligned16(scores[s]))
       return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL or not 16-byte aligned", s);
+    if (lse_win != nullptr && lse_win[s] == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "lse_win[%d] is NULL", s);
     cells += heads * cache->seq_len[s];
   }
   if ((int64_t)G * window > lkv::score_window_max_rows())
@@ -270,6 +272,7 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
       tab.k[n] = static_cast<const uint16_t*>(cache->k[s]);
       tab.q[n] = static_cast<const uint16_t*>(q_win[s]);
       tab.scores[n] = scores[s];
+      tab.lse[n] = lse_win != nullptr ? lse_win[s] : nullptr;
       tab.votes[n] = reinterpret_cast<float*>(ws);
       ws += lkv::score_window_votes_bytes(heads, T);
       tab.partial[n] = reinterpret_cast<float*>(ws);

@@ -38,6 +38,7 @@ struct WinTable {
   float* scores[kMaxSeqPerLaunch];               // [L, H, T]
   float* votes[kMaxSeqPerLaunch];                // workspace [2, L H, T]
   float* partial[kMaxSeqPerLaunch];              // workspace [L H, blocks per head, padded rows, 2]
+  const float* lse[kMaxSeqPerLaunch];            // optional: log-normalisers of the window rows [L, Hq, W], or null
   int32_t T[kMaxSeqPerLaunch];
   int32_t first[kMaxSeqPerLaunch + 1];
   int32_t n;

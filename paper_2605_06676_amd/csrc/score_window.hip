@@ -17,7 +17,9 @@
 //           each wave of a block writing the share of its own rows;
 //   pool    adds the two shares, takes the group mean, smooths and writes the scores.
 // Keeping the logits instead would cost as many bytes as reading the keys again (G W = 128
-// logits per 128-element key).
+// logits per 128-element key).  A caller that still has the log-normalisers of the window rows
+// (the prefill's attention kernel computes them for every query) passes them in: pass 1 and the
+// merge are skipped and the keys are read once.
 //
 // Pass 1 keeps a running reference per (row, lane) instead of a running maximum: the sum is
 // taken relative to a reference that is only moved when a logit exceeds it by more than 64
@@ -116,13 +118,26 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
 
   const size_t part_row0 = ((size_t)lh * chunks) * RP;
   if (kPass == 2) {
-    // log-normaliser of every row, merged from the pairs of pass 1 by the kernel in between
-    const float* lse = tab.partial[seq] + (size_t)heads * chunks * RP * 2 + (size_t)lh * RP;
+    if (tab.lse[seq] != nullptr) {
+      // the caller's log-normalisers (natural logarithm, one per window row of the group: what the prefill's
+      // attention kernel already returns for these queries); padding rows get +inf, i.e. weight zero
+      const float* lse = tab.lse[seq] + (size_t)lh * n_rows;
 #pragma unroll
-    for (int mw = 0; mw < MTW; ++mw) {
-      const f32x4_t v = *reinterpret_cast<const f32x4_t*>(lse + 16 * (half * MTW + mw) + 4 * r);
+      for (int mw = 0; mw < MTW; ++mw)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) ref[mw][e] = v[e];
+        for (int e = 0; e < 4; ++e) {
+          const int row = 16 * (half * MTW + mw) + 4 * r + e;
+          ref[mw][e] = row < n_rows ? lse[row] * 1.44269504088896340736f : INFINITY;
+        }
+    } else {
+      // log-normaliser of every row, merged from the pairs of pass 1 by the kernel in between
+      const float* lse = tab.partial[seq] + (size_t)heads * chunks * RP * 2 + (size_t)lh * RP;
+#pragma unroll
+      for (int mw = 0; mw < MTW; ++mw) {
+        const f32x4_t v = *reinterpret_cast<const f32x4_t*>(lse + 16 * (half * MTW + mw) + 4 * r);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ref[mw][e] = v[e];
+      }
     }
   }
 
@@ -341,10 +356,12 @@ static void launch_passes(const WinTable& tab, int heads, int window, int n_rows
                           hipStream_t stream) {
   const int blocks = tab.first[tab.n];
   const size_t lds1 = 2 * kWinStepLds;   // both passes
-  hipLaunchKernelGGL((score_window_kernel<MTW, 1>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
-                     n_rows, rows_per_block, log2_scale);
-  hipLaunchKernelGGL(score_window_merge_kernel, dim3(tab.n * heads), dim3(128), 0, stream, tab, heads, n_rows,
-                     rows_per_block, 32 * MTW);
+  if (tab.lse[0] == nullptr) {   // all sequences of a call come with normalisers, or none does
+    hipLaunchKernelGGL((score_window_kernel<MTW, 1>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
+                       n_rows, rows_per_block, log2_scale);
+    hipLaunchKernelGGL(score_window_merge_kernel, dim3(tab.n * heads), dim3(128), 0, stream, tab, heads, n_rows,
+                       rows_per_block, 32 * MTW);
+  }
   hipLaunchKernelGGL((score_window_kernel<MTW, 2>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
                      n_rows, rows_per_block, log2_scale);
 }

@@ -75,8 +75,9 @@ def load_library() -> C.CDLL:
     lib.lkv_score.restype = C.c_int
     lib.lkv_score_window_workspace_bytes.argtypes = [C.POINTER(_Cache)]
     lib.lkv_score_window_workspace_bytes.restype = C.c_size_t
-    lib.lkv_score_window.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.c_int32, C.c_int32,
-                                     C.c_int32, C.c_float, C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.lkv_score_window.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32,
+                                     C.c_int32, C.c_int32, C.c_float, C.POINTER(C.c_void_p), C.c_void_p, C.c_size_t,
+                                     C.c_void_p]
     lib.lkv_score_window.restype = C.c_int
     lib.lkv_select.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.POINTER(C.c_int32),
                                C.c_void_p, C.c_void_p, C.c_void_p]
@@ -230,17 +231,22 @@ def lkv_score_window_workspace_bytes(cache: Cache) -> int:
 
 
 def lkv_score_window(ctx: Context, cache: Cache, q_win: Sequence, window: int, pool_width: int, pool_kind: int,
-                     scale: float, scores: Sequence, workspace, stream=None) -> None:
+                     scale: float, scores: Sequence, workspace, stream=None, lse_win: Optional[Sequence] = None) -> None:
     """q_win: per-sequence bf16 [L, Hq, window, 128] GPU tensors (the queries of the last `window` positions);
-    scores: per-sequence fp32 [L, H, T_s] GPU tensors, written in place."""
+    scores: per-sequence fp32 [L, H, T_s] GPU tensors, written in place; lse_win: None, or per-sequence fp32
+    [L, Hq, window] GPU tensors with the log-normalisers of those queries (then the keys are read once)."""
     import torch
 
     assert all(q.dtype == torch.bfloat16 and q.is_contiguous() for q in q_win)
     assert all(s.dtype == torch.float32 and s.is_contiguous() for s in scores)
     qp = (C.c_void_p * cache.n_seq)(*[q.data_ptr() for q in q_win])
     sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    lp = None
+    if lse_win is not None:
+        assert all(t.dtype == torch.float32 and t.is_contiguous() for t in lse_win)
+        lp = (C.c_void_p * cache.n_seq)(*[t.data_ptr() for t in lse_win])
     ws_bytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    ctx._check(ctx.lib.lkv_score_window(ctx.h, C.byref(cache.c), qp, int(window), int(pool_width), int(pool_kind),
+    ctx._check(ctx.lib.lkv_score_window(ctx.h, C.byref(cache.c), qp, lp, int(window), int(pool_width), int(pool_kind),
                                         float(scale), sp, _ptr(workspace), ws_bytes, _stream_ptr(stream)))
 
 

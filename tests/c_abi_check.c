@@ -43,7 +43,7 @@ int main(void) {
   /* every call that takes a context refuses a null one before touching the GPU */
   memset(&scorer, 0, sizeof(scorer));
   CHECK(lkv_score(NULL, &cache, &scorer, NULL, NULL) == LKV_ERR_INVALID_ARG);
-  CHECK(lkv_score_window(NULL, &cache, NULL, 32, 7, LKV_POOL_MAX, 0.1f, NULL, NULL, 0, NULL) == LKV_ERR_INVALID_ARG);
+  CHECK(lkv_score_window(NULL, &cache, NULL, NULL, 32, 7, LKV_POOL_MAX, 0.1f, NULL, NULL, 0, NULL) == LKV_ERR_INVALID_ARG);
   CHECK(lkv_select(NULL, &cache, NULL, NULL, NULL, NULL, NULL) == LKV_ERR_INVALID_ARG);
   CHECK(lkv_soft_topk_backward(NULL, NULL, 0, 1, 1.0, NULL, NULL, NULL, NULL, NULL) == LKV_ERR_INVALID_ARG);
   CHECK(strcmp(lkv_last_error(NULL), "context is NULL") == 0);

@@ -296,3 +296,49 @@ def test_layer_by_layer_eviction_with_window_scores(ctx):
     torch.cuda.synchronize()
     assert torch.equal(offsets2, offsets) and torch.equal(idx2, idx)
     assert torch.equal(kp2.view(torch.int16), kp.view(torch.int16)) and torch.equal(vp2.view(torch.int16), vp.view(torch.int16))
+
+
+@pytest.mark.parametrize("L,H,Hq,T,window,pool,kind", [(2, 2, 8, 1700, 32, 7, lkv.POOL_MAX), (1, 3, 6, 333, 20, 5, lkv.POOL_AVG),
+                                                     (1, 1, 4, 32, 32, 3, lkv.POOL_MAX)])
+def test_with_the_callers_log_normalisers(ctx, L, H, Hq, T, window, pool, kind):
+    # the prefill's attention kernel has the normalisers of the window rows already: given them, the call reads the
+    # keys once and must give the scores of the two-pass route to the rounding of the normalisers (fp32 here)
+    w = W.scaled(W.CONFIGS[0], L=L, H=H, Hq=Hq, T=T, b_min=1)
+    K, _ = W.draw_kv(w, T, 0, 21)
+    Q = W.draw_window_queries(w, K, window, 0, 21)
+    lse = np.stack([WS.window_log_normalisers(O.bf16_bits_to_f64(Q[l]), O.bf16_bits_to_f64(K[l]), G.SCALE) for l in range(L)])
+    k = G.bits_to_bf16_gpu(K)
+    cache = lkv.Cache([k], [k], Hq)
+    q = G.bits_to_bf16_gpu(Q)
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    two_pass = torch.empty((L, H, T), dtype=torch.float32, device="cuda")
+    one_pass = torch.full((L, H, T), float("nan"), dtype=torch.float32, device="cuda")
+    lkv.lkv_score_window(ctx, cache, [q], window, pool, kind, G.SCALE, [two_pass], ws)
+    ws.fill_(255)                                          # nothing of the first call may be needed
+    lkv.lkv_score_window(ctx, cache, [q], window, pool, kind, G.SCALE, [one_pass], ws,
+                         lse_win=[torch.from_numpy(lse.astype(np.float32)).cuda()])
+    torch.cuda.synchronize()
+    check_against_oracle(one_pass.cpu().numpy(), K, Q, window, pool, kind, what="with given normalisers")
+    pre = slice(0, T - window)
+    assert torch.allclose(one_pass[:, :, pre], two_pass[:, :, pre], rtol=2e-5, atol=1e-12)
+    assert torch.isposinf(one_pass[:, :, T - window:]).all()
+
+
+def test_normalisers_from_the_attention_kernel(ctx):
+    # the chain a serving engine would run: causal attention over the prompt (here lkv_masked_attn_forward with
+    # m = 1) returns the log-normaliser of every query; those of the last W queries feed the window scorer
+    Hq, H, T, window = 8, 2, 900, 32
+    q, k, v, _, _ = W.draw_training_attention(Hq, H, T, seed=31)
+    tq, tk, tv = (G.bits_to_bf16_gpu(x) for x in (q, k, v))
+    ones = torch.ones((H, T), dtype=torch.float32, device="cuda")
+    o = torch.empty((Hq, T, 128), dtype=torch.float32, device="cuda")
+    lse = torch.empty((Hq, T), dtype=torch.float32, device="cuda")
+    lkv.lkv_masked_attn_forward(ctx, tq, tk, tv, ones, G.SCALE, o, lse)
+    cache = lkv.Cache([tk[None]], [tv[None]], Hq)
+    q_win = tq[:, T - window:].contiguous()[None]                      # [1, Hq, W, 128]
+    lse_win = lse[:, T - window:].contiguous()[None]                   # [1, Hq, W]
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    s = torch.empty((1, H, T), dtype=torch.float32, device="cuda")
+    lkv.lkv_score_window(ctx, cache, [q_win], window, 7, lkv.POOL_MAX, G.SCALE, [s], ws, lse_win=[lse_win])
+    torch.cuda.synchronize()
+    check_against_oracle(s.cpu().numpy(), k[None], q[:, T - window:][None], window, 7, lkv.POOL_MAX, what="normalisers from attention")

@@ -138,3 +138,22 @@ def test_scores_keep_the_window_and_the_heaviest_prefix_tokens():
     assert np.isposinf(ws.window_scores(Qall, Kall, scale, 3, "max")).all()
     with pytest.raises(ValueError):
         ws.window_attention(Qall, Kall[:, :4], scale)
+
+
+def test_log_normalisers_against_the_library_logsumexp():
+    Qw, K, scale = _draw(8)
+    Hq, W, _ = Qw.shape
+    H, T, _ = K.shape
+    G = Hq // H
+    lse = ws.window_log_normalisers(Qw, K, scale)
+    for hq in range(Hq):
+        logits = torch.from_numpy(scale * Qw[hq] @ K[hq // G].T)                    # [W, T]
+        for i in range(W):
+            assert np.isclose(lse[hq, i], float(torch.logsumexp(logits[i, :T - W + i + 1], 0)), rtol=0, atol=1e-13)
+    # and they are the normalisers of the weights: a = exp(logit - lse)
+    a = ws.window_attention(Qw, K, scale)
+    for hq in range(Hq):
+        logits = scale * Qw[hq] @ K[hq // G].T
+        for i in range(W):
+            n = T - W + i + 1
+            assert np.allclose(a[hq, i, :n], np.exp(logits[i, :n] - lse[hq, i]), rtol=1e-12, atol=0)
