@@ -60,3 +60,22 @@ def test_header_is_plain_c_and_links_from_c(tmp_path):
                     "-L", libdir, "-llkv", "-Wl,-rpath," + libdir, "-Wl,-rpath,/opt/rocm/lib", "-o", exe], check=True)
     out = subprocess.run([exe], check=True, capture_output=True, text=True)
     assert "c abi ok" in out.stdout
+
+
+def test_missing_library_is_an_error_not_a_fallback(tmp_path):
+    # the binding has no CPU route: without the built library it raises, in a fresh interpreter so that the
+    # library already loaded by this process plays no part
+    import subprocess
+    import sys
+
+    code = ("import sys; sys.path.insert(0, %r)\n"
+            "from paper_2605_06676_amd import lkv\n"
+            "try:\n"
+            "    lkv.load_library()\n"
+            "except FileNotFoundError as e:\n"
+            "    print('raised:', e)\n"
+            "else:\n"
+            "    print('loaded')\n") % ROOT
+    env = dict(os.environ, LKV_LIBRARY=str(tmp_path / "no_such_liblkv.so"))
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, env=env, check=True).stdout
+    assert out.startswith("raised:") and "no_such_liblkv.so" in out
