@@ -94,6 +94,15 @@ lkv_status check_scorer(lkv_ctx* ctx, const lkv_scorer* s, bool mfma_widths) {
   return LKV_OK;
 }
 
+// A caller-owned workspace: present, large enough and aligned to `align` bytes (a power of two).
+lkv_status check_workspace(lkv_ctx* ctx, const void* workspace, size_t bytes, size_t need, size_t align, const char* what) {
+  if (workspace == nullptr || bytes < need)
+    return fail(ctx, LKV_ERR_WORKSPACE, "%s workspace: need %zu bytes, got %zu", what, need, bytes);
+  if ((reinterpret_cast<uintptr_t>(workspace) & (align - 1)) != 0)
+    return fail(ctx, LKV_ERR_WORKSPACE, "%s workspace is not %zu-byte aligned", what, align);
+  return LKV_OK;
+}
+
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 }  // namespace
@@ -246,10 +255,7 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
     return fail(ctx, LKV_ERR_UNSUPPORTED, "group %d x window %d exceeds %d query rows per KV head", G, window,
                 lkv::score_window_max_rows());
   const size_t need = lkv_score_window_workspace_bytes(cache);
-  if (workspace == nullptr || workspace_bytes < need)
-    return fail(ctx, LKV_ERR_WORKSPACE, "window scoring workspace: need %zu bytes, got %zu", need, workspace_bytes);
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
-    return fail(ctx, LKV_ERR_WORKSPACE, "window scoring workspace is not 256-byte aligned");
+  if (lkv_status st = check_workspace(ctx, workspace, workspace_bytes, need, 256, "window scoring")) return st;
   const int rpb = lkv::score_window_rows_per_block(cells);
   hipStream_t st = as_stream(stream);
 
@@ -416,10 +422,7 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
   if (!aligned16(q) || !aligned16(kp) || !aligned16(vp) || !aligned16(out))
     return fail(ctx, LKV_ERR_INVALID_ARG, "q, kp, vp or out is not 16-byte aligned");
   const size_t need = lkv::decode_workspace_bytes((int)n_seg, total_kept, G);
-  if (workspace == nullptr || workspace_bytes < need)
-    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
-    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace is not 256-byte aligned");
+  if (lkv_status st = check_workspace(ctx, workspace, workspace_bytes, need, 256, "decode")) return st;
   if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, nullptr, (int)n_seg, total_kept, scale, out, lse,
                                         static_cast<float*>(workspace), as_stream(stream)))
     return hip_fail(ctx, e, "lkv_decode_attn launch");
@@ -625,10 +628,7 @@ lkv_status lkv_decode_attn_grown(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, 
   if (!aligned16(q) || !aligned16(kp) || !aligned16(vp) || !aligned16(out))
     return fail(ctx, LKV_ERR_INVALID_ARG, "q, kp, vp or out is not 16-byte aligned");
   const size_t need = lkv::decode_workspace_bytes((int)n_seg, total_rows, G);
-  if (workspace == nullptr || workspace_bytes < need)
-    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
-    return fail(ctx, LKV_ERR_WORKSPACE, "decode workspace is not 256-byte aligned");
+  if (lkv_status st = check_workspace(ctx, workspace, workspace_bytes, need, 256, "decode")) return st;
   if (hipError_t e = lkv::launch_decode(G, q, kp, vp, cap_offsets, lengths, (int)n_seg, total_rows, scale, out, lse,
                                         static_cast<float*>(workspace), as_stream(stream)))
     return hip_fail(ctx, e, "lkv_decode_attn_grown launch");
@@ -714,10 +714,7 @@ lkv_status lkv_masked_decode_attn(lkv_ctx* ctx, const lkv_cache* cache, const vo
       return fail(ctx, LKV_ERR_UNSUPPORTED, "sequence %d has 2^31 or more cache rows", s);
   }
   const size_t need = lkv_masked_decode_workspace_bytes(cache);
-  if (workspace == nullptr || workspace_bytes < need)
-    return fail(ctx, LKV_ERR_WORKSPACE, "masked decode workspace: need %zu bytes, got %zu", need, workspace_bytes);
-  if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0)
-    return fail(ctx, LKV_ERR_WORKSPACE, "masked decode workspace is not 256-byte aligned");
+  if (lkv_status st = check_workspace(ctx, workspace, workspace_bytes, need, 256, "masked decode")) return st;
   const size_t off_bytes = (((size_t)heads + 1) * sizeof(int32_t) + 255) / 256 * 256;
   int32_t* offsets = static_cast<int32_t*>(workspace);
   float* ws = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + off_bytes);
@@ -784,9 +781,7 @@ lkv_status lkv_masked_attn_backward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_k
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o) || !aligned16(d_o))
     return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v, o or d_o is not 16-byte aligned");
   const size_t need = lkv::masked_attn_bwd_workspace_bytes(n_q_heads, n_kv_heads, seq_len);
-  if (workspace == nullptr || workspace_bytes < need)
-    return fail(ctx, LKV_ERR_WORKSPACE, "masked attention backward workspace: need %zu bytes, got %zu", need, workspace_bytes);
-  if (!aligned16(workspace)) return fail(ctx, LKV_ERR_WORKSPACE, "masked attention backward workspace is not 16-byte aligned");
+  if (lkv_status st = check_workspace(ctx, workspace, workspace_bytes, need, 16, "masked attention backward")) return st;
   lkv::launch_masked_attn_bwd(q, k, v, m, o, lse, d_o, n_q_heads, n_kv_heads, seq_len, scale, dq, dk, dv, dm,
                               static_cast<float*>(workspace), as_stream(stream));
   if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_masked_attn_backward launch");
