@@ -103,6 +103,35 @@ lkv_status check_workspace(lkv_ctx* ctx, const void* workspace, size_t bytes, si
   return LKV_OK;
 }
 
+// Geometry of a decode call over a packed cache: counts, the GQA group and the number of segments.
+lkv_status check_decode_geometry(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads, int32_t n_q_heads,
+                                 int32_t head_dim, int* group, int64_t* n_segments) {
+  if (n_seq < 1 || n_layers < 1 || n_kv_heads < 1 || n_q_heads < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers, n_kv_heads and n_q_heads must be >= 1");
+  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  *group = n_q_heads / n_kv_heads;
+  if (*group > lkv::kDecodeMaxGroup)
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", *group, lkv::kDecodeMaxGroup);
+  *n_segments = (int64_t)n_seq * n_layers * n_kv_heads;
+  if (*n_segments > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  return LKV_OK;
+}
+
+// Geometry and scale of the training-time attention calls (one layer of one sequence).
+lkv_status check_attention_geometry(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv_heads, int32_t seq_len, int32_t head_dim,
+                                    float scale) {
+  if (n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
+  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
+  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
+  if (seq_len >= 1 << 24) return fail(ctx, LKV_ERR_UNSUPPORTED, "seq_len = %d must be below 2^24", seq_len);
+  if (((int64_t)seq_len + 127) / 128 * n_q_heads >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
+  if (!(scale > 0.f) || std::isinf(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale = %g must be positive and finite", (double)scale);
+  return LKV_OK;
+}
+
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 }  // namespace
@@ -407,14 +436,9 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
                            int64_t total_kept, float scale, float* out, float* lse, void* workspace,
                            size_t workspace_bytes, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
-  if (n_seq < 1 || n_layers < 1 || n_kv_heads < 1 || n_q_heads < 1)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers, n_kv_heads and n_q_heads must be >= 1");
-  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
-  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
-  const int G = n_q_heads / n_kv_heads;
-  if (G > lkv::kDecodeMaxGroup) return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", G, lkv::kDecodeMaxGroup);
-  const int64_t n_seg = (int64_t)n_seq * n_layers * n_kv_heads;
-  if (n_seg > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  int G = 0;
+  int64_t n_seg = 0;
+  if (lkv_status st = check_decode_geometry(ctx, n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, &G, &n_seg)) return st;
   if (total_kept < 0 || total_kept >= (int64_t)1 << 31)
     return fail(ctx, LKV_ERR_INVALID_ARG, "total_kept = %lld is outside [0, 2^31)", (long long)total_kept);
   if (q == nullptr || offsets == nullptr || out == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q, offsets or out is NULL");
@@ -612,14 +636,9 @@ lkv_status lkv_decode_attn_grown(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, 
                                  const int32_t* cap_offsets, const int32_t* lengths, int64_t total_rows, float scale,
                                  float* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
-  if (n_seq < 1 || n_layers < 1 || n_kv_heads < 1 || n_q_heads < 1)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "n_seq, n_layers, n_kv_heads and n_q_heads must be >= 1");
-  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
-  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
-  const int G = n_q_heads / n_kv_heads;
-  if (G > lkv::kDecodeMaxGroup) return fail(ctx, LKV_ERR_UNSUPPORTED, "GQA group %d exceeds %d", G, lkv::kDecodeMaxGroup);
-  const int64_t n_seg = (int64_t)n_seq * n_layers * n_kv_heads;
-  if (n_seg > kMaxSegments) return fail(ctx, LKV_ERR_UNSUPPORTED, "too many segments");
+  int G = 0;
+  int64_t n_seg = 0;
+  if (lkv_status st = check_decode_geometry(ctx, n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, &G, &n_seg)) return st;
   if (total_rows < 0 || total_rows >= (int64_t)1 << 31)
     return fail(ctx, LKV_ERR_INVALID_ARG, "total_rows = %lld is outside [0, 2^31)", (long long)total_rows);
   if (q == nullptr || cap_offsets == nullptr || lengths == nullptr || out == nullptr)
@@ -738,14 +757,7 @@ lkv_status lkv_masked_attn_forward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_kv
                                    int32_t head_dim, const void* q, const void* k, const void* v, const float* m,
                                    float scale, float* o, float* lse, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
-  if (n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
-  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
-  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
-  if (seq_len >= 1 << 24) return fail(ctx, LKV_ERR_UNSUPPORTED, "seq_len = %d must be below 2^24", seq_len);
-  if (((int64_t)seq_len + 127) / 128 * n_q_heads >= (int64_t)1 << 31)
-    return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
-  if (!(scale > 0.f) || std::isinf(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale = %g must be positive and finite", (double)scale);
+  if (lkv_status st = check_attention_geometry(ctx, n_q_heads, n_kv_heads, seq_len, head_dim, scale)) return st;
   if (q == nullptr || k == nullptr || v == nullptr || m == nullptr || o == nullptr || lse == nullptr)
     return fail(ctx, LKV_ERR_INVALID_ARG, "q, k, v, m, o or lse is NULL");
   if (!aligned16(q) || !aligned16(k) || !aligned16(v) || !aligned16(o))
@@ -765,16 +777,9 @@ lkv_status lkv_masked_attn_backward(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_k
                                     const float* o, const float* lse, const void* d_o, float scale, float* dq, float* dk,
                                     float* dv, float* dm, void* workspace, size_t workspace_bytes, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
-  if (n_q_heads < 1 || n_kv_heads < 1 || seq_len < 1)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads, n_kv_heads and seq_len must be >= 1");
-  if (n_q_heads % n_kv_heads != 0) return fail(ctx, LKV_ERR_INVALID_ARG, "n_q_heads is not a multiple of n_kv_heads");
-  if (head_dim != lkv::kHeadDim) return fail(ctx, LKV_ERR_UNSUPPORTED, "head_dim must be 128, got %d", head_dim);
-  if (seq_len >= 1 << 24) return fail(ctx, LKV_ERR_UNSUPPORTED, "seq_len = %d must be below 2^24", seq_len);
-  if (((int64_t)seq_len + 127) / 128 * n_q_heads >= (int64_t)1 << 31)
-    return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
+  if (lkv_status st = check_attention_geometry(ctx, n_q_heads, n_kv_heads, seq_len, head_dim, scale)) return st;
   if ((int64_t)n_q_heads * seq_len >= ((int64_t)1 << 31) * 16)
     return fail(ctx, LKV_ERR_UNSUPPORTED, "n_q_heads * seq_len is too large for one launch");
-  if (!(scale > 0.f) || std::isinf(scale)) return fail(ctx, LKV_ERR_INVALID_ARG, "scale = %g must be positive and finite", (double)scale);
   if (q == nullptr || k == nullptr || v == nullptr || m == nullptr || o == nullptr || lse == nullptr || d_o == nullptr ||
       dq == nullptr || dk == nullptr || dv == nullptr || dm == nullptr)
     return fail(ctx, LKV_ERR_INVALID_ARG, "an input or output pointer is NULL");
