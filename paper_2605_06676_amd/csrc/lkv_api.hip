@@ -228,8 +228,7 @@ lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* sco
     tab.first[n] = (int32_t)blocks;
     tab.n = n;
     if (scorer->kind == LKV_SCORER_LINEAR) {
-      lkv::launch_score_linear(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, (int)heads,
-                               heads_per_row, st);
+      lkv::launch_score_linear(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, heads_per_row, st);
     } else {
       lkv::launch_score_mlp(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, scorer->w2, scorer->b2,
                             scorer->hidden, scorer->act == LKV_ACT_SILU ? 0 : 1, heads_per_row, rpb0, st);

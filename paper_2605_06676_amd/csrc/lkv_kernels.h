@@ -6,8 +6,8 @@
 namespace lkv {
 
 // score_linear.hip
-void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b1, int n_heads,
-                         int heads_per_scorer_row, hipStream_t stream);
+void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b1, int heads_per_scorer_row,
+                         hipStream_t stream);
 int score_linear_blocks_per_head(int T);
 
 // score_mlp.hip

@@ -19,7 +19,7 @@ constexpr int kScoreUnroll = 4;   // row groups whose loads are in flight togeth
 
 __global__ void __launch_bounds__(kScoreBlockThreads)
 score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
-                    int n_heads, int heads_per_scorer_row /* H if per-layer scorer, 1 if per-head */) {
+                    int heads_per_scorer_row /* H if per-layer scorer, 1 if per-head */) {
   const int seq = seq_of_unit(tab, blockIdx.x);
   const int local = blockIdx.x - tab.first[seq];
   const int T = tab.T[seq];
@@ -77,12 +77,12 @@ score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* 
   if (out_row < T) tab.scores[seq][head_row0 + out_row] = mine + bias;
 }
 
-void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b1, int n_heads,
-                         int heads_per_scorer_row, hipStream_t stream) {
+void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b1, int heads_per_scorer_row,
+                         hipStream_t stream) {
   const int blocks = tab.first[tab.n];
   if (blocks <= 0) return;
   hipLaunchKernelGGL(score_linear_kernel, dim3(blocks), dim3(kScoreBlockThreads), 0, stream, tab, w1,
-                     b1, n_heads, heads_per_scorer_row);
+                     b1, heads_per_scorer_row);
 }
 
 int score_linear_blocks_per_head(int T) { return (T + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock; }
