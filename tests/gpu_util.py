@@ -8,7 +8,6 @@ import torch
 
 from oracle import lkv_oracle as O
 from paper_2605_06676_amd import lkv
-from paper_2605_06676_amd import workloads as W
 
 SCALE = 1.0 / math.sqrt(128.0)
 

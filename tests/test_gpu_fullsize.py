@@ -9,7 +9,6 @@ the packed rows must match bit for bit (selection on the GPU's own scores), and 
 output of its query heads must match to the stated tolerance.  Properties that hold at any
 size are checked over the whole output: offsets, index ranges and order, finite outputs.
 """
-import math
 
 import numpy as np
 import pytest

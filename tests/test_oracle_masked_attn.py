@@ -5,7 +5,6 @@ attention routine, automatic differentiation of the log-space formulation the pa
 equivalent, finite differences, or an identity that follows from the formula.
 """
 import numpy as np
-import pytest
 import torch
 
 from oracle import masked_attn as ma
