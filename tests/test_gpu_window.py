@@ -342,3 +342,39 @@ def test_normalisers_from_the_attention_kernel(ctx):
     lkv.lkv_score_window(ctx, cache, [q_win], window, 7, lkv.POOL_MAX, G.SCALE, [s], ws, lse_win=[lse_win])
     torch.cuda.synchronize()
     check_against_oracle(s.cpu().numpy(), k[None], q[:, T - window:][None], window, 7, lkv.POOL_MAX, what="normalisers from attention")
+
+
+def test_long_context_sampled_heads(ctx):
+    # 131072 tokens per head (the length of the second benchmark workload; four layers of it), 128 blocks per head
+    # and pass: two heads against the oracle, with and without the caller's normalisers
+    w = W.scaled(W.CONFIGS[2], L=4)
+    T, window = 131072, 32
+    k, _ = W.device_kv(w, T, 0, "cuda")
+    cache = lkv.Cache([k], [k], w.Hq)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(14)
+    q = torch.randn((w.L, w.Hq, window, w.d), device="cuda", generator=gen)
+    grp = w.Hq // w.H
+    q[1, 5, 7] += 0.5 * k[1, 5 // grp, 100000].float()
+    q[3, 30, 31] += 0.5 * k[3, 30 // grp, 7].float()
+    q = q.to(torch.bfloat16).contiguous()
+    ws = torch.empty(lkv.lkv_score_window_workspace_bytes(cache), dtype=torch.uint8, device="cuda")
+    s = torch.empty((w.L, w.H, T), dtype=torch.float32, device="cuda")
+    lkv.lkv_score_window(ctx, cache, [q], window, 7, lkv.POOL_AVG, G.SCALE, [s], ws)
+    torch.cuda.synchronize()
+    assert torch.isposinf(s[:, :, T - window:]).all() and torch.isfinite(s[:, :, :T - window]).all()
+    lse = torch.zeros((w.L, w.Hq, window), dtype=torch.float32, device="cuda")
+    picks = ((1, 5 // grp), (3, 30 // grp))
+    for l, h in picks:
+        Kb = G.bf16_gpu_to_bits(k[l, h])[None, None]
+        Qb = G.bf16_gpu_to_bits(q[l, h * grp:(h + 1) * grp])[None]
+        check_against_oracle(s[l, h][None, None].cpu().numpy(), Kb, Qb, window, 7, lkv.POOL_AVG, what=f"layer {l} head {h}")
+        ref_lse = WS.window_log_normalisers(O.bf16_bits_to_f64(Qb[0]), O.bf16_bits_to_f64(Kb[0]), G.SCALE)
+        lse[l, h * grp:(h + 1) * grp] = torch.from_numpy(ref_lse.astype(np.float32)).cuda()
+    one = torch.empty_like(s)
+    lkv.lkv_score_window(ctx, cache, [q], window, 7, lkv.POOL_AVG, G.SCALE, [one], ws, lse_win=[lse])
+    torch.cuda.synchronize()
+    for l, h in picks:      # only these heads were given true normalisers
+        Kb = G.bf16_gpu_to_bits(k[l, h])[None, None]
+        Qb = G.bf16_gpu_to_bits(q[l, h * grp:(h + 1) * grp])[None]
+        check_against_oracle(one[l, h][None, None].cpu().numpy(), Kb, Qb, window, 7, lkv.POOL_AVG, what=f"layer {l} head {h}, given normalisers")
