@@ -20,7 +20,17 @@
  * Streams.  `stream` is a hipStream_t passed as void* (NULL = the default
  *           stream).  The hot calls only enqueue work on it; they do not
  *           synchronise the host with the device and results are valid once the
- *           caller has synchronised the stream.
+ *           caller has synchronised the stream.  Calls that only enqueue kernels
+ *           can be recorded into a HIP graph.  The one exception is an upload
+ *           of segment offsets computed from HOST budgets: lkv_plan_offsets,
+ *           lkv_reevict, and lkv_select when it is given host budgets for 640
+ *           or more segments (fewer travel in the kernel arguments).  Such an
+ *           upload goes through a ring of 8 pinned buffers owned by the
+ *           context, may wait on the host until the ring slot's previous
+ *           upload has finished, and is refused with LKV_ERR_UNSUPPORTED while
+ *           `stream` is capturing (a replay would copy whatever a later call
+ *           left in the slot).  To stay free of both, call lkv_plan_offsets
+ *           once, outside any capture, and pass budgets = NULL to lkv_select.
  * Layout.   Cache tensors are bf16, row-major [n_layers, n_kv_heads, T, 128]
  *           per sequence.  A "segment" is one (sequence, layer, kv head); the
  *           segments are numbered s = (seq * n_layers + layer) * n_kv_heads +
@@ -161,9 +171,15 @@ lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *co
  *   idx[offsets[s] + j]     = j-th kept token of segment s, ascending.
  * The result is unique, hence reproducible bit for bit.
  * scores  : HOST [n_seq] of DEVICE pointers, fp32 [L, H, T_s] (as written by lkv_score)
- * budgets : HOST int32 [n_seq * L * H], 0 <= budgets[s] <= T_seq(s); sum < 2^31
+ * budgets : HOST int32 [n_seq * L * H], 0 <= budgets[s] <= T_seq(s); sum < 2^31.
+ *           Or NULL: `offsets` already holds the prefix sums that lkv_plan_offsets
+ *           wrote for the budgets (budgets are static, Sec. 3.3, so this is done once);
+ *           it is then an input, nothing is copied and the host never waits, whatever
+ *           the number of segments.  The budgets cannot be checked in that case: a
+ *           planned budget above T_seq(s) keeps all T_seq(s) tokens and leaves the rest
+ *           of that segment's idx range unwritten.
  * idx     : DEVICE int32 [sum of budgets]
- * offsets : DEVICE int32 [n_seq * L * H + 1] */
+ * offsets : DEVICE int32 [n_seq * L * H + 1]; written, or read when budgets is NULL */
 lkv_status lkv_select(lkv_ctx *ctx, const lkv_cache *cache, const float *const *scores,
                       const int32_t *budgets, int32_t *idx, int32_t *offsets, void *stream);
 

@@ -43,10 +43,19 @@ template <int kMode>
 __global__ void __launch_bounds__(kCompactThreads)
 compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __restrict__ offsets,
                int n_segments, int heads_per_seq, int seq_lo, int head_lo, int n_heads_view, int64_t row_lo,
-               int64_t row_hi, uint4* __restrict__ kp, uint4* __restrict__ vp, CompactGrow grow) {
+               int64_t row_hi, int rows_of_own_sequences, uint4* __restrict__ kp, uint4* __restrict__ vp,
+               CompactGrow grow) {
   // packed rows [row_lo, row_hi) are this launch's; the source tensors hold heads head_lo .. of each
   // sequence (all of them for a whole cache, one layer's for a layer view)
+  if (rows_of_own_sequences) {
+    // one of several launches over a cache of many sequences: the rows of the sequences this launch
+    // describes are one contiguous range, read from the table (the host does not know the budgets
+    // here); the grid was sized for all rows and the blocks past the range leave at once
+    row_lo = offsets[min(seq_lo * heads_per_seq, n_segments)];
+    row_hi = offsets[min((seq_lo + tab.n) * heads_per_seq, n_segments)];
+  }
   const int64_t p0 = row_lo + (int64_t)blockIdx.x * kCompactRowsPerBlock;
+  if (p0 >= row_hi) return;
   // the segment that contains row p0: the last one with offsets[s] <= p0
   const int s0 = wave_upper_segment(offsets, n_segments, p0, threadIdx.x & 63);
 
@@ -107,20 +116,20 @@ compact_kernel(SeqTable tab, const int32_t* __restrict__ idx, const int32_t* __r
 
 void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
                     int heads_per_seq, int seq_lo, int head_lo, int n_heads_view, int64_t row_lo, int64_t row_hi,
-                    void* kp, void* vp, hipStream_t stream) {
+                    void* kp, void* vp, hipStream_t stream, bool rows_of_own_sequences) {
   if (row_hi <= row_lo) return;
   const int blocks = (int)((row_hi - row_lo + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock);
   CompactGrow none = {};
   hipLaunchKernelGGL(compact_kernel<kCompactPlain>, dim3(blocks), dim3(kCompactThreads), 0, stream, tab, idx,
                      offsets, n_segments, heads_per_seq, seq_lo, head_lo, n_heads_view, row_lo, row_hi,
-                     reinterpret_cast<uint4*>(kp), reinterpret_cast<uint4*>(vp), none);
+                     rows_of_own_sequences ? 1 : 0, reinterpret_cast<uint4*>(kp), reinterpret_cast<uint4*>(vp), none);
 }
 
 // Compaction into a cache with `slack` spare rows behind every segment, from the prefilled cache
 // (tab.scores holds the scores the selection used).
 void launch_compact_grow(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
                          int heads_per_seq, int seq_lo, int64_t total_kept, int slack, void* kp, void* vp, float* up,
-                         hipStream_t stream) {
+                         hipStream_t stream, bool rows_of_own_sequences) {
   if (total_kept <= 0) return;
   const int blocks = (int)((total_kept + kCompactRowsPerBlock - 1) / kCompactRowsPerBlock);
   CompactGrow g = {};
@@ -128,7 +137,7 @@ void launch_compact_grow(const SeqTable& tab, const int32_t* idx, const int32_t*
   g.up = up;
   hipLaunchKernelGGL(compact_kernel<kCompactGrowCache>, dim3(blocks), dim3(kCompactThreads), 0, stream, tab, idx,
                      offsets, n_segments, heads_per_seq, seq_lo, 0, heads_per_seq, (int64_t)0, total_kept,
-                     reinterpret_cast<uint4*>(kp), reinterpret_cast<uint4*>(vp), g);
+                     rows_of_own_sequences ? 1 : 0, reinterpret_cast<uint4*>(kp), reinterpret_cast<uint4*>(vp), g);
 }
 
 // The same from an older packed cache with slack: idx[p] is a row position inside the old segment.
@@ -142,7 +151,7 @@ void launch_compact_regrow(const int32_t* idx, const int32_t* offsets, int n_seg
   CompactGrow g = {slack, up, reinterpret_cast<const uint4*>(kp_old), reinterpret_cast<const uint4*>(vp_old), up_old,
                    cap_old, len_old};
   hipLaunchKernelGGL(compact_kernel<kCompactGrowPacked>, dim3(blocks), dim3(kCompactThreads), 0, stream, tab, idx,
-                     offsets, n_segments, 1, 0, 0, 1, (int64_t)0, total_kept, reinterpret_cast<uint4*>(kp),
+                     offsets, n_segments, 1, 0, 0, 1, (int64_t)0, total_kept, 0, reinterpret_cast<uint4*>(kp),
                      reinterpret_cast<uint4*>(vp), g);
 }
 

@@ -46,12 +46,8 @@ constexpr int kDecMaxGroup = 16;
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-#ifndef LKV_DEC_TARGET_BLOCKS
-#define LKV_DEC_TARGET_BLOCKS 512
-#endif
-#ifndef LKV_DEC_MIN_CHUNK
-#define LKV_DEC_MIN_CHUNK 128
-#endif
+constexpr int kDecTargetBlocks = 512;        // chunks per launch: one round of resident blocks (2 per compute unit)
+constexpr int kDecMinChunk = 128;            // rows; shorter chunks only add partials to merge
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -318,11 +314,11 @@ decode_merge_kernel(const int32_t* __restrict__ offsets, const int32_t* __restri
   if (ch == 0 && lse != nullptr) lse[row] = den > 0.f ? mx * kLn2 + __logf(den) : -INFINITY;
 }
 
-// Rows per block: a multiple of the wave tile, sized for LKV_DEC_TARGET_BLOCKS blocks.
+// Rows per block: a multiple of the wave tile, sized for kDecTargetBlocks blocks.
 int decode_chunk_rows(int64_t total_kept) {
-  int64_t c = (total_kept + LKV_DEC_TARGET_BLOCKS - 1) / LKV_DEC_TARGET_BLOCKS;
+  int64_t c = (total_kept + kDecTargetBlocks - 1) / kDecTargetBlocks;
   c = (c + kDecTile - 1) / kDecTile * kDecTile;
-  if (c < LKV_DEC_MIN_CHUNK) c = LKV_DEC_MIN_CHUNK;
+  if (c < kDecMinChunk) c = kDecMinChunk;
   return (int)c;
 }
 

@@ -326,57 +326,86 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
   return LKV_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+// A pinned staging slot for an offsets upload on `st`.  The upload path cannot be recorded into a HIP
+// graph (a replay would copy whatever a later call has left in the slot) and may wait on the host for
+// the slot's previous upload, so it is refused while `st` is capturing.
+lkv_status take_stage_slot(lkv_ctx* ctx, hipStream_t st, const char* who, int* slot_out) {
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipError_t e = hipStreamIsCapturing(st, &cap)) return hip_fail(ctx, e, "capture status query");
+  if (cap != hipStreamCaptureStatusNone)
+    return fail(ctx, LKV_ERR_UNSUPPORTED,
+                "%s would upload offsets from host memory, which cannot be captured into a HIP graph: call "
+                "lkv_plan_offsets before the capture and pass budgets = NULL inside it", who);
+  const int slot = ctx->stage_next;
+  ctx->stage_next = (slot + 1) % kStageSlots;
+  if (ctx->stage_used[slot]) {
+    if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
+  }
+  *slot_out = slot;
+  return LKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
 lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
                       int32_t* idx, int32_t* offsets, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, cache, false)) return st;
-  if (scores == nullptr || budgets == nullptr || offsets == nullptr)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "scores, budgets or offsets is NULL");
+  if (scores == nullptr || offsets == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores or offsets is NULL");
   const int heads = cache->n_layers * cache->n_kv_heads;
   const int64_t n_seg = (int64_t)heads * cache->n_seq;
   if ((size_t)(n_seg + 1) * sizeof(int32_t) > kStageBytes)
     return fail(ctx, LKV_ERR_UNSUPPORTED, "%lld segments exceed the staging capacity", (long long)n_seg);
-  int64_t total = 0;
-  for (int s = 0; s < cache->n_seq; ++s) {
+  for (int s = 0; s < cache->n_seq; ++s)
     if (scores[s] == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL", s);
-    const int T = cache->seq_len[s];
-    for (int h = 0; h < heads; ++h) {
-      const int32_t b = budgets[(size_t)s * heads + h];
-      if (b < 0 || b > T)
-        return fail(ctx, LKV_ERR_INVALID_ARG, "budget %d of segment %lld is outside [0, %d]", b,
-                    (long long)s * heads + h, T);
-      total += b;
-    }
-  }
-  if (total >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "sum of budgets %lld >= 2^31", (long long)total);
-  if (total > 0 && idx == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "idx is NULL");
   hipStream_t st = as_stream(stream);
 
-  // offsets: computed on the host (budgets are host data).  Few segments: they ride in the kernel
-  // arguments and the kernel publishes them.  Many: uploaded through a pinned slot of the ring.
-  const bool inline_offsets = n_seg < lkv::select_inline_capacity() && cache->n_seq <= lkv::kMaxSeqPerLaunch;
+  // Offsets.  budgets == NULL: the device array already holds them (lkv_plan_offsets), nothing is
+  // computed or copied here.  Otherwise they are computed on the host; few segments ride in the kernel
+  // arguments and the kernel publishes them, many are uploaded through a pinned slot of the ring.
+  const bool planned = budgets == nullptr;
+  const bool inline_offsets = !planned && n_seg < lkv::select_inline_capacity() && cache->n_seq <= lkv::kMaxSeqPerLaunch;
   int32_t inline_buf[1024];
   int32_t* host_off = inline_buf;
-  int slot = -1;
-  if (!inline_offsets) {
-    slot = ctx->stage_next;
-    ctx->stage_next = (slot + 1) % kStageSlots;
-    if (ctx->stage_used[slot]) {
-      if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
+  if (planned) {
+    if (idx == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "idx is NULL");
+  } else {
+    int64_t total = 0;
+    for (int s = 0; s < cache->n_seq; ++s) {
+      const int T = cache->seq_len[s];
+      for (int h = 0; h < heads; ++h) {
+        const int32_t b = budgets[(size_t)s * heads + h];
+        if (b < 0 || b > T)
+          return fail(ctx, LKV_ERR_INVALID_ARG, "budget %d of segment %lld is outside [0, %d]", b,
+                      (long long)s * heads + h, T);
+        total += b;
+      }
     }
-    host_off = static_cast<int32_t*>(ctx->stage[slot]);
-  }
-  int32_t run = 0;
-  for (int64_t i = 0; i < n_seg; ++i) {
-    host_off[i] = run;
-    run += budgets[i];
-  }
-  host_off[n_seg] = run;
-  if (!inline_offsets) {
-    if (hipError_t e = hipMemcpyAsync(offsets, host_off, (size_t)(n_seg + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st))
-      return hip_fail(ctx, e, "offsets upload");
-    if (hipError_t e = hipEventRecord(ctx->stage_done[slot], st)) return hip_fail(ctx, e, "staging event");
-    ctx->stage_used[slot] = true;
+    if (total >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "sum of budgets %lld >= 2^31", (long long)total);
+    if (total > 0 && idx == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "idx is NULL");
+    int slot = -1;
+    if (!inline_offsets) {
+      if (lkv_status e = take_stage_slot(ctx, st, "lkv_select with host budgets for 640 or more segments", &slot)) return e;
+      host_off = static_cast<int32_t*>(ctx->stage[slot]);
+    }
+    int32_t run = 0;
+    for (int64_t i = 0; i < n_seg; ++i) {
+      host_off[i] = run;
+      run += budgets[i];
+    }
+    host_off[n_seg] = run;
+    if (!inline_offsets) {
+      if (hipError_t e = hipMemcpyAsync(offsets, host_off, (size_t)(n_seg + 1) * sizeof(int32_t), hipMemcpyHostToDevice, st))
+        return hip_fail(ctx, e, "offsets upload");
+      if (hipError_t e = hipEventRecord(ctx->stage_done[slot], st)) return hip_fail(ctx, e, "staging event");
+      ctx->stage_used[slot] = true;
+    }
   }
 
   for (int s0 = 0; s0 < cache->n_seq; s0 += lkv::kMaxSeqPerLaunch) {
@@ -419,7 +448,8 @@ lkv_status lkv_compact(lkv_ctx* ctx, const lkv_cache* cache, const int32_t* idx,
       tab.T[i] = cache->seq_len[s0 + i];
     }
     tab.n = n;
-    lkv::launch_compact(tab, idx, offsets, n_seg, heads, s0, 0, heads, 0, total_kept, kp, vp, st);
+    lkv::launch_compact(tab, idx, offsets, n_seg, heads, s0, 0, heads, 0, total_kept, kp, vp, st,
+                        cache->n_seq > lkv::kMaxSeqPerLaunch);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_compact launch");
   }
   return LKV_OK;
@@ -465,11 +495,8 @@ lkv_status lkv_plan_offsets(lkv_ctx* ctx, int64_t n_segments, const int32_t* bud
   }
   if (total >= (int64_t)1 << 31) return fail(ctx, LKV_ERR_UNSUPPORTED, "sum of budgets %lld >= 2^31", (long long)total);
   hipStream_t st = as_stream(stream);
-  const int slot = ctx->stage_next;
-  ctx->stage_next = (slot + 1) % kStageSlots;
-  if (ctx->stage_used[slot]) {
-    if (hipError_t e = hipEventSynchronize(ctx->stage_done[slot])) return hip_fail(ctx, e, "staging slot wait");
-  }
+  int slot = -1;
+  if (lkv_status e = take_stage_slot(ctx, st, "lkv_plan_offsets", &slot)) return e;
   int32_t* host_off = static_cast<int32_t*>(ctx->stage[slot]);
   int32_t run = 0;
   for (int64_t i = 0; i < n_segments; ++i) {
@@ -602,7 +629,8 @@ lkv_status lkv_compact_grow(lkv_ctx* ctx, const lkv_cache* cache, const float* c
       tab.T[i] = cache->seq_len[s0 + i];
     }
     tab.n = n;
-    lkv::launch_compact_grow(tab, idx, offsets, (int)n_seg, heads, s0, total_kept, slack, kp, vp, up, st);
+    lkv::launch_compact_grow(tab, idx, offsets, (int)n_seg, heads, s0, total_kept, slack, kp, vp, up, st,
+                             cache->n_seq > lkv::kMaxSeqPerLaunch);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_compact_grow launch");
   }
   return LKV_OK;

@@ -67,7 +67,7 @@ __device__ inline double constraint_at(double v, int j, double log_s1, double lo
 // In a batched launch block b works on vector b: rows of x, y and info, and its own target sum, which the paper
 // keeps strictly inside (0, n) (App. A.1, "Numerical Stability at Boundaries"); the same is enforced here by clamping.
 template <typename X>
-__device__ inline void select_vector(const X* __restrict__& x, double* __restrict__& y, double* __restrict__& info,
+__device__ inline void select_vector(const X*& x, double*& y, double* __restrict__& info,
                                      double& k, const double* __restrict__ k_vec, int n) {
   if (k_vec == nullptr) return;
   const size_t b = blockIdx.x;
@@ -85,7 +85,7 @@ struct StShared {
 
 template <typename X, typename Key>
 __global__ void __launch_bounds__(kStThreads)
-soft_topk_kernel(const X* __restrict__ x, int n, int P, double k, double tau, double* __restrict__ y,
+soft_topk_kernel(const X* x, int n, int P, double k, double tau, double* y /* may alias x */,
                  double* __restrict__ info, int32_t* __restrict__ budgets, double t, const double* __restrict__ k_vec) {
   extern __shared__ __align__(16) unsigned char smem[];
   select_vector(x, y, info, k, k_vec, n);   // batched call: this block's vector and target
@@ -257,7 +257,7 @@ __device__ inline void st_block_sum(StLargeShared* sh, double (&v)[4], long long
 
 template <typename X>
 __global__ void __launch_bounds__(kStThreads)
-soft_topk_large_kernel(const X* __restrict__ x, int n, double k, double tau, double* __restrict__ y,
+soft_topk_large_kernel(const X* x, int n, double k, double tau, double* y /* may alias x */,
                        double* __restrict__ info, int32_t* __restrict__ budgets, double t,
                        const double* __restrict__ k_vec) {
   __shared__ StLargeShared sh;
@@ -358,7 +358,7 @@ soft_topk_large_kernel(const X* __restrict__ x, int n, double k, double tau, dou
 template <typename X>
 __global__ void __launch_bounds__(kStThreads)
 soft_topk_backward_kernel(const X* __restrict__ x, int n, double tau, const double* __restrict__ info,
-                          const double* __restrict__ g, double* __restrict__ dx, double* __restrict__ dk) {
+                          const double* g, double* dx /* may alias g */, double* __restrict__ dk) {
   __shared__ StLargeShared sh;
   {   // one vector per block
     const size_t b = blockIdx.x;

@@ -36,11 +36,11 @@ void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total
 // compact.hip
 void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
                     int heads_per_seq, int seq_lo, int head_lo, int n_heads_view, int64_t row_lo, int64_t row_hi,
-                    void* kp, void* vp, hipStream_t stream);
+                    void* kp, void* vp, hipStream_t stream, bool rows_of_own_sequences = false);
 
 void launch_compact_grow(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,
                          int heads_per_seq, int seq_lo, int64_t total_kept, int slack, void* kp, void* vp, float* up,
-                         hipStream_t stream);
+                         hipStream_t stream, bool rows_of_own_sequences = false);
 void launch_compact_regrow(const int32_t* idx, const int32_t* offsets, int n_segments, int64_t total_kept, int slack,
                            const void* kp_old, const void* vp_old, const float* up_old, const int32_t* cap_old,
                            const int32_t* len_old, void* kp, void* vp, float* up, hipStream_t stream);

@@ -46,9 +46,7 @@ constexpr int kMbStride = 288;                 // LDS bytes per staged row: meas
                                                // reads and for the transposing reads (272 was not, for the straight ones)
 constexpr float kMbLog2e = 1.4426950408889634f;
 
-#ifndef LKV_MB_SPLIT_BELOW_BLOCKS
-#define LKV_MB_SPLIT_BELOW_BLOCKS 512
-#endif
+constexpr int kMbSplitBelowBlocks = 512;       // fewer dkv blocks than this: one block per query head instead of per KV head
 
 __device__ __forceinline__ float mb_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -502,11 +500,7 @@ hipError_t masked_attn_bwd_prepare() {
 // One block per query head (partial sums + a reduce pass) pays when the blocks of a KV head's whole group would be
 // few and long: the longest of them walks G * T / 64 staged tiles one after the other.
 static bool dkv_split_by_query_head(int n_kv_heads, int G, int T) {
-#ifdef LKV_MB_SPLIT_ALWAYS
-  return G > 1;
-#else
-  return G > 1 && (int64_t)((T + 127) / 128) * n_kv_heads < LKV_MB_SPLIT_BELOW_BLOCKS;
-#endif
+  return G > 1 && (int64_t)((T + 127) / 128) * n_kv_heads < kMbSplitBelowBlocks;
 }
 
 static size_t align256(size_t n) { return (n + 255) & ~(size_t)255; }

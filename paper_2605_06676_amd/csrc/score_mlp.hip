@@ -321,9 +321,6 @@ int score_mlp_rows_per_block(int T, int heads, int hidden) {
   // large tiles amortise the W1 fragments each wave loads; short heads, and launches over few
   // heads (one layer at a time), take smaller tiles so that the grid still covers the chip.
   // The wave-pair kernel has twice as many resident blocks, so half the rows give it as many rounds.
-#ifdef LKV_MLP_ROWS
-  if (T >= 16384) return LKV_MLP_ROWS;
-#endif
   const int longest = hidden > 64 ? 2048 : 4096;
   int rows = T >= 16384 ? longest : (T >= 4096 ? 1024 : 256);
   while (rows > 256 && (int64_t)heads * ((T + rows - 1) / rows) < 1024) rows >>= 1;

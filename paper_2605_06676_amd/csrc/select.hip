@@ -69,6 +69,7 @@ struct SelShared {
   uint32_t wave_eq[kSelWaves];
   uint32_t found_bin;
   uint32_t found_above;
+  uint32_t found_count;
   uint32_t cand_count;
 };
 
@@ -140,10 +141,12 @@ __device__ __forceinline__ void for_each_global_key(const float* __restrict__ u,
 }
 
 // One level of the radix descent.  `count(fn)` must call fn(key) for every key of the head.
-// On return prefix / prefix_mask / need are advanced by this level's digit.
+// On return prefix / prefix_mask / need are advanced by this level's digit.  Returns the number of
+// keys in the bin the descent entered (the same value in every thread: it is published by the one
+// thread that found the bin and read between two block barriers, so a branch on it is uniform).
 // `counted`: the histogram of this level has already been filled (and a barrier passed).
 template <typename Count>
-__device__ __forceinline__ void descend_level(SelShared& sh, int level, uint32_t& prefix, uint32_t& prefix_mask,
+__device__ __forceinline__ uint32_t descend_level(SelShared& sh, int level, uint32_t& prefix, uint32_t& prefix_mask,
                                               uint32_t& need, Count count, bool counted = false) {
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -170,13 +173,19 @@ __device__ __forceinline__ void descend_level(SelShared& sh, int level, uint32_t
   const uint32_t before = waves_before(sh.wave_tot, wave, lane);
   const uint32_t excl = before + incl - (c0 + c1);   // keys in bins above this thread's pair
   // exactly one bin satisfies: above < need <= above + count
-  if (c0 && excl < need && need <= excl + c0) { sh.found_bin = (uint32_t)top; sh.found_above = excl; }
-  if (c1 && excl + c0 < need && need <= excl + c0 + c1) { sh.found_bin = (uint32_t)(top - 1); sh.found_above = excl + c0; }
+  if (c0 && excl < need && need <= excl + c0) { sh.found_bin = (uint32_t)top; sh.found_above = excl; sh.found_count = c0; }
+  if (c1 && excl + c0 < need && need <= excl + c0 + c1) {
+    sh.found_bin = (uint32_t)(top - 1);
+    sh.found_above = excl + c0;
+    sh.found_count = c1;
+  }
   __syncthreads();
   prefix |= sh.found_bin << shift;
   prefix_mask |= (uint32_t)(nbins - 1) << shift;
   need -= sh.found_above;
+  const uint32_t in_bin = sh.found_count;
   __syncthreads();   // found_* and hist are rewritten at the next level
+  return in_bin;
 }
 
 // Ordered emission from a per-token key source `key_of(i)` (LDS key cache, or global scores).
@@ -412,13 +421,12 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
   }
 
   auto count = [&](auto fn) { for_each_global_key(u, T, [&](uint32_t key, int) { fn(key); }); };
-  descend_level(sh, 0, prefix, prefix_mask, need, count);
+  const uint32_t n_cand = descend_level(sh, 0, prefix, prefix_mask, need, count);   // keys left in the undecided bin
   // Heads too long for the key cache: the first level leaves one bin of 2048 undecided.  When its
   // keys are few enough to list (their token indices, in the space the emission stages through
   // later), one more pass over the scores settles everything above that bin and collects the
   // list; the remaining two levels and the final comparison then touch the listed tokens only.
   const uint32_t bin0 = prefix >> 21;
-  const uint32_t n_cand = sh.hist[bin0];   // level-0 counts stay until the next level clears them
   if (T <= bitmap_limit && n_cand <= (uint32_t)kSelCandCap) {
     const int n_words = (T + 31) >> 5;
     uint32_t* gt_map = region;
@@ -511,14 +519,13 @@ void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total
   const size_t bitmap_stage_off = 2 * (size_t)((bitmap_limit + 31) / 32);
   if (bitmap_limit > 0 && bitmap_stage_off * 4 + kSelStageBytes > region) region = bitmap_stage_off * 4 + kSelStageBytes;
   const SelRagged ragged = {ragged_scores, ragged_start, ragged_len};
-  InlineOffsets inl;
+  InlineOffsets inl = {};
   if (host_offsets != nullptr) {
     for (int i = 0; i <= n_total_segments; ++i) inl.v[i] = host_offsets[i];
     hipLaunchKernelGGL(select_kernel<true>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
                        inl, ragged, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
                        (int)bitmap_stage_off);
   } else {
-    inl.v[0] = 0;
     hipLaunchKernelGGL(select_kernel<false>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
                        inl, ragged, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
                        (int)bitmap_stage_off);

@@ -251,14 +251,17 @@ def lkv_score_window(ctx: Context, cache: Cache, q_win: Sequence, window: int, p
 
 
 def lkv_select(ctx: Context, cache: Cache, scores: Sequence, budgets, idx, offsets, stream=None) -> None:
-    """budgets: host int32 array [n_seq * L * H]; idx (int32 [sum b]) and offsets (int32 [n_seg + 1]) GPU tensors."""
+    """budgets: host int32 array [n_seq * L * H], or None when `offsets` already holds what lkv_plan_offsets wrote for
+    them; idx (int32 [sum b]) and offsets (int32 [n_seg + 1]) GPU tensors."""
     import numpy as np
 
-    b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
-    assert b.size == cache.n_segments
+    bp = None
+    if budgets is not None:
+        b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
+        assert b.size == cache.n_segments
+        bp = b.ctypes.data_as(C.POINTER(C.c_int32))
     sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
-    ctx._check(ctx.lib.lkv_select(ctx.h, C.byref(cache.c), sp, b.ctypes.data_as(C.POINTER(C.c_int32)),
-                                  _ptr(idx), _ptr(offsets), _stream_ptr(stream)))
+    ctx._check(ctx.lib.lkv_select(ctx.h, C.byref(cache.c), sp, bp, _ptr(idx), _ptr(offsets), _stream_ptr(stream)))
 
 
 def lkv_compact(ctx: Context, cache: Cache, idx, offsets, total_kept: int, kp, vp, stream=None) -> None:

@@ -140,3 +140,98 @@ def test_captured_window_scoring_replays_to_the_eager_result(ctx):
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(scores, want[0]) and torch.equal(idx, want[1]) and torch.equal(offsets, want[2]), f"replay {rep}"
+
+
+def _many_segment_case(ctx, n_seq=5):
+    # the shape of the batched workload (several sequences of different length, 32 x 8 heads each) at small T:
+    # 5 x 16 x 8 = 640 segments, the first count at which host budgets no longer fit the kernel arguments
+    w = W.scaled(W.CONFIGS[3], n_seq=n_seq, L=16, H=8, Hq=32, b_min=4)
+    rng = np.random.default_rng(11)
+    Ts = [int(t) for t in rng.integers(150, 700, size=n_seq)]
+    Ks, Vs, Qs, Bs = [], [], [], []
+    for s, T in enumerate(Ts):
+        K, V = W.draw_kv(w, T, s, 3)
+        Ks.append(K); Vs.append(V); Qs.append(W.draw_q(w, s, 3)); Bs.append(W.draw_budgets(w, T, s, 3))
+    sc = W.draw_scorer(w, 3)
+    run = G.GpuRun(ctx, Ks, Vs, Qs, sc, Bs, w.Hq)
+    assert run.cache.n_segments >= 640
+    return run, (Ks, Vs, Qs, sc, Bs)
+
+
+def test_captured_step_with_640_segments_reads_planned_offsets(ctx):
+    # offsets planned once outside the capture (budgets are static); inside it lkv_select gets budgets = NULL, so
+    # the captured step holds kernels only, whatever the number of segments
+    run, (Ks, Vs, Qs, sc, Bs) = _many_segment_case(ctx)
+    run.run_all()                                            # the route with host budgets (staged upload)
+    G.check_against_oracle(run, Ks, Vs, Qs, sc, Bs, "eager, host budgets")
+    want = {k: getattr(run, k).clone() for k in ("idx", "offsets", "kp", "vp", "out", "lse")}
+    run.offsets.fill_(-7)
+    assert lkv.lkv_plan_offsets(ctx, run.budgets, run.offsets) == run.total
+    torch.cuda.synchronize()
+    assert torch.equal(run.offsets, want["offsets"])
+
+    def step():
+        run.score()
+        lkv.lkv_select(ctx, run.cache, run.scores, None, run.idx, run.offsets)
+        run.compact(); run.decode()
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    other = np.ascontiguousarray(run.budgets[::-1])
+    scratch_off = torch.empty_like(run.offsets)
+    for rep in range(4):
+        for k in ("idx", "kp", "vp", "out", "lse"):
+            getattr(run, k).fill_(-3 if getattr(run, k).dtype == torch.int32 else float("nan"))
+        # eager uploads between the replays recycle every slot of the pinned ring with other contents
+        for _ in range(9):
+            lkv.lkv_plan_offsets(ctx, other, scratch_off)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(run.offsets, want["offsets"]), f"replay {rep}: offsets were modified"
+        assert torch.equal(run.idx, want["idx"]), f"replay {rep}: idx"
+        for k in ("kp", "vp"):
+            assert torch.equal(getattr(run, k).view(torch.int16), want[k].view(torch.int16)), f"replay {rep}: {k}"
+        for k in ("out", "lse"):
+            assert torch.equal(getattr(run, k), want[k]), f"replay {rep}: {k}"
+
+
+def test_offset_uploads_are_refused_during_capture(ctx):
+    # with 640 segments or more, host budgets mean a copy from a pinned ring slot: not capturable, and the call must
+    # say so before it enqueues anything (the capture stays valid and empty of that call)
+    run, _ = _many_segment_case(ctx)
+    run.score()
+    lkv.lkv_plan_offsets(ctx, run.budgets, run.offsets)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    errors = []
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for call in (lambda: lkv.lkv_select(ctx, run.cache, run.scores, run.budgets, run.idx, run.offsets),
+                         lambda: lkv.lkv_plan_offsets(ctx, run.budgets, run.offsets)):
+                with pytest.raises(lkv.LkvError) as e:
+                    call()
+                errors.append(e.value)
+            lkv.lkv_select(ctx, run.cache, run.scores, None, run.idx, run.offsets)      # the capturable route
+    torch.cuda.synchronize()
+    assert all(e.status == 2 and "captured" in str(e) for e in errors), [str(e) for e in errors]
+    run.idx.fill_(-3)
+    graph.replay()
+    torch.cuda.synchronize()
+    from oracle import lkv_oracle as O
+    row0 = 0
+    idx = run.idx.cpu().numpy()
+    for s in range(run.cache.n_seq):
+        b = run.budgets.reshape(run.cache.n_seq, run.cache.L, run.cache.H)[s]
+        idx_ref, off_ref = O.select_all(run.scores[s].cpu().numpy(), b)
+        assert np.array_equal(idx[row0:row0 + int(off_ref[-1])], idx_ref)
+        row0 += int(off_ref[-1])
