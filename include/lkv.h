@@ -219,6 +219,23 @@ lkv_status lkv_decode_attn(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_
                            float scale, float *out, float *lse, void *workspace,
                            size_t workspace_bytes, void *stream);
 
+/* lkv_decode_attn for callers that cannot allocate device memory or carry a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same
+ * kernels and bit-identical results; the split-K partials go to a fixed array of
+ * LKV_DECODE_STATIC_SCRATCH_BYTES in the library's device image instead of a caller-owned workspace
+ * (each GPU the library is used on holds that array until the process ends).  The call allocates
+ * nothing and frees nothing.  A problem whose lkv_decode_workspace_bytes(...) exceeds the array is
+ * refused with LKV_ERR_WORKSPACE before anything is enqueued (the five benchmark workloads need 1.6
+ * to 9.6 MB).  All calls on one GPU share the array, from whatever context or stream: two of them
+ * that overlap in time race on it, so order them on one stream or with events.  The array keeps the
+ * last call's partials; nothing needs clearing, because every slot that a call reads it has
+ * written first. */
+#define LKV_DECODE_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+lkv_status lkv_decode_attn_static(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads,
+                                  int32_t n_q_heads, int32_t head_dim, const void *q, const void *kp,
+                                  const void *vp, const int32_t *offsets, int64_t total_kept,
+                                  float scale, float *out, float *lse, void *stream);
+
 /* ---- Layer-by-layer eviction during prefill (Sec. 1: each layer's cache is evicted as soon as
  * the prefill has produced it, so the full cache of all layers never exists) ---------------- */
 

@@ -333,13 +333,41 @@ size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G) {
   return (bytes + 255) & ~(size_t)255;
 }
 
+// Split-K partials of the decode call that allocates nothing and takes no workspace argument: a
+// fixed array in the library's device image.  Every GPU the library runs on holds its own copy at
+// its own address until the process ends.  The name below is only a host-side handle for the
+// symbol; the device address is looked up once per device and everything on the host side uses
+// that address.
+constexpr size_t kDecStaticBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kDecStaticBytes];
+constexpr int kDecMaxDevices = 64;
+static void* g_scratch_ptr[kDecMaxDevices] = {};
+
+size_t decode_static_scratch_bytes() { return kDecStaticBytes; }
+
+// Device address of the static scratch array on `device`, or null if decode_prepare has not run there.
+void* decode_static_scratch(int device) {
+  return device >= 0 && device < kDecMaxDevices ? g_scratch_ptr[device] : nullptr;
+}
+
+// Once per device, with that device current (lkv_create calls it right after selecting the device).
 // The four staging tiles exceed the default 64 KB of LDS per workgroup.
-hipError_t decode_prepare() {
+hipError_t decode_prepare(int device) {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel<false>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, kDecWaves * kDecWaveLds);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel<true>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, kDecWaves * kDecWaveLds);
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(decode_partial_kernel<true>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kDecWaves * kDecWaveLds);
+  if (e != hipSuccess) return e;
+  if (device < 0 || device >= kDecMaxDevices) return hipErrorInvalidDevice;
+  if (g_scratch_ptr[device] == nullptr) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (ptr == nullptr) return hipErrorInvalidSymbol;
+    g_scratch_ptr[device] = ptr;
+  }
+  return hipSuccess;
 }
 
 // offsets[s] = s * len for s = 0..n_segments: the uncompacted cache of one sequence seen as a packed cache

@@ -156,7 +156,7 @@ lkv_status lkv_create(lkv_ctx** out, int device) {
       return LKV_ERR_HIP;
     }
   }
-  if (lkv::select_prepare() != hipSuccess || lkv::decode_prepare() != hipSuccess ||
+  if (lkv::select_prepare() != hipSuccess || lkv::decode_prepare(device) != hipSuccess ||
       lkv::score_mlp_prepare() != hipSuccess || lkv::lkv_h_prepare() != hipSuccess ||
       lkv::masked_attn_prepare() != hipSuccess || lkv::masked_attn_bwd_prepare() != hipSuccess) {
     lkv_destroy(ctx);
@@ -479,6 +479,33 @@ lkv_status lkv_decode_attn(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_
   if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, nullptr, (int)n_seg, total_kept, scale, out, lse,
                                         static_cast<float*>(workspace), as_stream(stream)))
     return hip_fail(ctx, e, "lkv_decode_attn launch");
+  return LKV_OK;
+}
+
+lkv_status lkv_decode_attn_static(lkv_ctx* ctx, int32_t n_seq, int32_t n_layers, int32_t n_kv_heads, int32_t n_q_heads,
+                                  int32_t head_dim, const void* q, const void* kp, const void* vp, const int32_t* offsets,
+                                  int64_t total_kept, float scale, float* out, float* lse, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  int G = 0;
+  int64_t n_seg = 0;
+  if (lkv_status st = check_decode_geometry(ctx, n_seq, n_layers, n_kv_heads, n_q_heads, head_dim, &G, &n_seg)) return st;
+  if (total_kept < 0 || total_kept >= (int64_t)1 << 31)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "total_kept = %lld is outside [0, 2^31)", (long long)total_kept);
+  if (q == nullptr || offsets == nullptr || out == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "q, offsets or out is NULL");
+  if (total_kept > 0 && (kp == nullptr || vp == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is NULL");
+  if (!aligned16(q) || !aligned16(kp) || !aligned16(vp) || !aligned16(out))
+    return fail(ctx, LKV_ERR_INVALID_ARG, "q, kp, vp or out is not 16-byte aligned");
+  const size_t need = lkv::decode_workspace_bytes((int)n_seg, total_kept, G);
+  if (need > lkv::decode_static_scratch_bytes())
+    return fail(ctx, LKV_ERR_WORKSPACE,
+                "this problem needs %zu bytes of split-K scratch, the static array holds %zu: use lkv_decode_attn with a "
+                "caller-owned workspace", need, lkv::decode_static_scratch_bytes());
+  // the device address of the static array on this context's GPU (looked up by lkv_create), never the symbol itself
+  float* ws = static_cast<float*>(lkv::decode_static_scratch(ctx->device));
+  if (ws == nullptr) return fail(ctx, LKV_ERR_HIP, "the static scratch array of device %d has no address", ctx->device);
+  if (hipError_t e = lkv::launch_decode(G, q, kp, vp, offsets, nullptr, (int)n_seg, total_kept, scale, out, lse, ws,
+                                        as_stream(stream)))
+    return hip_fail(ctx, e, "lkv_decode_attn_static launch");
   return LKV_OK;
 }
 

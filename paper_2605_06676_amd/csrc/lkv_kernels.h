@@ -55,8 +55,10 @@ void launch_append(int n_segments, int heads_per_seq, int n_kv_heads, int scorer
 
 // decode.hip
 constexpr int kDecodeMaxGroup = 16;
-hipError_t decode_prepare();
+hipError_t decode_prepare(int device);
 size_t decode_workspace_bytes(int n_segments, int64_t total_kept, int G);
+size_t decode_static_scratch_bytes();
+void* decode_static_scratch(int device);
 hipError_t launch_decode(int G, const void* q, const void* kp, const void* vp, const int32_t* offsets,
                          const int32_t* lengths, int n_segments, int64_t total_kept, float scale, float* out, float* lse, float* ws,
                          hipStream_t stream, const float* mask = nullptr);

@@ -22,7 +22,7 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score",
            "lkv_score_window_workspace_bytes", "lkv_score_window", "lkv_select",
-           "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_soft_topk_max_n",
+           "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_decode_attn_static", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_soft_topk_backward", "lkv_soft_topk_batched", "lkv_soft_topk_backward_batched",
            "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
            "lkv_append", "lkv_decode_attn_grown", "lkv_reevict", "lkv_masked_decode_workspace_bytes",
@@ -91,6 +91,10 @@ def load_library() -> C.CDLL:
                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lkv_decode_attn.restype = C.c_int
+    lib.lkv_decode_attn_static.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_float, C.c_void_p,
+                                           C.c_void_p, C.c_void_p]
+    lib.lkv_decode_attn_static.restype = C.c_int
     lib.lkv_plan_offsets.argtypes = [C.c_void_p, C.c_int64, C.POINTER(C.c_int32), C.c_void_p, C.POINTER(C.c_int64),
                                      C.c_void_p]
     lib.lkv_plan_offsets.restype = C.c_int
@@ -279,6 +283,16 @@ def lkv_decode_attn(ctx: Context, n_seq: int, L: int, H: int, Hq: int, d: int, q
     ctx._check(ctx.lib.lkv_decode_attn(ctx.h, n_seq, L, H, Hq, d, _ptr(q), _ptr(kp), _ptr(vp), _ptr(offsets),
                                        int(total_kept), float(scale), _ptr(out), _ptr(lse), _ptr(workspace),
                                        ws_bytes, _stream_ptr(stream)))
+
+
+DECODE_STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def lkv_decode_attn_static(ctx: Context, n_seq: int, L: int, H: int, Hq: int, d: int, q, kp, vp, offsets,
+                           total_kept: int, scale: float, out, lse, stream=None) -> None:
+    """lkv_decode_attn without a workspace argument: the partials go to the library's static device array."""
+    ctx._check(ctx.lib.lkv_decode_attn_static(ctx.h, n_seq, L, H, Hq, d, _ptr(q), _ptr(kp), _ptr(vp), _ptr(offsets),
+                                              int(total_kept), float(scale), _ptr(out), _ptr(lse), _stream_ptr(stream)))
 
 
 def lkv_soft_topk_max_n(x_is_f64: bool) -> int:
