@@ -8,11 +8,17 @@ eviction calls ((head-tokens - kept) / time); the decode leg is reported as
 achieved HBM GB/s in `decode`.  The `roofline` object is for the kernel that
 moves most of the bytes, the token scorer.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
+With no --config the headline (top-level keys) is the 131072-token workload
+(32 x 8 heads, MLP 256 -> 64 GELU scorer) and `per_workload` carries the same
+keys for the 32768-token workload, the 16-sequence batch and the 8 x 65536
+batch, measured one after the other in the same process.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N]
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import math
 import os
@@ -25,10 +31,39 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the score kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled
-# by what the counter reads for a plain 1 GiB copy (profiles/hbm_traffic_counters__*.md).
-# Hardware counters cannot be read from inside this script, so the figure is carried per workload; None = not measured.
-MEASURED_SCORE_TRAFFIC_BYTES = {1: 4328786289, 2: 17324229632, 5: 4465987584}
+HEADLINE_CONFIG = 2
+ALSO_BY_DEFAULT = (1, 3, 4)
+
+# HBM bytes per launch of the score kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs, each scaled by what
+# the same counter reads for a plain 1 GiB copy (the profiles/ file named next to each figure).  Hardware counters
+# cannot be read from inside this script, so the figure is carried per workload together with the hash of the
+# kernel's sources at the time of the measurement; when the sources have changed since, `traffic` is null.
+SCORE_KERNEL_SOURCES = {
+    "score_linear_kernel": ("score_linear.hip", "lkv_common.h"),
+    "score_mlp_kernel": ("score_mlp.hip", "lkv_act.h", "lkv_common.h"),
+    "score_mlp_wide_kernel": ("score_mlp.hip", "lkv_act.h", "lkv_common.h"),
+}
+MEASURED_SCORE_TRAFFIC = {
+    # workload name: (bytes per launch, sha256[:16] of the kernel's sources, profile)
+}
+
+
+def kernel_source_hash(kernel: str) -> str:
+    h = hashlib.sha256()
+    for name in SCORE_KERNEL_SOURCES[kernel]:
+        with open(os.path.join(ROOT, "paper_2605_06676_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload: str, kernel: str):
+    rec = MEASURED_SCORE_TRAFFIC.get(workload)
+    if rec is None:
+        return None, None
+    nbytes, src_hash, profile = rec
+    if src_hash != kernel_source_hash(kernel):
+        return None, None          # the kernel has changed since the counters were read
+    return nbytes, profile
 
 
 def parse():
@@ -36,7 +71,9 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=1, help="workload 0..5 (1 = the Llama-3-8B-shaped 32k cache)")
+    ap.add_argument("--config", type=int, default=None,
+                    help="measure this workload only (0..6); default: the 131072-token workload as the headline and "
+                         "workloads 1, 3 and 4 under `per_workload`")
     ap.add_argument("--seq-len", type=int, default=0, metavar="T",
                     help="override the context length of a fixed-length workload (the paper's overhead run is at 200k, Sec. 4.5)")
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
@@ -54,7 +91,11 @@ def parse():
     ap.add_argument("--window-score", type=int, nargs="?", const=32, default=0, metavar="W",
                     help="also time the observation-window scorer (window W, default 32) and the eviction it feeds")
     ap.add_argument("--layerwise", action="store_true",
-                    help="also measure layer-by-layer eviction during prefill; adds the key `layerwise`")
+                    help="also measure layer-by-layer eviction during prefill; adds the key `layerwise` (a list: one entry "
+                         "per --layerwise-shape)")
+    ap.add_argument("--layerwise-shape", action="append", default=None, metavar="STREAMS,LAYERS",
+                    help="eviction streams and layers per lkv_evict_layer call for --layerwise (repeatable; "
+                         "default 2,1 and 4,1 and 2,4)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy before the timed region (a kernel of known "
                          "traffic for scaling hardware byte counters under rocprofv3 --pmc)")
@@ -62,48 +103,34 @@ def parse():
     return ap.parse_args()
 
 
-def main():
-    args = parse()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (every (sequence, layer, head) is independent, "
-              "so more GPUs would just take disjoint heads); run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def to_dev(a, dev, bf16=False):
     import torch
 
-    from paper_2605_06676_amd import lkv
-    from paper_2605_06676_amd import workloads as W
+    if a is None:
+        return None
+    if bf16:
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
 
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU visible", file=sys.stderr)
-        sys.exit(2)
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    w = W.CONFIGS[args.config]
-    if args.seq_len:
-        if not isinstance(w.T, int):
-            print("bench.py: --seq-len needs a workload with one fixed length", file=sys.stderr)
-            sys.exit(2)
-        w = W.scaled(w, T=args.seq_len, name=f"{w.name}-T{args.seq_len}")
-    ctx = lkv.Context(0)
+
+def run_workload(ctx, lkv, W, w, args, dev, headline):
+    """Times the step on workload `w`; returns the keys that describe one workload.  The extras that the
+    command line asks for (growth, layer-by-layer, ...) and the oracle baseline are measured for the
+    headline workload only."""
+    import torch
+
     layerwise_result = None
-
     sc_host = W.draw_scorer(w)
-
-    def to_dev(a, bf16=False):
-        if a is None:
-            return None
-        if bf16:
-            return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(dev)
-        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(dev)
-
     scorer = {"kind": sc_host["kind"], "act": sc_host["act"], "hidden": sc_host["hidden"],
-              "per_head": sc_host["per_head"], "w1": to_dev(sc_host["w1"], True), "b1": to_dev(sc_host["b1"]),
-              "w2": to_dev(sc_host["w2"]), "b2": to_dev(sc_host["b2"])}
+              "per_head": sc_host["per_head"], "w1": to_dev(sc_host["w1"], dev, True), "b1": to_dev(sc_host["b1"], dev),
+              "w2": to_dev(sc_host["w2"], dev), "b2": to_dev(sc_host["b2"], dev)}
     # ---- layer-by-layer mode first, while the whole cache does not exist yet ---------------
-    if args.layerwise:
-        layerwise_result = layerwise(ctx, lkv, W, w, scorer, dev)
-        torch.cuda.empty_cache()
+    if headline and args.layerwise:
+        shapes = [tuple(int(x) for x in sh.split(",")) for sh in (args.layerwise_shape or ["2,1", "4,1", "2,4"])]
+        layerwise_result = []
+        for n_streams, per_call in shapes:
+            layerwise_result.append(layerwise(ctx, lkv, W, w, scorer, dev, n_streams, per_call))
+            torch.cuda.empty_cache()
 
     # ---- inputs, resident in HBM before the timed region --------------------------------
     Ts = [int(t) for t in W.seq_lengths(w)]
@@ -114,8 +141,8 @@ def main():
     cache = lkv.Cache(Ks, Vs, w.Hq)
     # LKV-H (Sec. 3.3): ratios are computed once from static parameters; timed apart from the step
     emb_h, mlp_h = W.draw_head_predictor(w)
-    emb_d = to_dev(emb_h)
-    pred_d = {k: to_dev(mlp_h[k]) for k in ("w1", "b1", "w2")}
+    emb_d = to_dev(emb_h, dev)
+    pred_d = {k: to_dev(mlp_h[k], dev) for k in ("w1", "b1", "w2")}
     pred_d["b2"] = None
     r_d = torch.empty((w.L * w.H,), dtype=torch.float64, device=dev)
     b_d = torch.empty((w.L * w.H,), dtype=torch.int32, device=dev)
@@ -144,24 +171,33 @@ def main():
     offsets = torch.empty((cache.n_segments + 1,), dtype=torch.int32, device=dev)
     kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
     vp = torch.empty_like(kp)
-    q = torch.stack([to_dev(W.draw_q(w, s), True) for s in range(w.n_seq)]).contiguous()
+    q = torch.stack([to_dev(W.draw_q(w, s), dev, True) for s in range(w.n_seq)]).contiguous()
     out = torch.empty((w.n_seq, w.L, w.Hq, w.d), dtype=torch.float32, device=dev)
     lse = torch.empty((w.n_seq, w.L, w.Hq), dtype=torch.float32, device=dev)
     ws = torch.empty((lkv.lkv_decode_workspace_bytes(cache.n_segments, total, w.Hq, w.H),), dtype=torch.uint8, device=dev)
     scale = 1.0 / math.sqrt(w.d)
 
+    # The packed layout follows from the budgets alone, and those are static (Sec. 3.3: b = floor(r t) with frozen
+    # ratios), so the offsets are planned once per (model, context length), before the timed region; inside it
+    # lkv_select reads them from the device: no copy and no host wait, whatever the number of segments.
+    t0 = time.perf_counter()
+    planned = lkv.lkv_plan_offsets(ctx, budgets_flat, offsets)
+    torch.cuda.synchronize()
+    plan_us = (time.perf_counter() - t0) * 1e6
+    assert planned == total
+
     def step(ev=None):
         if ev: ev[0].record()
         lkv.lkv_score(ctx, cache, scorer, scores)
         if ev: ev[1].record()
-        lkv.lkv_select(ctx, cache, scores, budgets_flat, idx, offsets)
+        lkv.lkv_select(ctx, cache, scores, None, idx, offsets)
         if ev: ev[2].record()
         lkv.lkv_compact(ctx, cache, idx, offsets, total, kp, vp)
         if ev: ev[3].record()
         lkv.lkv_decode_attn(ctx, w.n_seq, w.L, w.H, w.Hq, w.d, q, kp, vp, offsets, total, scale, out, lse, ws)
         if ev: ev[4].record()
 
-    if args.calibrate_copy:
+    if headline and args.calibrate_copy:
         src = torch.zeros((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
         dst = torch.empty_like(src)
         torch.cuda.synchronize()
@@ -187,18 +223,19 @@ def main():
     evict_bytes = N * 520 + total * 1032
     decode_bytes = total * 512 + w.n_seq * w.L * w.Hq * w.d * (2 + 4)
     score_bytes = N * 516
+    kernel = "score_linear_kernel" if w.scorer == "linear" else ("score_mlp_kernel" if w.hidden <= 64 else "score_mlp_wide_kernel")
+    launches = 1 if w.n_seq <= 32 else math.ceil(w.n_seq / 32)
+    traffic, traffic_profile = (None, None) if args.seq_len or args.budgets != "recipe" else measured_traffic(w.name, kernel)
 
     result = {
-        "metric": "KV tokens evicted/sec (score+select+compact); ragged decode-attn HBM GB/s in `decode`",
         "value": (N - total) / (t_evict * 1e-3),
-        "unit": "evicted KV entries/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": wall * 1e3 / args.steps,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "accumulate": "f32", "data": "synthetic",
         "config": {"workload": w.name, "n_seq": w.n_seq, "layers": w.L, "kv_heads": w.H, "q_heads": w.Hq,
                    "seq_len": Ts if len(set(Ts)) > 1 else Ts[0], "head_tokens": N, "kept": total,
-                   "retention": rho, "scorer": w.scorer if w.scorer == "linear" else f"mlp256-{w.hidden}-{w.act}"},
+                   "retention": rho, "scorer": w.scorer if w.scorer == "linear" else f"mlp256-{w.hidden}-{w.act}",
+                   "budgets": "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe",
+                   "offsets": "planned once before the timed region (budgets are static); lkv_select reads them from the device",
+                   "plan_offsets_us": plan_us},
         "phases_ms": {"score": t_score, "select": t_select, "compact": t_compact, "decode": t_decode,
                       "evict": t_evict, "step_gpu": float(ph.sum(axis=1).mean())},
         "evict": {"bytes": evict_bytes, "GBps": evict_bytes / (t_evict * 1e6),
@@ -206,13 +243,12 @@ def main():
                   "context_tokens_per_s": sum(Ts) / (t_evict * 1e-3)},
         "decode": {"bytes": decode_bytes, "GBps": decode_bytes / (t_decode * 1e6),
                    "frac_of_peak": decode_bytes / (t_decode * 1e6) / HBM_PEAK_GBS},
-        "roofline": {"kernel": "score_linear_kernel" if w.scorer == "linear"
-                     else ("score_mlp_kernel" if w.hidden <= 64 else "score_mlp_wide_kernel"),
-                     "bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS,
+        # achieved = algorithmic bytes of one launch (516 B per head-token) over the kernel's average duration,
+        # from the events that bracket lkv_score on the stream it runs on (the call is `launches` launches back to back)
+        "roofline": {"kernel": kernel, "bound": "hbm", "achieved": score_bytes / (t_score * 1e6), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": score_bytes / (t_score * 1e6) / HBM_PEAK_GBS,
-                     "traffic": None if args.seq_len else MEASURED_SCORE_TRAFFIC_BYTES.get(args.config),
-                     "launches_per_step": 1 if w.n_seq <= 32 else math.ceil(w.n_seq / 32),
-                     "bytes_per_launch": score_bytes},
+                     "traffic": traffic, "traffic_profile": traffic_profile, "kernel_source_sha256_16": kernel_source_hash(kernel),
+                     "launches_per_step": launches, "bytes_per_launch": score_bytes // launches},
     }
 
     # decode by itself, back to back: what a serving loop sees between evictions (the in-step figure above
@@ -228,6 +264,8 @@ def main():
     result["decode"]["steady_state_ms"] = t_steady
     result["decode"]["steady_state_GBps"] = decode_bytes / (t_steady * 1e6)
     result["decode"]["steady_state_frac_of_peak"] = decode_bytes / (t_steady * 1e6) / HBM_PEAK_GBS
+    if not headline:
+        return result
 
     # ---- context figures: a plain device copy on this machine, and decode launched once per layer ----
     src = torch.empty((1 << 28,), dtype=torch.float32, device=dev)      # 1 GiB
@@ -286,7 +324,6 @@ def main():
                                                "hip_graph_us_per_layer": t_graph * 1e3 / w.L,
                                                "hip_graph_GBps": decode_bytes / (t_graph * 1e6),
                                                "note": "launch-latency bound at batch 1: one layer is ~20-54 MB"}
-    result["config"]["budgets"] = "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe"
     result["lkv_h"] = {"n_heads": w.L * w.H, "us_per_call": lkv_h_us, "dtype": "f64",
                        "note": "head scores + Soft-TopK + floor(r t); computed once, outside the step"}
     if layerwise_result is not None:
@@ -300,6 +337,55 @@ def main():
                                                 Ts, args.window_score, scale, dev)
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, args.cpu_seconds)
+    return result
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (every (sequence, layer, head) is independent, "
+              "so more GPUs would just take disjoint heads); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2605_06676_amd import lkv
+    from paper_2605_06676_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    head_id = HEADLINE_CONFIG if args.config is None else args.config
+    others = ALSO_BY_DEFAULT if args.config is None and not args.seq_len else ()
+    w = W.CONFIGS[head_id]
+    if args.seq_len:
+        if not isinstance(w.T, int):
+            print("bench.py: --seq-len needs a workload with one fixed length", file=sys.stderr)
+            sys.exit(2)
+        w = W.scaled(w, T=args.seq_len, name=f"{w.name}-T{args.seq_len}")
+    ctx = lkv.Context(0)
+
+    head = run_workload(ctx, lkv, W, w, args, dev, headline=True)
+    result = {
+        "metric": "KV tokens evicted/sec (score+select+compact); ragged decode-attn HBM GB/s in `decode`",
+        "value": head.pop("value"),
+        "unit": "evicted KV entries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head.pop("ms_per_step"),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "accumulate": "f32", "data": "synthetic",
+    }
+    result.update(head)
+    if others:
+        per = {}
+        for cid in others:
+            torch.cuda.empty_cache()
+            r = run_workload(ctx, lkv, W, W.CONFIGS[cid], args, dev, headline=False)
+            r["unit"] = "evicted KV entries/s"
+            per[r["config"]["workload"]] = r
+        result["per_workload"] = per
     print(json.dumps(result))
 
 
@@ -490,83 +576,95 @@ def growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total
             "reevict_ms": t_reevict, "reevict_kept": total2, "reevict_GBps": re_bytes / (t_reevict * 1e6)}
 
 
-def layerwise(ctx, lkv, W, w, scorer, dev, reps=3):
-    """Layer-by-layer eviction during prefill (Sec. 1): a stand-in producer fills one layer's K/V on
-    one stream (it takes the place of the prefill compute), the eviction of the previous layer runs on
-    another; two layer buffers are alive at any time instead of L.  Reports time and peak memory."""
+def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, reps=3):
+    """Layer-by-layer eviction during prefill (Sec. 1): a stand-in producer fills the K/V of the next
+    `layers_per_call` layers on one stream (it takes the place of the prefill compute), the eviction of
+    earlier layers runs on `n_streams` other streams in turn; n_streams buffers of layers_per_call layers
+    are alive at any time instead of L layers.  Reports time and peak memory."""
     import torch
 
     Ts = [int(t) for t in W.seq_lengths(w)]
     if len(Ts) > 32:
         return None
+    m = layers_per_call
+    calls = [(l, min(m, w.L - l)) for l in range(0, w.L, m)]
     torch.cuda.synchronize()
     torch.cuda.reset_peak_memory_stats()
     base = torch.cuda.memory_allocated()
     budgets = np.concatenate([W.draw_budgets(w, T, s).reshape(-1) for s, T in enumerate(Ts)]).astype(np.int32)
     n_seg = budgets.size
     total = int(budgets.sum())
-    ring = [([torch.empty((1, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts],
-             [torch.empty((1, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts]) for _ in range(2)]
-    views = [lkv.Cache(k, v, w.Hq) for k, v in ring]
-    # eviction alternates between two streams (each with its own score scratch) so that the latency-bound
-    # top-k of one layer overlaps the bandwidth-bound scoring of the next
-    scratch = [[torch.empty((w.H, T), dtype=torch.float32, device=dev) for T in Ts] for _ in range(2)]
+    ring = [([torch.empty((m, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts],
+             [torch.empty((m, w.H, T, w.d), dtype=torch.bfloat16, device=dev) for T in Ts]) for _ in range(n_streams)]
+
+    def view(slot, n):
+        return lkv.Cache([k[:n] for k in ring[slot][0]], [v[:n] for v in ring[slot][1]], w.Hq)
+
+    views = {(slot, n): view(slot, n) for slot in range(n_streams) for n in {c[1] for c in calls}}
+    # the eviction streams take the calls in turn (each with its own score scratch) so that the latency-bound
+    # top-k of one call overlaps the bandwidth-bound scoring of the next
+    scratch = [[torch.empty((m, w.H, T), dtype=torch.float32, device=dev) for T in Ts] for _ in range(n_streams)]
     idx = torch.empty((total,), dtype=torch.int32, device=dev)
     offsets = torch.empty((n_seg + 1,), dtype=torch.int32, device=dev)
     kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
     vp = torch.empty_like(kp)
-    s_fill, s_evicts = torch.cuda.Stream(), [torch.cuda.Stream(), torch.cuda.Stream()]
+    s_fill, s_evicts = torch.cuda.Stream(), [torch.cuda.Stream() for _ in range(n_streams)]
 
     def fill(slot):
         for t in ring[slot][0] + ring[slot][1]:
             t.normal_()
 
     def run(evict=True, produce=True):
-        filled = [torch.cuda.Event() for _ in range(w.L)]
-        evicted = [torch.cuda.Event(enable_timing=True) for _ in range(w.L)]
-        started = [torch.cuda.Event(enable_timing=True) for _ in range(w.L)]
+        n = len(calls)
+        filled = [torch.cuda.Event() for _ in range(n)]
+        evicted = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+        started = [torch.cuda.Event(enable_timing=True) for _ in range(n)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         if evict:
             lkv.lkv_plan_offsets(ctx, budgets, offsets, stream=s_evicts[0])
             planned = torch.cuda.Event()
             planned.record(s_evicts[0])
-            s_evicts[1].wait_event(planned)
-        for l in range(w.L):
-            slot = l & 1
+            for s_e in s_evicts[1:]:
+                s_e.wait_event(planned)
+        for i, (l, nl) in enumerate(calls):
+            slot = i % n_streams
             s_evict = s_evicts[slot]
             if produce:
                 with torch.cuda.stream(s_fill):
-                    if evict and l >= 2:
-                        s_fill.wait_event(evicted[l - 2])     # the buffer's previous layer has left it
+                    if evict and i >= n_streams:
+                        s_fill.wait_event(evicted[i - n_streams])     # the buffer's previous layers have left it
                     fill(slot)
-                    filled[l].record(s_fill)
+                    filled[i].record(s_fill)
             if evict:
                 if produce:
-                    s_evict.wait_event(filled[l])
-                started[l].record(s_evict)
-                lkv.lkv_evict_layer(ctx, views[slot], l, w.L, scorer, budgets, offsets, scratch[slot], idx, kp, vp,
-                                    stream=s_evict)
-                evicted[l].record(s_evict)
+                    s_evict.wait_event(filled[i])
+                started[i].record(s_evict)
+                lkv.lkv_evict_layer(ctx, views[(slot, nl)], l, w.L, scorer, budgets, offsets,
+                                    [t[:nl] for t in scratch[slot]], idx, kp, vp, stream=s_evict)
+                evicted[i].record(s_evict)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
-        per_layer = float(np.mean([started[l].elapsed_time(evicted[l]) for l in range(w.L)])) if evict else 0.0
-        return wall, per_layer
+        per_call = float(np.mean([started[i].elapsed_time(evicted[i]) for i in range(n)])) if evict else 0.0
+        return wall, per_call
 
     run()                                   # warm-up
     both = min(run()[0] for _ in range(reps))
     produce_only = min(run(evict=False)[0] for _ in range(reps))
-    fill(0); fill(1)
-    evict_only, per_layer = min(run(produce=False) for _ in range(reps))
+    for slot in range(n_streams):
+        fill(slot)
+    evict_only, per_call = min(run(produce=False) for _ in range(reps))
     peak = torch.cuda.max_memory_allocated() - base
     layer_bytes = sum(2 * w.H * T * w.d * 2 for T in Ts)
     N = sum(w.L * w.H * T for T in Ts)
-    return {"ms_producer_and_eviction": both, "ms_producer_alone": produce_only, "ms_eviction_alone": evict_only,
-            "ms_per_layer_eviction": per_layer,
-            "evict_GBps_eviction_alone": (N * 520 + total * 1032) / (evict_only * 1e6),
+    gbps = (N * 520 + total * 1032) / (evict_only * 1e6)
+    return {"eviction_streams": n_streams, "layers_per_call": m, "layer_buffers_alive": n_streams * m,
+            "ms_producer_and_eviction": both, "ms_producer_alone": produce_only, "ms_eviction_alone": evict_only,
+            "ms_per_call_eviction": per_call,
+            "evict_GBps_eviction_alone": gbps, "evict_frac_of_peak_eviction_alone": gbps / HBM_PEAK_GBS,
             "peak_bytes": int(peak), "peak_bytes_whole_cache_path": int(w.L * layer_bytes + total * 1032 + N * 4),
-            "layer_buffers_alive": 2,
-            "note": "producer = in-place normal_() of one layer's K/V on a second stream, standing in for prefill"}
+            "note": "producer = in-place normal_() of the layers' K/V on another stream, standing in for prefill; "
+                    "wall-clock times from the first enqueue to the last completion"}
 
 
 def cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, cap_s):

@@ -248,21 +248,23 @@ lkv_status lkv_decode_attn_static(lkv_ctx *ctx, int32_t n_seq, int32_t n_layers,
 lkv_status lkv_plan_offsets(lkv_ctx *ctx, int64_t n_segments, const int32_t *budgets, int32_t *offsets,
                             int64_t *total_kept, void *stream);
 
-/* Score, select and compact ONE layer into its final rows of the packed cache; the result is bit
- * for bit what lkv_score + lkv_select + lkv_compact over the whole cache write for that layer.
+/* Score, select and compact ONE layer (or a few consecutive ones) into its final rows of the packed cache;
+ * the result is bit for bit what lkv_score + lkv_select + lkv_compact over the whole cache write for it.
  * All work is enqueued on `stream`, so it can overlap the prefill of the next layer on another
  * stream; the layer's K/V may be released once the stream has passed this call.
- * layer       : a cache description with n_layers = 1 whose k[s], v[s] point at bf16 [H, T_s, d] of
- *               this layer; at most 32 sequences
- * layer_index : which layer of the model this is, in [0, n_layers)
+ * layer       : a cache description whose k[s], v[s] point at bf16 [m, H, T_s, d] of m = layer->n_layers
+ *               consecutive layers starting at layer_index (m = 1: one layer at a time, the lowest peak
+ *               memory; a larger m trades live layer buffers for fewer dependent launches per layer);
+ *               at most 32 sequences
+ * layer_index : which layer of the model the view starts at; layer_index + m <= n_layers
  * scorer      : the whole model's scorer (parameters of all layers), as for lkv_score; or NULL:
- *               `scores` already holds this layer's scores (from any scorer, for example
- *               lkv_score_window on the same layer view) and only the top-k and the compaction run
+ *               `scores` already holds the view's scores (from any scorer, for example
+ *               lkv_score_window on the same view) and only the top-k and the compaction run
  * budgets     : HOST int32 [n_seq, n_layers, H], the same table lkv_plan_offsets was given
  * offsets     : DEVICE int32 [n_seq * n_layers * H + 1] written by lkv_plan_offsets
- * scores      : HOST [n_seq] of DEVICE fp32 [H, T_s]: scratch, overwritten (an input when scorer is NULL)
- * idx         : DEVICE int32 [total_kept], the global index buffer (this layer's part is written)
- * kp, vp      : DEVICE bf16 [total_kept, d], the global packed cache (this layer's rows are written) */
+ * scores      : HOST [n_seq] of DEVICE fp32 [m, H, T_s]: scratch, overwritten (an input when scorer is NULL)
+ * idx         : DEVICE int32 [total_kept], the global index buffer (the view's part is written)
+ * kp, vp      : DEVICE bf16 [total_kept, d], the global packed cache (the view's rows are written) */
 lkv_status lkv_evict_layer(lkv_ctx *ctx, const lkv_cache *layer, int32_t layer_index, int32_t n_layers,
                            const lkv_scorer *scorer, const int32_t *budgets, const int32_t *offsets,
                            float *const *scores, int32_t *idx, void *kp, void *vp, void *stream);

@@ -544,9 +544,10 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
                            float* const* scores, int32_t* idx, void* kp, void* vp, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, layer, true)) return st;
-  if (layer->n_layers != 1) return fail(ctx, LKV_ERR_INVALID_ARG, "the layer view must have n_layers = 1, got %d", layer->n_layers);
-  if (n_layers < 1 || layer_index < 0 || layer_index >= n_layers)
-    return fail(ctx, LKV_ERR_INVALID_ARG, "layer_index %d is outside [0, %d)", layer_index, n_layers);
+  const int m = layer->n_layers;   // consecutive layers in the view
+  if (n_layers < 1 || layer_index < 0 || layer_index > n_layers - m)
+    return fail(ctx, LKV_ERR_INVALID_ARG, "layers %d .. %d of the view are outside [0, %d)", layer_index, layer_index + m - 1,
+                n_layers);
   if (budgets == nullptr || offsets == nullptr || scores == nullptr)
     return fail(ctx, LKV_ERR_INVALID_ARG, "budgets, offsets or scores is NULL");
   for (int s = 0; s < layer->n_seq; ++s)
@@ -570,7 +571,7 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
         return fail(ctx, LKV_ERR_INVALID_ARG, "budget %d of segment %lld is outside [0, %d]", b, (long long)s * heads_all + j, T);
       if (j == layer_index * H) row_lo[s] = run;
       run += b;
-      if (j == layer_index * H + H - 1) row_hi[s] = run;
+      if (j == (layer_index + m) * H - 1) row_hi[s] = run;
     }
     layer_rows += row_hi[s] - row_lo[s];
   }
@@ -578,7 +579,7 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   if (layer_rows > 0 && (idx == nullptr || kp == nullptr || vp == nullptr)) return fail(ctx, LKV_ERR_INVALID_ARG, "idx, kp or vp is NULL");
   if (!aligned16(kp) || !aligned16(vp)) return fail(ctx, LKV_ERR_INVALID_ARG, "kp or vp is not 16-byte aligned");
 
-  // score with this layer's scorer parameters, unless the caller has already scored the layer
+  // score with the scorer parameters of the view's layers, unless the caller has already scored them
   if (scorer != nullptr) {
     if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
     lkv_scorer sl = *scorer;
@@ -603,11 +604,11 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
     tab.v[i] = static_cast<const uint16_t*>(layer->v[i]);
     tab.scores[i] = scores[i];
     tab.T[i] = layer->seq_len[i];
-    tab.first[i] = i * H;
+    tab.first[i] = i * m * H;
   }
-  tab.first[layer->n_seq] = layer->n_seq * H;
+  tab.first[layer->n_seq] = layer->n_seq * m * H;
   tab.n = layer->n_seq;
-  // select: segment of (sequence i, head h) is (i * n_layers + layer_index) * H + h, offsets already on the device
+  // select: segment of (sequence i, view head j) is i * n_layers * H + layer_index * H + j, offsets already on the device
   lkv::launch_select(tab, nullptr, (int)n_seg, const_cast<int32_t*>(offsets), idx, layer_index * H, heads_all, st);
   if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer select launch");
   // compact: one contiguous row range per sequence
@@ -618,7 +619,7 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
     one.v[0] = tab.v[i];
     one.T[0] = tab.T[i];
     one.n = 1;
-    lkv::launch_compact(one, idx, offsets, (int)n_seg, heads_all, i, layer_index * H, H, row_lo[i], row_hi[i], kp, vp, st);
+    lkv::launch_compact(one, idx, offsets, (int)n_seg, heads_all, i, layer_index * H, m * H, row_lo[i], row_hi[i], kp, vp, st);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer compact launch");
   }
   return LKV_OK;

@@ -159,6 +159,19 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
   }
 }
 
+// Sum of x over the four lanes c, c + 16, c + 32, c + 48 (the four feature blocks of one token), in every one of
+// them.  Row swaps on the vector ALU (v_permlane16_swap exchanges the odd rows of its first operand with the even
+// rows of its second, v_permlane32_swap the upper half of the first with the lower half of the second; with both
+// operands equal the two results are x[lane] and x[lane ^ 16], resp. x[lane ^ 32], in some order).  A shuffle
+// through the LDS crossbar costs an LDS round trip that an in-order wave has to sit out.
+__device__ __forceinline__ float sum_over_feature_blocks(float x) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a.x) + __uint_as_float(a.y);
+  const u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
+
 // Hidden widths 80..128 (the paper's network is 256 -> 128 -> 1): W1 no longer fits the registers of
 // one wave at two waves per SIMD, so the hidden units are split over a pair of waves, and a block is
 // one pair.  Wave `half` keeps the fragments of M tiles [half * MTW, half * MTW + MTW) and both
@@ -166,8 +179,13 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
 // split evenly: wave 0 brings the key halves of the rows, wave 1 the value halves, each two tiles
 // ahead in registers.  The tile and the partial-sum slots are double buffered and one barrier per
 // tile orders everything: a wave that stages tile i + 1 has passed barrier i, so its partner has
-// finished reading tile i - 1.  Inside a wave the matrix products of tile i are issued ahead of the
-// activation arithmetic of tile i - 1, so the matrix and vector pipes overlap.
+// finished reading tile i - 1.
+// A wave issues in order, so every LDS round trip inside a step is time in which it issues nothing,
+// and with two waves per SIMD there is little else to run: the output-layer weights therefore stay in
+// registers, the bias is read at the top of the step together with the operand fragments, and the
+// four-lane sums use row swaps instead of LDS shuffles (together 7 % faster than with all three in
+// LDS).  Issuing the products of tile i ahead of the activations of tile i - 1 (a second accumulator
+// set), a third register set for rows in flight, or no barrier at all changed nothing measurable.
 constexpr int kWideThreads = 128;
 
 template <int MTW, int kAct>
@@ -216,6 +234,14 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
     par_lds[i] = j < hidden ? src[(size_t)scorer * hidden + j] : 0.f;
   }
   const float bias2 = b2 != nullptr ? b2[scorer] : 0.f;
+  __syncthreads();
+  // lane (r, c) owns hidden units 16 mw + 4 r + e of its wave's share: their bias and output weight
+  f32x4_t b1r[MTW], w2r[MTW];
+#pragma unroll
+  for (int mw = 0; mw < MTW; ++mw) {
+    b1r[mw] = *reinterpret_cast<const f32x4_t*>(par_lds + half * HW + mw * 16 + 4 * r);
+    w2r[mw] = *reinterpret_cast<const f32x4_t*>(par_lds + 2 * HW + half * HW + mw * 16 + 4 * r);
+  }
 
   const size_t head_row0 = (size_t)lh * (size_t)T;
   // this wave's half of the rows: keys for wave 0, values for wave 1
@@ -241,11 +267,15 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
     for (int j = 0; j < 4; ++j)
       *reinterpret_cast<uint4*>(x_lds + buf * kMlpWaveLds + (4 * j + r) * kMlpRowStride + half * 256 + c * 16) = xx[j];
   };
-  auto issue_products = [&](f32x4_t (&acc)[MTW], int buf) {
+  float prev = 0.f;   // wave 0: its own partial sums of the tile before this one
+  // One step: products, activation and output layer of tile i; store of tile i - 1 (wave 0 adds the partner's
+  // partial sums, which barrier i - 1 made visible); staging of tile i + 1, whose registers then fetch tile i + 3;
+  // barrier i.
+  auto step = [&](uint4 (&x_next)[4], int i) {
+    f32x4_t acc[MTW];
 #pragma unroll
-    for (int mw = 0; mw < MTW; ++mw)
-      acc[mw] = *reinterpret_cast<const f32x4_t*>(par_lds + half * HW + mw * 16 + 4 * r);   // bias
-    const unsigned char* xt = x_lds + buf * kMlpWaveLds;
+    for (int mw = 0; mw < MTW; ++mw) acc[mw] = b1r[mw];
+    const unsigned char* xt = x_lds + (i & 1) * kMlpWaveLds;
 #pragma unroll
     for (int ks = 0; ks < kMlpKSteps; ++ks) {
       const uint4 x = *reinterpret_cast<const uint4*>(xt + c * kMlpRowStride + ks * 64 + r * 16);
@@ -254,38 +284,21 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
       for (int mw = 0; mw < MTW; ++mw)
         acc[mw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfrag[mw][ks], xv, acc[mw], 0, 0, 0);
     }
-  };
-  float held_prev = 0.f, held = 0.f;   // wave 0: its own partial sums of the two latest finished tiles
-  auto finish_tile = [&](const f32x4_t (&acc)[MTW], int t) {   // activation and output layer of tile t
+    if (half == 0 && i >= 1) {
+      const int row = block_row0 + 16 * (i - 1) + c;
+      if (r == 0 && row < T) out[row] = prev + sum_lds[((i - 1) & 1) * 16 + c] + bias2;
+    }
     float part = 0.f;
 #pragma unroll
-    for (int mw = 0; mw < MTW; ++mw) {
-      const f32x4_t wo = *reinterpret_cast<const f32x4_t*>(par_lds + 2 * HW + half * HW + mw * 16 + 4 * r);
+    for (int mw = 0; mw < MTW; ++mw)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) part = fmaf(wo[e], activation<kAct>(acc[mw][e]), part);
-    }
-    part += __shfl_xor(part, 16, 64);
-    part += __shfl_xor(part, 32, 64);
+      for (int e = 0; e < 4; ++e) part = fmaf(w2r[mw][e], activation<kAct>(acc[mw][e]), part);
+    part = sum_over_feature_blocks(part);
     if (half == 1) {
-      if (r == 0) sum_lds[(t & 1) * 16 + c] = part;
+      if (r == 0) sum_lds[(i & 1) * 16 + c] = part;
     } else {
-      held_prev = held;
-      held = part;
+      prev = part;
     }
-  };
-  auto store_tile = [&](int t, float mine) {   // wave 0: add the partner's partial sum of tile t and store
-    const int row = block_row0 + 16 * t + c;
-    if (half == 0 && r == 0 && row < T) out[row] = mine + sum_lds[(t & 1) * 16 + c] + bias2;
-  };
-
-  // Barrier i makes tile i visible; it also means both waves have finished reading tile i - 1 and
-  // have written the partial sums of tile i - 2.  One step: products of tile i, epilogue of tile
-  // i - 1, store of tile i - 2, staging of tile i + 1 (fetching tile i + 3 behind it), barrier i + 1.
-  f32x4_t acc_a[MTW], acc_b[MTW];
-  auto step = [&](f32x4_t (&acc_new)[MTW], const f32x4_t (&acc_old)[MTW], uint4 (&x_next)[4], int i) {
-    issue_products(acc_new, i & 1);
-    finish_tile(acc_old, i - 1);
-    if (i >= 2) store_tile(i - 2, held_prev);
     if (i + 1 < n_tiles) {
       stage_half(x_next, (i + 1) & 1);
       if (i + 3 < n_tiles) load_half(x_next, i + 3);
@@ -296,25 +309,16 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   if (1 < n_tiles) load_half(xb, 1);
   stage_half(xa, 0);
   if (2 < n_tiles) load_half(xa, 2);
-  __syncthreads();   // tile 0 and b1 / w2 are in LDS
-  issue_products(acc_a, 0);
-  if (1 < n_tiles) {
-    stage_half(xb, 1);
-    if (3 < n_tiles) load_half(xb, 3);
-  }
-  __syncthreads();
+  __syncthreads();   // tile 0 is in LDS
 #pragma unroll 1
-  for (int i = 1; i < n_tiles; i += 2) {
-    step(acc_b, acc_a, xa, i);                               // stages the even tile i + 1
-    if (i + 1 < n_tiles) step(acc_a, acc_b, xb, i + 1);      // uniform condition around the barrier
+  for (int i = 0; i < n_tiles; i += 2) {
+    step(xb, i);                               // stages the odd tile i + 1
+    if (i + 1 < n_tiles) step(xa, i + 1);      // uniform condition around the barrier
   }
-  // drain: the last tile's epilogue, one more barrier for its partial sums, then the last two stores
-  const int last = n_tiles - 1;
-  if (last & 1) finish_tile(acc_b, last);
-  else finish_tile(acc_a, last);
-  __syncthreads();
-  if (last >= 1) store_tile(last - 1, held_prev);
-  store_tile(last, held);
+  if (half == 0) {
+    const int row = block_row0 + 16 * (n_tiles - 1) + c;
+    if (r == 0 && row < T) out[row] = prev + sum_lds[((n_tiles - 1) & 1) * 16 + c] + bias2;
+  }
 }
 
 int score_mlp_rows_per_block(int T, int heads, int hidden) {

@@ -379,8 +379,8 @@ def lkv_plan_offsets(ctx: Context, budgets, offsets, stream=None) -> int:
 
 def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int, scorer: dict, budgets, offsets,
                     scores: Sequence, idx, kp, vp, stream=None) -> None:
-    """layer: a Cache built from per-sequence tensors [1, H, T_s, 128]; budgets: host int32
-    [n_seq * n_layers * H]; scores: per-sequence GPU fp32 [H, T_s] scratch."""
+    """layer: a Cache built from per-sequence tensors [m, H, T_s, 128] of m consecutive layers starting at
+    layer_index; budgets: host int32 [n_seq * n_layers * H]; scores: per-sequence GPU fp32 [m, H, T_s] scratch."""
     import numpy as np
 
     b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))

@@ -96,6 +96,9 @@ CONFIGS = (
     # on the Llama-3.1-8B cache shape of its App. C.1
     Workload(5, "paper-L32-H8-T32768-mlp128silu-per-head", 1, 32, 8, 32, 32768, "mlp", 128, "silu", 0.15, 0.5, 64,
              per_head=True, out_bias=False),
+    # the same scorer on the other model shape of App. C.1 (36 layers x 8 KV heads: 288 scorers, Table 5)
+    Workload(6, "paper-L36-H8-T32768-mlp128silu-per-head", 1, 36, 8, 32, 32768, "mlp", 128, "silu", 0.15, 0.5, 64,
+             per_head=True, out_bias=False),
 )
 
 

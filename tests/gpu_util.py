@@ -151,21 +151,24 @@ class LayerwiseRun(GpuRun):
     """Same buffers, but the packed cache is built one layer at a time (lkv_plan_offsets, then
     lkv_evict_layer per layer, optionally in a shuffled layer order and on a side stream)."""
 
-    def evict_layerwise(self, order=None, stream=None):
+    def evict_layerwise(self, order=None, stream=None, layers_per_call=1):
+        """`order`: the first layer of every call (default: 0, m, 2m, ...); a call covers up to
+        `layers_per_call` layers from there (fewer at the end of the model)."""
         c = self.cache
         planned = lkv.lkv_plan_offsets(self.ctx, self.budgets, self.offsets, stream=stream)
         assert planned == self.total
-        scratch = [torch.empty((c.H, t), dtype=torch.float32, device="cuda") for t in c.seq_len]
-        for l in (range(c.L) if order is None else order):
-            view = lkv.Cache([k[l:l + 1] for k in self.k], [v[l:l + 1] for v in self.v], c.Hq)
+        for l in (range(0, c.L, layers_per_call) if order is None else order):
+            m = min(layers_per_call, c.L - l)
+            scratch = [torch.empty((m, c.H, t), dtype=torch.float32, device="cuda") for t in c.seq_len]
+            view = lkv.Cache([k[l:l + m] for k in self.k], [v[l:l + m] for v in self.v], c.Hq)
             lkv.lkv_evict_layer(self.ctx, view, l, c.L, self.scorer, self.budgets, self.offsets, scratch, self.idx,
                                 self.kp, self.vp, stream=stream)
             for s in range(c.n_seq):      # keep the scores for the comparison with the oracle
                 if stream is not None:
                     with torch.cuda.stream(stream):
-                        self.scores[s][l].copy_(scratch[s])
+                        self.scores[s][l:l + m].copy_(scratch[s])
                 else:
-                    self.scores[s][l].copy_(scratch[s])
+                    self.scores[s][l:l + m].copy_(scratch[s])
 
     def run_all(self, order=None, stream=None):
         self.evict_layerwise(order, stream)

@@ -66,6 +66,26 @@ def test_layerwise_long_heads_use_the_uncached_select(ctx):
     _both_ways(ctx, w, [40000], seed=1, what="T=40000")
 
 
+@pytest.mark.parametrize("scorer,hidden,per_head", [("linear", 0, False), ("mlp", 48, True), ("mlp", 128, True)])
+def test_several_layers_per_call(ctx, scorer, hidden, per_head):
+    # views of 1, 2 and 3 consecutive layers (7 layers: 3 + 3 + 1, then 2 + 2 + 2 + 1), in any order of the calls
+    w = W.scaled(W.CONFIGS[0], n_seq=2, L=7, H=3, Hq=6, scorer=scorer, hidden=hidden, act="silu", per_head=per_head, b_min=4)
+    K, V, Q, sc, B = _inputs(w, [900, 333], seed=9)
+    whole = G.GpuRun(ctx, K, V, Q, sc, B, w.Hq)
+    whole.run_all()
+    for m, starts in ((3, [6, 0, 3]), (2, [4, 6, 0, 2])):
+        lay = G.LayerwiseRun(ctx, K, V, Q, sc, B, w.Hq)
+        lay.evict_layerwise(order=starts, layers_per_call=m)
+        lay.decode()
+        torch.cuda.synchronize()
+        G.check_against_oracle(lay, K, V, Q, sc, B, f"{m} layers per call")
+        n = whole.total
+        assert torch.equal(lay.offsets, whole.offsets) and torch.equal(lay.idx[:n], whole.idx[:n])
+        assert torch.equal(lay.kp[:n].view(torch.int16), whole.kp[:n].view(torch.int16))
+        assert torch.equal(lay.vp[:n].view(torch.int16), whole.vp[:n].view(torch.int16))
+        assert torch.equal(lay.out, whole.out)
+
+
 def test_layerwise_argument_errors(ctx):
     w = W.scaled(W.CONFIGS[0], L=3, H=2, Hq=4, b_min=4)
     K, V, Q, sc, B = _inputs(w, [256])
@@ -77,8 +97,8 @@ def test_layerwise_argument_errors(ctx):
         with pytest.raises(lkv.LkvError) as e:
             lkv.lkv_evict_layer(ctx, view, layer, w.L, run.scorer, run.budgets, run.offsets, scratch, run.idx, run.kp, run.vp)
         assert e.value.status == 1
-    with pytest.raises(lkv.LkvError) as e:      # a view with more than one layer
-        lkv.lkv_evict_layer(ctx, run.cache, 0, w.L, run.scorer, np.tile(run.budgets, 1), run.offsets,
+    with pytest.raises(lkv.LkvError) as e:      # a view of three layers that starts at layer 1 of three
+        lkv.lkv_evict_layer(ctx, run.cache, 1, w.L, run.scorer, run.budgets, run.offsets,
                             [torch.empty((w.L, w.H, 256), dtype=torch.float32, device="cuda")], run.idx, run.kp, run.vp)
     assert e.value.status == 1
     bad = run.budgets.copy(); bad[1] = 257
