@@ -79,6 +79,9 @@ def parse():
     ap.add_argument("--budgets", choices=("recipe", "lkvh"), default="recipe",
                     help="per-head budgets: the seeded recipe of the workload, or LKV-H computed on the GPU")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--plain-select", action="store_true",
+                    help="never let the scoring kernel count for the top-k (default: it does for the MLP scorers, whose "
+                         "kernels count at no cost; lkv_score_counted / lkv_select_counted)")
     ap.add_argument("--decode-per-layer", action="store_true",
                     help="also time the decode as one launch per layer (single-sequence workloads); adds the key "
                          "`decode_per_layer_launches`")
@@ -101,6 +104,10 @@ def parse():
                          "traffic for scaling hardware byte counters under rocprofv3 --pmc)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="time cap of the oracle sample")
     return ap.parse_args()
+
+
+def count_in_scorer(w, args):
+    return w.scorer == "mlp" and w.hidden <= 64 and not args.plain_select
 
 
 def to_dev(a, dev, bf16=False):
@@ -129,7 +136,8 @@ def run_workload(ctx, lkv, W, w, args, dev, headline):
         shapes = [tuple(int(x) for x in sh.split(",")) for sh in (args.layerwise_shape or ["2,1", "4,1", "2,4"])]
         layerwise_result = []
         for n_streams, per_call in shapes:
-            layerwise_result.append(layerwise(ctx, lkv, W, w, scorer, dev, n_streams, per_call))
+            layerwise_result.append(layerwise(ctx, lkv, W, w, scorer, dev, n_streams, per_call,
+                                              counted=count_in_scorer(w, args)))
             torch.cuda.empty_cache()
 
     # ---- inputs, resident in HBM before the timed region --------------------------------
@@ -186,11 +194,25 @@ def run_workload(ctx, lkv, W, w, args, dev, headline):
     plan_us = (time.perf_counter() - t0) * 1e6
     assert planned == total
 
+    # MLP scorers up to 64 hidden units: the scoring kernel counts the first radix level of the top-k on its way out
+    # (free there: the kernel waits for HBM; the wider scorer is bound by instruction issue and pays 3 % for it)
+    counted = count_in_scorer(w, args)
+    counts = None
+    if counted:
+        counts = torch.empty((cache.n_segments, 2048), dtype=torch.int32, device=dev)
+        lkv.lkv_clear_counts(ctx, counts, cache.n_segments)      # once: every select leaves the counters zero again
+
     def step(ev=None):
         if ev: ev[0].record()
-        lkv.lkv_score(ctx, cache, scorer, scores)
+        if counted:
+            lkv.lkv_score_counted(ctx, cache, scorer, scores, counts)
+        else:
+            lkv.lkv_score(ctx, cache, scorer, scores)
         if ev: ev[1].record()
-        lkv.lkv_select(ctx, cache, scores, None, idx, offsets)
+        if counted:
+            lkv.lkv_select_counted(ctx, cache, scores, None, counts, idx, offsets)
+        else:
+            lkv.lkv_select(ctx, cache, scores, None, idx, offsets)
         if ev: ev[2].record()
         lkv.lkv_compact(ctx, cache, idx, offsets, total, kp, vp)
         if ev: ev[3].record()
@@ -235,7 +257,8 @@ def run_workload(ctx, lkv, W, w, args, dev, headline):
                    "retention": rho, "scorer": w.scorer if w.scorer == "linear" else f"mlp256-{w.hidden}-{w.act}",
                    "budgets": "lkv-h on the GPU" if args.budgets == "lkvh" else "seeded recipe",
                    "offsets": "planned once before the timed region (budgets are static); lkv_select reads them from the device",
-                   "plan_offsets_us": plan_us},
+                   "plan_offsets_us": plan_us,
+                   "top_k_first_level": "counted by the scoring kernel" if counted else "counted by the top-k kernel"},
         "phases_ms": {"score": t_score, "select": t_select, "compact": t_compact, "decode": t_decode,
                       "evict": t_evict, "step_gpu": float(ph.sum(axis=1).mean())},
         "evict": {"bytes": evict_bytes, "GBps": evict_bytes / (t_evict * 1e6),
@@ -576,7 +599,7 @@ def growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total
             "reevict_ms": t_reevict, "reevict_kept": total2, "reevict_GBps": re_bytes / (t_reevict * 1e6)}
 
 
-def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, reps=3):
+def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, counted=False, reps=3):
     """Layer-by-layer eviction during prefill (Sec. 1): a stand-in producer fills the K/V of the next
     `layers_per_call` layers on one stream (it takes the place of the prefill compute), the eviction of
     earlier layers runs on `n_streams` other streams in turn; n_streams buffers of layers_per_call layers
@@ -609,6 +632,11 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, reps=
     kp = torch.empty((total, w.d), dtype=torch.bfloat16, device=dev)
     vp = torch.empty_like(kp)
     s_fill, s_evicts = torch.cuda.Stream(), [torch.cuda.Stream() for _ in range(n_streams)]
+    counts = None
+    if counted:
+        counts = torch.empty((n_seg, 2048), dtype=torch.int32, device=dev)
+        lkv.lkv_clear_counts(ctx, counts, n_seg)
+        torch.cuda.synchronize()
 
     def fill(slot):
         for t in ring[slot][0] + ring[slot][1]:
@@ -641,7 +669,7 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, reps=
                     s_evict.wait_event(filled[i])
                 started[i].record(s_evict)
                 lkv.lkv_evict_layer(ctx, views[(slot, nl)], l, w.L, scorer, budgets, offsets,
-                                    [t[:nl] for t in scratch[slot]], idx, kp, vp, stream=s_evict)
+                                    [t[:nl] for t in scratch[slot]], idx, kp, vp, stream=s_evict, counts=counts)
                 evicted[i].record(s_evict)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
@@ -659,6 +687,7 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, reps=
     N = sum(w.L * w.H * T for T in Ts)
     gbps = (N * 520 + total * 1032) / (evict_only * 1e6)
     return {"eviction_streams": n_streams, "layers_per_call": m, "layer_buffers_alive": n_streams * m,
+            "top_k_first_level": "counted by the scoring kernel" if counted else "counted by the top-k kernel",
             "ms_producer_and_eviction": both, "ms_producer_alone": produce_only, "ms_eviction_alone": evict_only,
             "ms_per_call_eviction": per_call,
             "evict_GBps_eviction_alone": gbps, "evict_frac_of_peak_eviction_alone": gbps / HBM_PEAK_GBS,

@@ -183,6 +183,27 @@ lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *co
 lkv_status lkv_select(lkv_ctx *ctx, const lkv_cache *cache, const float *const *scores,
                       const int32_t *budgets, int32_t *idx, int32_t *offsets, void *stream);
 
+/* ---- Scoring that counts for the top-k -------------------------------------------------------
+ * The top-k finds its threshold by a radix descent over the score bits; the first level looks at
+ * the top 11 bits of every score.  lkv_score_counted writes the same scores as lkv_score and, on
+ * the way, counts those 11-bit digits per segment (inside the scoring kernel for the MLP scorers;
+ * by one extra pass over the scores, 4 bytes per token, for the linear scorer).
+ * lkv_select_counted then starts from the counts instead of from a pass over the scores: heads too
+ * long for the top-k's on-chip key cache (more than 34304 tokens) are read twice instead of three
+ * times, shorter ones skip the counting.  Same result as lkv_select, bit for bit.
+ * counts : DEVICE uint32 [n_seq * L * H, 2048], 16-byte aligned, lkv_counts_bytes(n_segments) bytes.
+ *          Must be all zero when lkv_score_counted is called; lkv_select_counted reads every
+ *          segment's counters and leaves them zero again, so a buffer cleared once with
+ *          lkv_clear_counts serves any number of score / select pairs.  The two calls must see the
+ *          same cache geometry and the scores must not change in between. */
+size_t lkv_counts_bytes(int64_t n_segments);
+lkv_status lkv_clear_counts(lkv_ctx *ctx, uint32_t *counts, int64_t n_segments, void *stream);
+lkv_status lkv_score_counted(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *scorer,
+                             float *const *scores, uint32_t *counts, void *stream);
+lkv_status lkv_select_counted(lkv_ctx *ctx, const lkv_cache *cache, const float *const *scores,
+                              const int32_t *budgets, uint32_t *counts, int32_t *idx, int32_t *offsets,
+                              void *stream);
+
 /* Compaction into the padding-free ragged cache (Sec. 4.5: the compressed
  * cache is flattened so that no padding is stored).
  *   kp[offsets[s] + j, :] = K[seq, l, h, idx[offsets[s] + j], :]   (same for vp / V)
@@ -264,10 +285,15 @@ lkv_status lkv_plan_offsets(lkv_ctx *ctx, int64_t n_segments, const int32_t *bud
  * offsets     : DEVICE int32 [n_seq * n_layers * H + 1] written by lkv_plan_offsets
  * scores      : HOST [n_seq] of DEVICE fp32 [m, H, T_s]: scratch, overwritten (an input when scorer is NULL)
  * idx         : DEVICE int32 [total_kept], the global index buffer (the view's part is written)
- * kp, vp      : DEVICE bf16 [total_kept, d], the global packed cache (the view's rows are written) */
+ * kp, vp      : DEVICE bf16 [total_kept, d], the global packed cache (the view's rows are written)
+ * counts      : NULL, or DEVICE uint32 [n_seq * n_layers * H, 2048] as for lkv_score_counted (all zero
+ *               on entry, left zero): the scoring then counts for the top-k.  Ignored when scorer is NULL.
+ *               Calls that run at the same time on different streams touch different segments'
+ *               counters, so they can share the buffer. */
 lkv_status lkv_evict_layer(lkv_ctx *ctx, const lkv_cache *layer, int32_t layer_index, int32_t n_layers,
                            const lkv_scorer *scorer, const int32_t *budgets, const int32_t *offsets,
-                           float *const *scores, int32_t *idx, void *kp, void *vp, void *stream);
+                           float *const *scores, int32_t *idx, void *kp, void *vp, uint32_t *counts,
+                           void *stream);
 
 /* ---- Decode-time growth of the packed cache -----------------------------------------------
  * The paper evicts during prefill (Sec. 1), lets step t attend every cached token up to t (Eq. 1)

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblkv.so")
-SOURCES = ["lkv_api.hip", "score_linear.hip", "score_mlp.hip", "score_window.hip", "select.hip", "compact.hip", "decode.hip", "lkv_h.hip", "append.hip",
+SOURCES = ["lkv_api.hip", "score_linear.hip", "score_mlp.hip", "score_window.hip", "select.hip", "counts.hip", "compact.hip", "decode.hip", "lkv_h.hip", "append.hip",
            "masked_attn.hip", "masked_attn_bwd.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -134,6 +134,79 @@ lkv_status check_attention_geometry(lkv_ctx* ctx, int32_t n_q_heads, int32_t n_k
 
 hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
+// lkv_score, optionally counting the first-level top-k digits of every segment on the way (counts zero on entry).
+// The segment of (sequence s, view head j) is seg_base + s * seg_stride + j.
+lkv_status score_impl(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* scorer, float* const* scores,
+                      uint32_t* counts, int seg_base, int seg_stride, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (lkv_status st = check_cache(ctx, cache, true)) return st;
+  if (scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores is NULL");
+  if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
+  const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
+  for (int s = 0; s < cache->n_seq; ++s) {
+    if (scores[s] == nullptr || !aligned16(scores[s]))
+      return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL or not 16-byte aligned", s);
+  }
+  const int heads_per_row = scorer->per_head ? 1 : cache->n_kv_heads;
+  hipStream_t st = as_stream(stream);
+
+  // launches of up to kMaxSeqPerLaunch sequences; MLP launches also need one tile size per launch
+  int s = 0;
+  while (s < cache->n_seq) {
+    lkv::SeqTable tab;
+    memset(&tab, 0, sizeof(tab));
+    int64_t blocks = 0;
+    const int s_first = s;
+    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s], (int)heads, scorer->hidden) : 0;
+    int n = 0;
+    while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
+      const int T = cache->seq_len[s];
+      int64_t per_head;
+      if (scorer->kind == LKV_SCORER_MLP) {
+        if (lkv::score_mlp_rows_per_block(T, (int)heads, scorer->hidden) != rpb0) break;
+        per_head = (T + rpb0 - 1) / rpb0;
+      } else {
+        per_head = lkv::score_linear_blocks_per_head(T);
+      }
+      if (blocks + per_head * heads >= ((int64_t)1 << 31) - 1) {
+        if (n == 0) return fail(ctx, LKV_ERR_UNSUPPORTED, "sequence %d is too long for one launch", s);
+        break;
+      }
+      tab.k[n] = static_cast<const uint16_t*>(cache->k[s]);
+      tab.v[n] = static_cast<const uint16_t*>(cache->v[s]);
+      tab.scores[n] = scores[s];
+      tab.T[n] = T;
+      tab.first[n] = (int32_t)blocks;
+      blocks += per_head * heads;
+      ++n;
+      ++s;
+    }
+    tab.first[n] = (int32_t)blocks;
+    tab.n = n;
+    const int launch_seg_base = seg_base + s_first * seg_stride;
+    if (scorer->kind == LKV_SCORER_LINEAR) {
+      lkv::launch_score_linear(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, heads_per_row, st);
+      if (counts != nullptr) {
+        // the linear kernel's blocks are too small to carry a histogram: a pass over the scores counts instead
+        if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_score launch");
+        int64_t cblocks = 0;
+        for (int i = 0; i < n; ++i) {
+          tab.first[i] = (int32_t)cblocks;
+          cblocks += heads * lkv::count_level0_blocks_per_head(tab.T[i]);
+        }
+        tab.first[n] = (int32_t)cblocks;
+        lkv::launch_count_level0(tab, counts, launch_seg_base, seg_stride, st);
+      }
+    } else {
+      lkv::launch_score_mlp(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, scorer->w2, scorer->b2,
+                            scorer->hidden, scorer->act == LKV_ACT_SILU ? 0 : 1, heads_per_row, rpb0, st, counts,
+                            launch_seg_base, seg_stride);
+    }
+    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_score launch");
+  }
+  return LKV_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -183,58 +256,27 @@ const char* lkv_last_error(const lkv_ctx* ctx) { return ctx != nullptr ? ctx->er
 
 lkv_status lkv_score(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* scorer, float* const* scores,
                      void* stream) {
-  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
-  if (lkv_status st = check_cache(ctx, cache, true)) return st;
-  if (scores == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores is NULL");
-  if (lkv_status st = check_scorer(ctx, scorer, true)) return st;
-  const int64_t heads = (int64_t)cache->n_layers * cache->n_kv_heads;
-  for (int s = 0; s < cache->n_seq; ++s) {
-    if (scores[s] == nullptr || !aligned16(scores[s]))
-      return fail(ctx, LKV_ERR_INVALID_ARG, "scores[%d] is NULL or not 16-byte aligned", s);
-  }
-  const int heads_per_row = scorer->per_head ? 1 : cache->n_kv_heads;
-  hipStream_t st = as_stream(stream);
+  return score_impl(ctx, cache, scorer, scores, nullptr, 0, 0, stream);
+}
 
-  // launches of up to kMaxSeqPerLaunch sequences; MLP launches also need one tile size per launch
-  int s = 0;
-  while (s < cache->n_seq) {
-    lkv::SeqTable tab;
-    memset(&tab, 0, sizeof(tab));
-    int64_t blocks = 0;
-    const int rpb0 = scorer->kind == LKV_SCORER_MLP ? lkv::score_mlp_rows_per_block(cache->seq_len[s], (int)heads, scorer->hidden) : 0;
-    int n = 0;
-    while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
-      const int T = cache->seq_len[s];
-      int64_t per_head;
-      if (scorer->kind == LKV_SCORER_MLP) {
-        if (lkv::score_mlp_rows_per_block(T, (int)heads, scorer->hidden) != rpb0) break;
-        per_head = (T + rpb0 - 1) / rpb0;
-      } else {
-        per_head = lkv::score_linear_blocks_per_head(T);
-      }
-      if (blocks + per_head * heads >= ((int64_t)1 << 31) - 1) {
-        if (n == 0) return fail(ctx, LKV_ERR_UNSUPPORTED, "sequence %d is too long for one launch", s);
-        break;
-      }
-      tab.k[n] = static_cast<const uint16_t*>(cache->k[s]);
-      tab.v[n] = static_cast<const uint16_t*>(cache->v[s]);
-      tab.scores[n] = scores[s];
-      tab.T[n] = T;
-      tab.first[n] = (int32_t)blocks;
-      blocks += per_head * heads;
-      ++n;
-      ++s;
-    }
-    tab.first[n] = (int32_t)blocks;
-    tab.n = n;
-    if (scorer->kind == LKV_SCORER_LINEAR) {
-      lkv::launch_score_linear(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, heads_per_row, st);
-    } else {
-      lkv::launch_score_mlp(tab, static_cast<const uint16_t*>(scorer->w1), scorer->b1, scorer->w2, scorer->b2,
-                            scorer->hidden, scorer->act == LKV_ACT_SILU ? 0 : 1, heads_per_row, rpb0, st);
-    }
-    if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_score launch");
-  }
+lkv_status lkv_score_counted(lkv_ctx* ctx, const lkv_cache* cache, const lkv_scorer* scorer, float* const* scores,
+                             uint32_t* counts, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (counts == nullptr || !aligned16(counts)) return fail(ctx, LKV_ERR_INVALID_ARG, "counts is NULL or not 16-byte aligned");
+  if (cache == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "cache is NULL");
+  return score_impl(ctx, cache, scorer, scores, counts, 0, cache->n_layers * cache->n_kv_heads, stream);
+}
+
+size_t lkv_counts_bytes(int64_t n_segments) {
+  return n_segments > 0 ? (size_t)n_segments * lkv::kLevel0Bins * sizeof(uint32_t) : 0;
+}
+
+lkv_status lkv_clear_counts(lkv_ctx* ctx, uint32_t* counts, int64_t n_segments, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (counts == nullptr || !aligned16(counts)) return fail(ctx, LKV_ERR_INVALID_ARG, "counts is NULL or not 16-byte aligned");
+  if (n_segments < 1 || n_segments > kMaxSegments) return fail(ctx, LKV_ERR_INVALID_ARG, "n_segments = %lld is out of range", (long long)n_segments);
+  lkv::launch_clear_counts(counts, n_segments, as_stream(stream));
+  if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_clear_counts launch");
   return LKV_OK;
 }
 
@@ -349,12 +391,8 @@ lkv_status take_stage_slot(lkv_ctx* ctx, hipStream_t st, const char* who, int* s
   return LKV_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
-                      int32_t* idx, int32_t* offsets, void* stream) {
+lkv_status select_impl(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
+                       uint32_t* counts, int32_t* idx, int32_t* offsets, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, cache, false)) return st;
   if (scores == nullptr || offsets == nullptr) return fail(ctx, LKV_ERR_INVALID_ARG, "scores or offsets is NULL");
@@ -419,10 +457,27 @@ lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* 
     }
     tab.first[n] = n * heads;
     tab.n = n;
-    lkv::launch_select(tab, inline_offsets ? host_off : nullptr, (int)n_seg, offsets, idx, s0 * heads, heads, st);
+    lkv::launch_select(tab, inline_offsets ? host_off : nullptr, (int)n_seg, offsets, idx, s0 * heads, heads, st, nullptr,
+                       nullptr, nullptr, counts);
     if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_select launch");
   }
   return LKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+lkv_status lkv_select(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
+                      int32_t* idx, int32_t* offsets, void* stream) {
+  return select_impl(ctx, cache, scores, budgets, nullptr, idx, offsets, stream);
+}
+
+lkv_status lkv_select_counted(lkv_ctx* ctx, const lkv_cache* cache, const float* const* scores, const int32_t* budgets,
+                              uint32_t* counts, int32_t* idx, int32_t* offsets, void* stream) {
+  if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
+  if (counts == nullptr || !aligned16(counts)) return fail(ctx, LKV_ERR_INVALID_ARG, "counts is NULL or not 16-byte aligned");
+  return select_impl(ctx, cache, scores, budgets, counts, idx, offsets, stream);
 }
 
 lkv_status lkv_compact(lkv_ctx* ctx, const lkv_cache* cache, const int32_t* idx, const int32_t* offsets,
@@ -541,9 +596,10 @@ lkv_status lkv_plan_offsets(lkv_ctx* ctx, int64_t n_segments, const int32_t* bud
 
 lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_index, int32_t n_layers,
                            const lkv_scorer* scorer, const int32_t* budgets, const int32_t* offsets,
-                           float* const* scores, int32_t* idx, void* kp, void* vp, void* stream) {
+                           float* const* scores, int32_t* idx, void* kp, void* vp, uint32_t* counts, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, layer, true)) return st;
+  if (counts != nullptr && !aligned16(counts)) return fail(ctx, LKV_ERR_INVALID_ARG, "counts is not 16-byte aligned");
   const int m = layer->n_layers;   // consecutive layers in the view
   if (n_layers < 1 || layer_index < 0 || layer_index > n_layers - m)
     return fail(ctx, LKV_ERR_INVALID_ARG, "layers %d .. %d of the view are outside [0, %d)", layer_index, layer_index + m - 1,
@@ -593,7 +649,9 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
       sl.w2 = scorer->w2 + rows * scorer->hidden;
       sl.b2 = scorer->b2 != nullptr ? scorer->b2 + rows : nullptr;
     }
-    if (lkv_status st = lkv_score(ctx, layer, &sl, scores, stream)) return st;
+    if (lkv_status st = score_impl(ctx, layer, &sl, scores, counts, layer_index * H, heads_all, stream)) return st;
+  } else {
+    counts = nullptr;   // the scores came from elsewhere: nothing has counted them
   }
 
   hipStream_t st = as_stream(stream);
@@ -609,7 +667,8 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   tab.first[layer->n_seq] = layer->n_seq * m * H;
   tab.n = layer->n_seq;
   // select: segment of (sequence i, view head j) is i * n_layers * H + layer_index * H + j, offsets already on the device
-  lkv::launch_select(tab, nullptr, (int)n_seg, const_cast<int32_t*>(offsets), idx, layer_index * H, heads_all, st);
+  lkv::launch_select(tab, nullptr, (int)n_seg, const_cast<int32_t*>(offsets), idx, layer_index * H, heads_all, st, nullptr,
+                     nullptr, nullptr, counts);
   if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer select launch");
   // compact: one contiguous row range per sequence
   for (int i = 0; i < layer->n_seq; ++i) {

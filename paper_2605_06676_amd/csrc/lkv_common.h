@@ -44,6 +44,31 @@ struct WinTable {
   int32_t n;
 };
 
+// Order-preserving key of a score: unsigned comparison of keys is the comparison of the scores, with NaN ranked
+// as -inf and -0.0 below +0.0 (the total order of the fp32 bit patterns).
+__device__ __forceinline__ uint32_t order_key(float u) {
+  uint32_t bits = __float_as_uint(u);
+  if ((bits & 0x7fffffffu) > 0x7f800000u) bits = 0xff800000u;   // NaN ranks as -inf
+  return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+}
+
+// First level of the top-k's radix descent: the top 11 bits of the key.  A scoring launch can count them per
+// segment on the way out (`counts`: uint32 [segments][kLevel0Bins], zero before the launch), which saves the
+// top-k one pass over the scores.
+constexpr int kLevel0Bins = 2048;
+constexpr int kLevel0Shift = 21;
+
+// Adds a block's LDS histogram of first-level digits to the segment's global one.  Most bins are empty (scores of
+// one head span a few dozen quarter-octaves), so only the occupied ones cost an atomic.
+__device__ __forceinline__ void flush_level0_counts(const uint32_t* hist_lds, uint32_t* __restrict__ counts, size_t seg,
+                                                    int n_threads) {
+  uint32_t* dst = counts + seg * kLevel0Bins;
+  for (int i = threadIdx.x; i < kLevel0Bins; i += n_threads) {
+    const uint32_t v = hist_lds[i];
+    if (v != 0) atomicAdd(dst + i, v);
+  }
+}
+
 // Index of the sequence that owns work unit `unit`.  `unit` is wave-uniform,
 // so this runs on the scalar unit.
 __device__ __forceinline__ int seq_of_unit(const SeqTable& tab, int unit) {

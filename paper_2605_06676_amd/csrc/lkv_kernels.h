@@ -14,7 +14,7 @@ int score_linear_blocks_per_head(int T);
 hipError_t score_mlp_prepare();
 void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
                       const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
-                      hipStream_t stream);
+                      hipStream_t stream, uint32_t* counts = nullptr, int seg_base = 0, int seg_stride = 0);
 int score_mlp_rows_per_block(int T, int heads, int hidden);
 
 // score_window.hip
@@ -31,7 +31,12 @@ int select_inline_capacity();
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
                    int32_t* idx, int seg_base, int seg_stride, hipStream_t stream,
                    const float* ragged_scores = nullptr, const int32_t* ragged_start = nullptr,
-                   const int32_t* ragged_len = nullptr);
+                   const int32_t* ragged_len = nullptr, uint32_t* counts = nullptr);
+
+// counts.hip
+void launch_clear_counts(uint32_t* counts, int64_t n_segments, hipStream_t stream);
+void launch_count_level0(const SeqTable& tab, uint32_t* counts, int seg_base, int seg_stride, hipStream_t stream);
+int count_level0_blocks_per_head(int T);
 
 // compact.hip
 void launch_compact(const SeqTable& tab, const int32_t* idx, const int32_t* offsets, int n_segments,

@@ -34,11 +34,13 @@ __device__ __forceinline__ bf16x8_t as_bf16x8(const uint4& p) {
 }
 
 // Hidden widths up to 64: one wave multiplies a tile by the whole W1 (128 registers), two waves per SIMD.
-template <int MT, int kAct>
+// kCount: the block also counts the first-level top-k digits of the scores it writes (LDS histogram, added to the
+// segment's global counters at the end); segment = seg_base + sequence * seg_stride + head of the view.
+template <int MT, int kAct, bool kCount>
 __global__ void __launch_bounds__(kMlpThreads, 2)
 score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
                  const float* __restrict__ w2, const float* __restrict__ b2, int heads_per_scorer_row,
-                 int rows_per_block) {
+                 int rows_per_block, uint32_t* __restrict__ counts, int seg_base, int seg_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int HID = MT * 16;
 
@@ -70,8 +72,11 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
   // are 16-byte groups, so each is one broadcast LDS read per M tile.  Keeping them out of the
   // register file leaves room for a second prefetch buffer.
   float* par_lds = reinterpret_cast<float*>(smem + kMlpWaves * kMlpWaveLds);   // b1[HID] then w2[HID]
+  uint32_t* hist_lds = reinterpret_cast<uint32_t*>(par_lds + 2 * HID);          // [kLevel0Bins] when counting
   for (int i = threadIdx.x; i < 2 * HID; i += kMlpThreads)
     par_lds[i] = i < HID ? b1[(size_t)scorer * HID + i] : w2[(size_t)scorer * HID + i - HID];
+  if (kCount)
+    for (int i = threadIdx.x; i < kLevel0Bins; i += kMlpThreads) hist_lds[i] = 0;
   const float bias2 = b2 != nullptr ? b2[scorer] : 0.f;
   __syncthreads();
 
@@ -86,7 +91,7 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
   constexpr int kStep = kMlpWaves * kMlpTokTile;                 // 64 rows between a wave's tiles
   const int wave_row0 = tile * rows_per_block + wave * kMlpTokTile;
   const int wave_row1 = min(T, tile * rows_per_block + rows_per_block);
-  if (wave_row0 >= wave_row1) return;   // after the only block barrier
+  if (!kCount && wave_row0 >= wave_row1) return;   // after the only block barrier (a counting block has one more)
 
   // Two register buffers of 16 rows each: while one tile is multiplied, the loads of the next
   // two are in flight (16 KB per wave), which is what it takes to keep HBM busy at two waves
@@ -140,22 +145,32 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
     part += __shfl_xor(part, 16, 64);
     part += __shfl_xor(part, 32, 64);
     const int row = row0 + c;
-    if (r == 0 && row < T) out[row] = part + bias2;
+    if (r == 0 && row < T) {
+      const float u = part + bias2;
+      out[row] = u;
+      if (kCount) atomicAdd(&hist_lds[order_key(u) >> kLevel0Shift], 1u);
+    }
     wave_lds_sync();   // the next staging overwrites the tile
   };
 
-  load_tile(ka, va, wave_row0);
-  if (wave_row0 + kStep < wave_row1) load_tile(kb, vb, wave_row0 + kStep);
+  if (wave_row0 < wave_row1) {
+    load_tile(ka, va, wave_row0);
+    if (wave_row0 + kStep < wave_row1) load_tile(kb, vb, wave_row0 + kStep);
 #pragma unroll 1
-  for (int row0 = wave_row0; row0 < wave_row1; row0 += 2 * kStep) {
-    stage_tile(ka, va);
-    if (row0 + 2 * kStep < wave_row1) load_tile(ka, va, row0 + 2 * kStep);
-    multiply_tile(row0);
-    if (row0 + kStep < wave_row1) {
-      stage_tile(kb, vb);
-      if (row0 + 3 * kStep < wave_row1) load_tile(kb, vb, row0 + 3 * kStep);
-      multiply_tile(row0 + kStep);
+    for (int row0 = wave_row0; row0 < wave_row1; row0 += 2 * kStep) {
+      stage_tile(ka, va);
+      if (row0 + 2 * kStep < wave_row1) load_tile(ka, va, row0 + 2 * kStep);
+      multiply_tile(row0);
+      if (row0 + kStep < wave_row1) {
+        stage_tile(kb, vb);
+        if (row0 + 3 * kStep < wave_row1) load_tile(kb, vb, row0 + 3 * kStep);
+        multiply_tile(row0 + kStep);
+      }
     }
+  }
+  if (kCount) {
+    __syncthreads();
+    flush_level0_counts(hist_lds, counts, (size_t)(seg_base + seq * seg_stride + lh), kMlpThreads);
   }
 }
 
@@ -188,11 +203,12 @@ __device__ __forceinline__ float sum_over_feature_blocks(float x) {
 // set), a third register set for rows in flight, or no barrier at all changed nothing measurable.
 constexpr int kWideThreads = 128;
 
-template <int MTW, int kAct>
+template <int MTW, int kAct, bool kCount>
 __global__ void __launch_bounds__(kWideThreads, 2)
 score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
                       const float* __restrict__ w2, const float* __restrict__ b2, int hidden,
-                      int heads_per_scorer_row, int rows_per_block) {
+                      int heads_per_scorer_row, int rows_per_block, uint32_t* __restrict__ counts, int seg_base,
+                      int seg_stride) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int HW = MTW * 16;                      // hidden units per wave (zero padded past `hidden`)
   const int MT = hidden / 16;
@@ -213,6 +229,9 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   unsigned char* x_lds = smem;
   float* sum_lds = reinterpret_cast<float*>(smem + 2 * kMlpWaveLds);
   float* par_lds = sum_lds + 32;   // b1[2 HW] then w2[2 HW]
+  uint32_t* hist_lds = reinterpret_cast<uint32_t*>(par_lds + 4 * HW);   // [kLevel0Bins] when counting
+  if (kCount)
+    for (int i = threadIdx.x; i < kLevel0Bins; i += kWideThreads) hist_lds[i] = 0;
 
   bf16x8_t wfrag[MTW][kMlpKSteps];
   {
@@ -286,7 +305,11 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
     }
     if (half == 0 && i >= 1) {
       const int row = block_row0 + 16 * (i - 1) + c;
-      if (r == 0 && row < T) out[row] = prev + sum_lds[((i - 1) & 1) * 16 + c] + bias2;
+      if (r == 0 && row < T) {
+        const float u = prev + sum_lds[((i - 1) & 1) * 16 + c] + bias2;
+        out[row] = u;
+        if (kCount) atomicAdd(&hist_lds[order_key(u) >> kLevel0Shift], 1u);
+      }
     }
     float part = 0.f;
 #pragma unroll
@@ -317,7 +340,15 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   }
   if (half == 0) {
     const int row = block_row0 + 16 * (n_tiles - 1) + c;
-    if (r == 0 && row < T) out[row] = prev + sum_lds[((n_tiles - 1) & 1) * 16 + c] + bias2;
+    if (r == 0 && row < T) {
+      const float u = prev + sum_lds[((n_tiles - 1) & 1) * 16 + c] + bias2;
+      out[row] = u;
+      if (kCount) atomicAdd(&hist_lds[order_key(u) >> kLevel0Shift], 1u);
+    }
+  }
+  if (kCount) {
+    __syncthreads();
+    flush_level0_counts(hist_lds, counts, (size_t)(seg_base + seq * seg_stride + lh), kWideThreads);
   }
 }
 
@@ -333,48 +364,63 @@ int score_mlp_rows_per_block(int T, int heads, int hidden) {
 
 hipError_t score_mlp_prepare() { return hipSuccess; }
 
-template <int MT>
+template <int MT, bool kCount>
 static void launch_mt(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
                       const float* b2, int act, int heads_per_scorer_row, int rows_per_block,
-                      hipStream_t stream) {
+                      uint32_t* counts, int seg_base, int seg_stride, hipStream_t stream) {
   const int blocks = tab.first[tab.n];
-  const size_t lds = (size_t)kMlpWaves * kMlpWaveLds + 2 * MT * 16 * sizeof(float);
+  const size_t lds = (size_t)kMlpWaves * kMlpWaveLds + 2 * MT * 16 * sizeof(float) + (kCount ? kLevel0Bins * 4 : 0);
   if (act == kActSilu)
-    hipLaunchKernelGGL((score_mlp_kernel<MT, kActSilu>), dim3(blocks), dim3(kMlpThreads), lds, stream, tab,
-                       w1, b1, w2, b2, heads_per_scorer_row, rows_per_block);
+    hipLaunchKernelGGL((score_mlp_kernel<MT, kActSilu, kCount>), dim3(blocks), dim3(kMlpThreads), lds, stream, tab,
+                       w1, b1, w2, b2, heads_per_scorer_row, rows_per_block, counts, seg_base, seg_stride);
   else
-    hipLaunchKernelGGL((score_mlp_kernel<MT, kActGelu>), dim3(blocks), dim3(kMlpThreads), lds, stream, tab,
-                       w1, b1, w2, b2, heads_per_scorer_row, rows_per_block);
+    hipLaunchKernelGGL((score_mlp_kernel<MT, kActGelu, kCount>), dim3(blocks), dim3(kMlpThreads), lds, stream, tab,
+                       w1, b1, w2, b2, heads_per_scorer_row, rows_per_block, counts, seg_base, seg_stride);
 }
 
-template <int MTW>
+template <int MTW, bool kCount>
 static void launch_wide(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
                         const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
-                        hipStream_t stream) {
+                        uint32_t* counts, int seg_base, int seg_stride, hipStream_t stream) {
   const int blocks = tab.first[tab.n];
-  const size_t lds = (size_t)2 * kMlpWaveLds + 32 * sizeof(float) + 4 * MTW * 16 * sizeof(float);
+  const size_t lds = (size_t)2 * kMlpWaveLds + 32 * sizeof(float) + 4 * MTW * 16 * sizeof(float) + (kCount ? kLevel0Bins * 4 : 0);
   if (act == kActSilu)
-    hipLaunchKernelGGL((score_mlp_wide_kernel<MTW, kActSilu>), dim3(blocks), dim3(kWideThreads), lds, stream, tab,
-                       w1, b1, w2, b2, hidden, heads_per_scorer_row, rows_per_block);
+    hipLaunchKernelGGL((score_mlp_wide_kernel<MTW, kActSilu, kCount>), dim3(blocks), dim3(kWideThreads), lds, stream, tab,
+                       w1, b1, w2, b2, hidden, heads_per_scorer_row, rows_per_block, counts, seg_base, seg_stride);
   else
-    hipLaunchKernelGGL((score_mlp_wide_kernel<MTW, kActGelu>), dim3(blocks), dim3(kWideThreads), lds, stream, tab,
-                       w1, b1, w2, b2, hidden, heads_per_scorer_row, rows_per_block);
+    hipLaunchKernelGGL((score_mlp_wide_kernel<MTW, kActGelu, kCount>), dim3(blocks), dim3(kWideThreads), lds, stream, tab,
+                       w1, b1, w2, b2, hidden, heads_per_scorer_row, rows_per_block, counts, seg_base, seg_stride);
 }
 
-// All sequences of one launch must share rows_per_block (the host groups them so).
-void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
-                      const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
-                      hipStream_t stream) {
-  if (tab.first[tab.n] <= 0) return;
+template <bool kCount>
+static void launch_score_mlp_impl(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
+                                  const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
+                                  uint32_t* counts, int seg_base, int seg_stride, hipStream_t stream) {
+#define LKV_MLP_ARGS act, heads_per_scorer_row, rows_per_block, counts, seg_base, seg_stride, stream
   switch (hidden / 16) {
-    case 1: launch_mt<1>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 2: launch_mt<2>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 3: launch_mt<3>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 4: launch_mt<4>(tab, w1, b1, w2, b2, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 5: case 6: launch_wide<3>(tab, w1, b1, w2, b2, hidden, act, heads_per_scorer_row, rows_per_block, stream); break;
-    case 7: case 8: launch_wide<4>(tab, w1, b1, w2, b2, hidden, act, heads_per_scorer_row, rows_per_block, stream); break;
+    case 1: launch_mt<1, kCount>(tab, w1, b1, w2, b2, LKV_MLP_ARGS); break;
+    case 2: launch_mt<2, kCount>(tab, w1, b1, w2, b2, LKV_MLP_ARGS); break;
+    case 3: launch_mt<3, kCount>(tab, w1, b1, w2, b2, LKV_MLP_ARGS); break;
+    case 4: launch_mt<4, kCount>(tab, w1, b1, w2, b2, LKV_MLP_ARGS); break;
+    case 5: case 6: launch_wide<3, kCount>(tab, w1, b1, w2, b2, hidden, LKV_MLP_ARGS); break;
+    case 7: case 8: launch_wide<4, kCount>(tab, w1, b1, w2, b2, hidden, LKV_MLP_ARGS); break;
     default: break;
   }
+#undef LKV_MLP_ARGS
+}
+
+// All sequences of one launch must share rows_per_block (the host groups them so).  `counts` non-null: the launch
+// also counts the first-level top-k digits of every segment (counts zero on entry).
+void launch_score_mlp(const SeqTable& tab, const uint16_t* w1, const float* b1, const float* w2,
+                      const float* b2, int hidden, int act, int heads_per_scorer_row, int rows_per_block,
+                      hipStream_t stream, uint32_t* counts, int seg_base, int seg_stride) {
+  if (tab.first[tab.n] <= 0) return;
+  if (counts != nullptr)
+    launch_score_mlp_impl<true>(tab, w1, b1, w2, b2, hidden, act, heads_per_scorer_row, rows_per_block, counts, seg_base,
+                                seg_stride, stream);
+  else
+    launch_score_mlp_impl<false>(tab, w1, b1, w2, b2, hidden, act, heads_per_scorer_row, rows_per_block, nullptr, 0, 0,
+                                 stream);
 }
 
 }  // namespace lkv

@@ -52,12 +52,6 @@ static_assert(kSelMaxCachedKeys * 4 + 2 * ((kSelMaxCachedKeys + 31) / 32) * 4 <=
 constexpr int kSelBatch = 8;                                // loads in flight per thread
 constexpr int kSelInlineOffsets = 640;                      // offsets that fit the kernel arguments next to the launch table
 
-__device__ __forceinline__ uint32_t order_key(float u) {
-  uint32_t bits = __float_as_uint(u);
-  if ((bits & 0x7fffffffu) > 0x7f800000u) bits = 0xff800000u;   // NaN ranks as -inf
-  return (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
-}
-
 struct InlineOffsets {
   int32_t v[kSelInlineOffsets];
 };
@@ -318,9 +312,13 @@ struct SelRagged {
   const int32_t* len;
 };
 
-template <bool kInline>
+// kCounted: the first-level digits of every segment's scores have already been counted by the scoring launch
+// (`counts`: uint32 [segments][kLevel0Bins]); the block takes its histogram from there instead of from a pass over
+// the scores, and leaves the counters zero for the next scoring launch.
+template <bool kInline, bool kCounted>
 __global__ void __launch_bounds__(kSelThreads)
 select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
+              uint32_t* __restrict__ counts,
               int seg_base, int seg_stride /* global segment = seg_base + sequence * seg_stride + head */,
               int cached_limit /* heads of at most this many tokens use the LDS key cache */,
               int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */,
@@ -344,10 +342,20 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
     if (local_seg == (int)gridDim.x - 1) offsets[seg + 1] = off + budget;   // the total, by the launch's last block
   }
   int32_t* out = idx + off;
-  if (budget <= 0) return;
-  if (budget >= T) {   // everything is kept
-    for (int i = tid; i < T; i += kSelThreads) out[i] = i;
+  uint32_t* my_counts = kCounted ? counts + (size_t)seg * kLevel0Bins : nullptr;
+  if (budget <= 0 || budget >= T) {   // nothing or everything is kept
+    if (kCounted)
+      for (int i = tid; i < kLevel0Bins; i += kSelThreads) my_counts[i] = 0;
+    if (budget > 0)
+      for (int i = tid; i < T; i += kSelThreads) out[i] = i;
     return;
+  }
+  if (kCounted) {
+    for (int i = tid; i < kSelBins; i += kSelThreads) {
+      sh.hist[i] = my_counts[i];
+      my_counts[i] = 0;
+    }
+    __syncthreads();
   }
 
   uint32_t prefix = 0;        // bits of the threshold key decided so far
@@ -360,12 +368,17 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
     uint32_t* gt_map = region + cached_limit;   // after the key cache of the launch's longest cached head
     uint32_t* eq_map = gt_map + n_words;
     // the first level's histogram is counted while the keys pass through registers on their way to LDS
-    for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
-    __syncthreads();
-    for_each_global_key(u, T, [&](uint32_t key, int i) {
-      keys[i] = key;
-      atomicAdd(&sh.hist[key >> 21], 1u);
-    });
+    // (unless the scoring launch has counted it already)
+    if (kCounted) {
+      for_each_global_key(u, T, [&](uint32_t key, int i) { keys[i] = key; });
+    } else {
+      for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = 0;
+      __syncthreads();
+      for_each_global_key(u, T, [&](uint32_t key, int i) {
+        keys[i] = key;
+        atomicAdd(&sh.hist[key >> 21], 1u);
+      });
+    }
     __syncthreads();
     // later levels read the cached keys eight at a time so that the LDS latency is paid once per batch
     auto count = [&](auto fn) {
@@ -421,7 +434,7 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
   }
 
   auto count = [&](auto fn) { for_each_global_key(u, T, [&](uint32_t key, int) { fn(key); }); };
-  const uint32_t n_cand = descend_level(sh, 0, prefix, prefix_mask, need, count);   // keys left in the undecided bin
+  const uint32_t n_cand = descend_level(sh, 0, prefix, prefix_mask, need, count, kCounted);   // keys left in the undecided bin
   // Heads too long for the key cache: the first level leaves one bin of 2048 undecided.  When its
   // keys are few enough to list (their token indices, in the space the emission stages through
   // later), one more pass over the scores settles everything above that bin and collects the
@@ -485,11 +498,13 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
 
 hipError_t select_prepare() {
   const int lds = (int)(sizeof(SelShared) + (size_t)kSelRegionBytes);
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<false>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(select_kernel<true>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  const void* kernels[] = {reinterpret_cast<const void*>(select_kernel<false, false>),
+                           reinterpret_cast<const void*>(select_kernel<true, false>),
+                           reinterpret_cast<const void*>(select_kernel<false, true>),
+                           reinterpret_cast<const void*>(select_kernel<true, true>)};
+  for (const void* k : kernels)
+    if (hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, lds)) return e;
+  return hipSuccess;
 }
 
 int select_inline_capacity() { return kSelInlineOffsets; }
@@ -499,7 +514,7 @@ int select_inline_capacity() { return kSelInlineOffsets; }
 // device array has already been filled.
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
                    int32_t* idx, int seg_base, int seg_stride, hipStream_t stream, const float* ragged_scores,
-                   const int32_t* ragged_start, const int32_t* ragged_len) {
+                   const int32_t* ragged_start, const int32_t* ragged_len, uint32_t* counts) {
   const int segs = tab.first[tab.n];
   if (segs <= 0) return;
   // the LDS region is sized for the longest sequence of this launch that can use it
@@ -520,16 +535,20 @@ void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total
   if (bitmap_limit > 0 && bitmap_stage_off * 4 + kSelStageBytes > region) region = bitmap_stage_off * 4 + kSelStageBytes;
   const SelRagged ragged = {ragged_scores, ragged_start, ragged_len};
   InlineOffsets inl = {};
-  if (host_offsets != nullptr) {
+  if (host_offsets != nullptr)
     for (int i = 0; i <= n_total_segments; ++i) inl.v[i] = host_offsets[i];
-    hipLaunchKernelGGL(select_kernel<true>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
-                       inl, ragged, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
-                       (int)bitmap_stage_off);
+  const dim3 grid(segs), block(kSelThreads);
+  const size_t lds = sizeof(SelShared) + region;
+#define LKV_SELECT_LAUNCH(kInline, kCounted)                                                                          \
+  hipLaunchKernelGGL((select_kernel<kInline, kCounted>), grid, block, lds, stream, tab, inl, ragged, offsets, idx,     \
+                     counts, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,                  \
+                     (int)bitmap_stage_off)
+  if (host_offsets != nullptr) {
+    if (counts != nullptr) LKV_SELECT_LAUNCH(true, true); else LKV_SELECT_LAUNCH(true, false);
   } else {
-    hipLaunchKernelGGL(select_kernel<false>, dim3(segs), dim3(kSelThreads), sizeof(SelShared) + region, stream, tab,
-                       inl, ragged, offsets, idx, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,
-                       (int)bitmap_stage_off);
+    if (counts != nullptr) LKV_SELECT_LAUNCH(false, true); else LKV_SELECT_LAUNCH(false, false);
   }
+#undef LKV_SELECT_LAUNCH
 }
 
 }  // namespace lkv

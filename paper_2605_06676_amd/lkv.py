@@ -22,6 +22,7 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score",
            "lkv_score_window_workspace_bytes", "lkv_score_window", "lkv_select",
+           "lkv_counts_bytes", "lkv_clear_counts", "lkv_score_counted", "lkv_select_counted",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_decode_attn_static", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_soft_topk_backward", "lkv_soft_topk_batched", "lkv_soft_topk_backward_batched",
            "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
@@ -82,6 +83,16 @@ def load_library() -> C.CDLL:
     lib.lkv_select.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.POINTER(C.c_int32),
                                C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lkv_select.restype = C.c_int
+    lib.lkv_counts_bytes.argtypes = [C.c_int64]
+    lib.lkv_counts_bytes.restype = C.c_size_t
+    lib.lkv_clear_counts.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.lkv_clear_counts.restype = C.c_int
+    lib.lkv_score_counted.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(_Scorer), C.POINTER(C.c_void_p), C.c_void_p,
+                                      C.c_void_p]
+    lib.lkv_score_counted.restype = C.c_int
+    lib.lkv_select_counted.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.POINTER(C.c_int32),
+                                       C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.lkv_select_counted.restype = C.c_int
     lib.lkv_compact.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
                                 C.c_void_p, C.c_void_p]
     lib.lkv_compact.restype = C.c_int
@@ -100,7 +111,7 @@ def load_library() -> C.CDLL:
     lib.lkv_plan_offsets.restype = C.c_int
     lib.lkv_evict_layer.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_int32, C.c_int32, C.POINTER(_Scorer),
                                     C.POINTER(C.c_int32), C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
-                                    C.c_void_p, C.c_void_p]
+                                    C.c_void_p, C.c_void_p, C.c_void_p]
     lib.lkv_evict_layer.restype = C.c_int
     lib.lkv_compact_grow.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -268,6 +279,39 @@ def lkv_select(ctx: Context, cache: Cache, scores: Sequence, budgets, idx, offse
     ctx._check(ctx.lib.lkv_select(ctx.h, C.byref(cache.c), sp, bp, _ptr(idx), _ptr(offsets), _stream_ptr(stream)))
 
 
+def lkv_counts_bytes(n_segments: int) -> int:
+    return int(load_library().lkv_counts_bytes(int(n_segments)))
+
+
+def lkv_clear_counts(ctx: Context, counts, n_segments: int, stream=None) -> None:
+    """counts: GPU uint8/int32 buffer of lkv_counts_bytes(n_segments) bytes; zeroed by a fill kernel."""
+    assert counts.numel() * counts.element_size() >= lkv_counts_bytes(n_segments)
+    ctx._check(ctx.lib.lkv_clear_counts(ctx.h, _ptr(counts), int(n_segments), _stream_ptr(stream)))
+
+
+def lkv_score_counted(ctx: Context, cache: Cache, scorer: dict, scores: Sequence, counts, stream=None) -> None:
+    """lkv_score that also counts the first-level top-k digits per segment into `counts` (zero on entry)."""
+    assert counts.numel() * counts.element_size() >= lkv_counts_bytes(cache.n_segments)
+    sc = _scorer_struct(scorer)
+    sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    ctx._check(ctx.lib.lkv_score_counted(ctx.h, C.byref(cache.c), C.byref(sc), sp, _ptr(counts), _stream_ptr(stream)))
+
+
+def lkv_select_counted(ctx: Context, cache: Cache, scores: Sequence, budgets, counts, idx, offsets, stream=None) -> None:
+    """lkv_select that starts from the counts lkv_score_counted left (and zeroes them again)."""
+    import numpy as np
+
+    assert counts.numel() * counts.element_size() >= lkv_counts_bytes(cache.n_segments)
+    bp = None
+    if budgets is not None:
+        b = np.ascontiguousarray(np.asarray(budgets, dtype=np.int32).reshape(-1))
+        assert b.size == cache.n_segments
+        bp = b.ctypes.data_as(C.POINTER(C.c_int32))
+    sp = (C.c_void_p * cache.n_seq)(*[s.data_ptr() for s in scores])
+    ctx._check(ctx.lib.lkv_select_counted(ctx.h, C.byref(cache.c), sp, bp, _ptr(counts), _ptr(idx), _ptr(offsets),
+                                          _stream_ptr(stream)))
+
+
 def lkv_compact(ctx: Context, cache: Cache, idx, offsets, total_kept: int, kp, vp, stream=None) -> None:
     ctx._check(ctx.lib.lkv_compact(ctx.h, C.byref(cache.c), _ptr(idx), _ptr(offsets), int(total_kept),
                                    _ptr(kp), _ptr(vp), _stream_ptr(stream)))
@@ -378,7 +422,7 @@ def lkv_plan_offsets(ctx: Context, budgets, offsets, stream=None) -> int:
 
 
 def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int, scorer: dict, budgets, offsets,
-                    scores: Sequence, idx, kp, vp, stream=None) -> None:
+                    scores: Sequence, idx, kp, vp, stream=None, counts=None) -> None:
     """layer: a Cache built from per-sequence tensors [m, H, T_s, 128] of m consecutive layers starting at
     layer_index; budgets: host int32 [n_seq * n_layers * H]; scores: per-sequence GPU fp32 [m, H, T_s] scratch."""
     import numpy as np
@@ -389,7 +433,7 @@ def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int,
     sp = (C.c_void_p * layer.n_seq)(*[s.data_ptr() for s in scores])
     ctx._check(ctx.lib.lkv_evict_layer(ctx.h, C.byref(layer.c), layer_index, n_layers, sc,
                                        b.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(offsets), sp, _ptr(idx), _ptr(kp),
-                                       _ptr(vp), _stream_ptr(stream)))
+                                       _ptr(vp), _ptr(counts), _stream_ptr(stream)))
 
 
 def lkv_compact_grow(ctx: Context, cache: Cache, scores: Sequence, idx, offsets, total_kept: int, slack: int, kp, vp,

@@ -151,7 +151,7 @@ class LayerwiseRun(GpuRun):
     """Same buffers, but the packed cache is built one layer at a time (lkv_plan_offsets, then
     lkv_evict_layer per layer, optionally in a shuffled layer order and on a side stream)."""
 
-    def evict_layerwise(self, order=None, stream=None, layers_per_call=1):
+    def evict_layerwise(self, order=None, stream=None, layers_per_call=1, counts=None):
         """`order`: the first layer of every call (default: 0, m, 2m, ...); a call covers up to
         `layers_per_call` layers from there (fewer at the end of the model)."""
         c = self.cache
@@ -162,7 +162,7 @@ class LayerwiseRun(GpuRun):
             scratch = [torch.empty((m, c.H, t), dtype=torch.float32, device="cuda") for t in c.seq_len]
             view = lkv.Cache([k[l:l + m] for k in self.k], [v[l:l + m] for v in self.v], c.Hq)
             lkv.lkv_evict_layer(self.ctx, view, l, c.L, self.scorer, self.budgets, self.offsets, scratch, self.idx,
-                                self.kp, self.vp, stream=stream)
+                                self.kp, self.vp, stream=stream, counts=counts)
             for s in range(c.n_seq):      # keep the scores for the comparison with the oracle
                 if stream is not None:
                     with torch.cuda.stream(stream):
