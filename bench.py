@@ -96,6 +96,14 @@ def parse():
     ap.add_argument("--layerwise", action="store_true",
                     help="also measure layer-by-layer eviction during prefill; adds the key `layerwise` (a list: one entry "
                          "per --layerwise-shape)")
+    ap.add_argument("--layerwise-producer", choices=("normal", "attention"), default="normal",
+                    help="what produces a layer's K/V on the other stream in --layerwise: in-place normal_() (a stand-in "
+                         "that costs about what the eviction costs, so the overlap is visible), or the layer's causal "
+                         "attention over the prompt (lkv_masked_attn_forward with m = 1; single-sequence workloads, one "
+                         "layer per call)")
+    ap.add_argument("--layerwise-selector", choices=("lkv-t", "window"), default="lkv-t",
+                    help="with --layerwise-producer attention: score with the workload's LKV-T scorer, or with the "
+                         "observation-window scorer fed by the attention's log-normalisers (window 32, max pooling 7)")
     ap.add_argument("--layerwise-shape", action="append", default=None, metavar="STREAMS,LAYERS",
                     help="eviction streams and layers per lkv_evict_layer call for --layerwise (repeatable; "
                          "default 2,1 and 4,1 and 2,4)")
@@ -137,7 +145,8 @@ def run_workload(ctx, lkv, W, w, args, dev, headline):
         layerwise_result = []
         for n_streams, per_call in shapes:
             layerwise_result.append(layerwise(ctx, lkv, W, w, scorer, dev, n_streams, per_call,
-                                              counted=count_in_scorer(w, args)))
+                                              counted=count_in_scorer(w, args), producer=args.layerwise_producer,
+                                              selector=args.layerwise_selector))
             torch.cuda.empty_cache()
 
     # ---- inputs, resident in HBM before the timed region --------------------------------
@@ -599,7 +608,8 @@ def growth(ctx, lkv, w, cache, scorer, scores, idx, offsets, budgets_flat, total
             "reevict_ms": t_reevict, "reevict_kept": total2, "reevict_GBps": re_bytes / (t_reevict * 1e6)}
 
 
-def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, counted=False, reps=3):
+def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, counted=False, producer="normal",
+              selector="lkv-t", reps=3):
     """Layer-by-layer eviction during prefill (Sec. 1): a stand-in producer fills the K/V of the next
     `layers_per_call` layers on one stream (it takes the place of the prefill compute), the eviction of
     earlier layers runs on `n_streams` other streams in turn; n_streams buffers of layers_per_call layers
@@ -608,6 +618,9 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, count
 
     Ts = [int(t) for t in W.seq_lengths(w)]
     if len(Ts) > 32:
+        return None
+    attention = producer == "attention"
+    if attention and (len(Ts) != 1 or layers_per_call != 1):
         return None
     m = layers_per_call
     calls = [(l, min(m, w.L - l)) for l in range(0, w.L, m)]
@@ -638,7 +651,27 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, count
         lkv.lkv_clear_counts(ctx, counts, n_seg)
         torch.cuda.synchronize()
 
+    if attention:
+        # the layer's own attention over the prompt: queries of all positions (a stand-in draw; K/V keep what the
+        # first fill wrote), output and log-normalisers; the last `window` queries and their normalisers feed the
+        # observation-window scorer when that is the selector
+        T0, window = Ts[0], 32
+        q_all = torch.randn((w.Hq, T0, w.d), device=dev).to(torch.bfloat16)
+        ones = torch.ones((w.H, T0), dtype=torch.float32, device=dev)
+        att_o = torch.empty((w.Hq, T0, w.d), dtype=torch.float32, device=dev)
+        att_lse = [torch.empty((w.Hq, T0), dtype=torch.float32, device=dev) for _ in range(n_streams)]
+        q_win = q_all[:, T0 - window:].contiguous()[None]
+        win_ws = torch.empty((lkv.lkv_score_window_workspace_bytes(views[(0, 1)]),), dtype=torch.uint8, device=dev)
+        for slot in range(n_streams):
+            for t in ring[slot][0] + ring[slot][1]:
+                t.normal_()
+        att_scale = 1.0 / math.sqrt(w.d)
+
     def fill(slot):
+        if attention:
+            lkv.lkv_masked_attn_forward(ctx, q_all, ring[slot][0][0][0], ring[slot][1][0][0], ones, att_scale, att_o,
+                                        att_lse[slot], stream=s_fill)
+            return
         for t in ring[slot][0] + ring[slot][1]:
             t.normal_()
 
@@ -668,8 +701,16 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, count
                 if produce:
                     s_evict.wait_event(filled[i])
                 started[i].record(s_evict)
-                lkv.lkv_evict_layer(ctx, views[(slot, nl)], l, w.L, scorer, budgets, offsets,
-                                    [t[:nl] for t in scratch[slot]], idx, kp, vp, stream=s_evict, counts=counts)
+                if attention and selector == "window":
+                    with torch.cuda.stream(s_evict):
+                        lse_win = att_lse[slot][:, T0 - window:].contiguous()[None]
+                    lkv.lkv_score_window(ctx, views[(slot, 1)], [q_win], window, 7, lkv.POOL_MAX, att_scale,
+                                         [scratch[slot][0][:1]], win_ws, stream=s_evict, lse_win=[lse_win])
+                    lkv.lkv_evict_layer(ctx, views[(slot, 1)], l, w.L, None, budgets, offsets, [scratch[slot][0][0]],
+                                        idx, kp, vp, stream=s_evict)
+                else:
+                    lkv.lkv_evict_layer(ctx, views[(slot, nl)], l, w.L, scorer, budgets, offsets,
+                                        [t[:nl] for t in scratch[slot]], idx, kp, vp, stream=s_evict, counts=counts)
                 evicted[i].record(s_evict)
         torch.cuda.synchronize()
         wall = (time.perf_counter() - t0) * 1e3
@@ -692,8 +733,11 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, count
             "ms_per_call_eviction": per_call,
             "evict_GBps_eviction_alone": gbps, "evict_frac_of_peak_eviction_alone": gbps / HBM_PEAK_GBS,
             "peak_bytes": int(peak), "peak_bytes_whole_cache_path": int(w.L * layer_bytes + total * 1032 + N * 4),
-            "note": "producer = in-place normal_() of the layers' K/V on another stream, standing in for prefill; "
-                    "wall-clock times from the first enqueue to the last completion"}
+            "producer": "causal attention over the prompt, lkv_masked_attn_forward with m = 1" if attention
+                        else "in-place normal_() of the layers' K/V on another stream, standing in for prefill",
+            "selector": ("observation window fed by the attention's log-normalisers" if selector == "window" else "lkv-t")
+                        if attention else "lkv-t",
+            "note": "wall-clock times from the first enqueue to the last completion"}
 
 
 def cpu_baseline(w, Ts, Ks, Vs, sc_host, budgets, q, cap_s):
