@@ -12,7 +12,11 @@
 // is a whole segment is normalised and written straight to the output; other
 // pieces go to workspace slot (segment + chunk) -- distinct pieces get distinct
 // slots because segment and chunk indices both grow along the packed rows --
-// and a second, small kernel merges the slots of each segment.  (Merging inside
+// and a second, small kernel merges the slots of each segment.  A piece of at most 64 rows is
+// not worth four waves and three block barriers: such pieces are dealt round robin to single
+// waves, which run them on their own from load to store, so that a run of short segments inside
+// a chunk (skewed budgets leave dozens of heads at the floor) costs a quarter of the serial
+// latency chains it would otherwise.  (Merging inside
 // the first kernel, by the block that delivers a segment's last piece, needs
 // device-scope fences; with one L2 per XCD those write back and invalidate L2
 // and were measured to cost more than the second launch.)
@@ -43,6 +47,7 @@ constexpr int kDecKStride = 272;             // LDS bytes per staged K row
 constexpr int kDecVStride = 288;             // LDS bytes per staged V row
 constexpr int kDecWaveLds = kDecTile * (kDecKStride + kDecVStride);   // 17920
 constexpr int kDecMaxGroup = 16;
+constexpr int kDecSmallPiece = 2 * kDecTile; // pieces of at most this many rows are taken by one wave each (see below)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
@@ -91,6 +96,7 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
   const float qscale = scale * kLog2e;
   // first segment of this block: the one that contains row p0, i.e. the last with offsets[s] <= p0
   const int s_first = wave_upper_segment(offsets, n_segments, p0, lane);
+  int small_seen = 0;   // short pieces met so far in this chunk (the same count in every wave)
 
 #pragma unroll 1
   for (int s = s_first; s < n_segments; ++s) {
@@ -102,6 +108,17 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
     if (b <= a) continue;   // empty segment (the merge kernel zeroes its output)
     const int n_rows = (int)(b - a);
     const int n_tiles = (n_rows + kDecTile - 1) / kDecTile;
+
+    // Short pieces go to one wave each, in turn; the other waves move on to the next segment.
+    const bool small = n_rows <= kDecSmallPiece;
+    int t_first = wave, t_step = kDecWaves;
+    if (small) {
+      const int owner = small_seen & (kDecWaves - 1);
+      ++small_seen;
+      if (wave != owner) continue;
+      t_first = 0;
+      t_step = 1;
+    }
 
     // B operand of the first product: Q^T, lane (head c, K-block r) holds q[head c][32 ks + 8 r .. +7]
     bf16x8_t qfrag[4];
@@ -127,10 +144,10 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
         vv[j] = load_stream16(vp + (a + row) * kChunksPerRow + c);
       }
     };
-    if (wave < n_tiles) load_tile(wave);
+    if (t_first < n_tiles) load_tile(t_first);
 
 #pragma unroll 1
-    for (int t = wave; t < n_tiles; t += kDecWaves) {
+    for (int t = t_first; t < n_tiles; t += t_step) {
       // stage 32 rows: row 4j + r, piece c
       if ((t + 1) * kDecTile <= n_rows) {   // wave-uniform: a full tile
 #pragma unroll
@@ -148,7 +165,7 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
               make_uint4(vv[j].x & keep, vv[j].y & keep, vv[j].z & keep, vv[j].w & keep);
         }
       }
-      if (t + kDecWaves < n_tiles) load_tile(t + kDecWaves);   // prefetch
+      if (t + t_step < n_tiles) load_tile(t + t_step);   // prefetch
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -217,9 +234,38 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 
-    // ---- combine the four waves through LDS (the staging tiles are free now) ----
     l_run += __shfl_xor(l_run, 16, 64);
     l_run += __shfl_xor(l_run, 32, 64);
+    const bool whole = seg_lo >= p0 && seg_hi <= p1;
+    const size_t slot = (size_t)s + (size_t)chunk;
+    if (small) {
+      // ---- one wave had the whole piece: it writes the result (or the partial) straight from its registers;
+      // head h's maximum and denominator sit in lane h ----
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int h = 4 * r + e;
+        const float mxh = __shfl(m_run, h, 64);
+        const float den = __shfl(l_run, h, 64);
+        if (h < G) {
+#pragma unroll
+          for (int ct = 0; ct < 8; ++ct) {
+            const float num = acc_o[ct][e];
+            if (whole) out[((size_t)s * G + h) * kHeadDim + ct * 16 + c] = den > 0.f ? num / den : 0.f;
+            else ws_acc[(slot * G + h) * kHeadDim + ct * 16 + c] = num;
+          }
+          if (c == 0) {
+            if (whole) {
+              if (lse != nullptr) lse[(size_t)s * G + h] = den > 0.f ? mxh * kLn2 + __logf(den) : -INFINITY;
+            } else {
+              ws_m[slot * G + h] = mxh;
+              ws_l[slot * G + h] = den;
+            }
+          }
+        }
+      }
+      continue;
+    }
+    // ---- combine the four waves through LDS (the staging tiles are free now) ----
     __syncthreads();   // every wave is done with its staging tile
     if (r == 0 && c < G) { mg.m[wave][c] = m_run; mg.l[wave][c] = l_run; }
 #pragma unroll
@@ -231,8 +277,6 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
       }
     }
     __syncthreads();
-    const bool whole = seg_lo >= p0 && seg_hi <= p1;
-    const size_t slot = (size_t)s + (size_t)chunk;
     for (int o = tid; o < G * kHeadDim; o += kDecThreads) {
       const int h = o / kHeadDim, ch = o - h * kHeadDim;
       float mxw = -INFINITY;
