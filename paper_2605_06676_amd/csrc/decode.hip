@@ -197,8 +197,7 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
           sv[tt * 4 + e] = ok ? sc : -INFINITY;
           mx = fmaxf(mx, sv[tt * 4 + e]);
         }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      mx = max_over_row_blocks(mx);
       const float ref = mx == -INFINITY ? 0.f : mx;
       const float alpha = fast_exp2(m_run - ref);     // exp2(-inf) = 0 on the first tile
       m_run = mx;
@@ -234,8 +233,7 @@ decode_partial_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__ 
       __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     }
 
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
+    l_run = sum_over_row_blocks(l_run);
     const bool whole = seg_lo >= p0 && seg_hi <= p1;
     const size_t slot = (size_t)s + (size_t)chunk;
     if (small) {

@@ -109,6 +109,27 @@ __device__ __forceinline__ float row16_allreduce_sum(float x) {
   return x;
 }
 
+// Sum (or maximum) of x over the four lanes c, c + 16, c + 32, c + 48 -- the same position in the four rows of 16
+// lanes, which is where the matrix instructions leave the four K blocks (or accumulator row blocks) of one column --
+// in every one of them.  Row swaps on the vector ALU: v_permlane16_swap exchanges the odd rows of its first operand
+// with the even rows of its second, v_permlane32_swap the upper half of the first with the lower half of the second;
+// with both operands equal the two results are x[lane] and x[lane ^ 16], resp. x[lane ^ 32], in some order, and the
+// operations that follow are symmetric.  A shuffle through the LDS crossbar (ds_bpermute) gives the same values bit
+// for bit but costs an LDS round trip that an in-order wave has to sit out.
+typedef unsigned u32x2_swap_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float sum_over_row_blocks(float x) {
+  const u32x2_swap_t a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a.x) + __uint_as_float(a.y);
+  const u32x2_swap_t b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b.x) + __uint_as_float(b.y);
+}
+__device__ __forceinline__ float max_over_row_blocks(float x) {
+  const u32x2_swap_t a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a.x), __uint_as_float(a.y));
+  const u32x2_swap_t b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b.x), __uint_as_float(b.y));
+}
+
 // Largest s in [0, n - 1] with table[s] <= p, for a non-decreasing table with table[0] <= p.
 // The whole wave takes part (p must be wave-uniform): 64 probes per round, so two rounds
 // of loads cover 4096 entries where a binary search needs twelve dependent ones.

@@ -192,8 +192,7 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
             sv[4 * sub + e] = kDiag && key0 + 16 * sub + 4 * r + e > query ? -INFINITY : s;
             mx = fmaxf(mx, sv[4 * sub + e]);
           }
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        mx = max_over_row_blocks(mx);
         mx = fmaxf(m_run[qb], mx * qscale);              // qscale > 0: scaling commutes with the maximum
         const float ref = mx == -INFINITY ? 0.f : mx;
         const float alpha = ma_exp2(m_run[qb] - ref);    // exp2(-inf) = 0 on the first tile
@@ -263,8 +262,7 @@ masked_attn_fwd_kernel(const uint16_t* __restrict__ q, const uint4* __restrict__
 #pragma unroll
   for (int qb = 0; qb < kQB; ++qb) {
     float l = l_run[qb];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
+    l = sum_over_row_blocks(l);
     const int query = qw0 + 16 * qb + c;
     if (r == 0 && query < T) lse[(size_t)hq * T + query] = l > 0.f ? m_run[qb] * kMaLn2 + __logf(l) : -INFINITY;
 #pragma unroll

@@ -450,8 +450,7 @@ masked_attn_bwd_dkv_kernel(const uint4* __restrict__ q, const uint16_t* __restri
 #pragma unroll
   for (int kb = 0; kb < kKB; ++kb) {
     float s = dm_acc[kb];
-    s += __shfl_xor(s, 16, 64);
-    s += __shfl_xor(s, 32, 64);
+    s = sum_over_row_blocks(s);
     const int key = kw0 + 16 * kb + c;
     if (r == 0 && key < T) dm[(size_t)unit * T + key] = s;
 #pragma unroll

@@ -142,8 +142,7 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
       for (int e = 0; e < 4; ++e) part = fmaf(wo[e], activation<kAct>(acc[mt][e]), part);
     }
     // sum the four feature-block lanes of each token: lanes c, c+16, c+32, c+48
-    part += __shfl_xor(part, 16, 64);
-    part += __shfl_xor(part, 32, 64);
+    part = sum_over_row_blocks(part);
     const int row = row0 + c;
     if (r == 0 && row < T) {
       const float u = part + bias2;
@@ -172,19 +171,6 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
     __syncthreads();
     flush_level0_counts(hist_lds, counts, (size_t)(seg_base + seq * seg_stride + lh), kMlpThreads);
   }
-}
-
-// Sum of x over the four lanes c, c + 16, c + 32, c + 48 (the four feature blocks of one token), in every one of
-// them.  Row swaps on the vector ALU (v_permlane16_swap exchanges the odd rows of its first operand with the even
-// rows of its second, v_permlane32_swap the upper half of the first with the lower half of the second; with both
-// operands equal the two results are x[lane] and x[lane ^ 16], resp. x[lane ^ 32], in some order).  A shuffle
-// through the LDS crossbar costs an LDS round trip that an in-order wave has to sit out.
-__device__ __forceinline__ float sum_over_feature_blocks(float x) {
-  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-  const u32x2 a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  x = __uint_as_float(a.x) + __uint_as_float(a.y);
-  const u32x2 b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
-  return __uint_as_float(b.x) + __uint_as_float(b.y);
 }
 
 // Hidden widths 80..128 (the paper's network is 256 -> 128 -> 1): W1 no longer fits the registers of
@@ -273,12 +259,24 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   const int n_tiles = (block_rows + 15) >> 4;
 
   uint4 xa[4], xb[4];   // this wave's halves of an even and of an odd tile on their way to LDS
+  // Rows of a tile that lies wholly inside the head are addressed as a wave-uniform base (scalar arithmetic) plus a
+  // per-lane constant, so a load costs no vector instruction for its address (the kernel is short of vector issue
+  // slots, not of anything else); only a tile that reaches past the end of the head clamps its rows one by one.
+  const uint4* Xb = Xh + (size_t)block_row0 * kChunksPerRow;            // uniform
+  const int lane_off = r * kChunksPerRow + c;                           // in 16-byte pieces; + 64 per group of four rows
+  const int full_tiles = (T - block_row0) >> 4;                         // tiles of this block with all 16 rows inside the head
   auto load_half = [&](uint4 (&xx)[4], int i) {
+    if (i < full_tiles) {
+      const uint4* tb = Xb + (size_t)i * (16 * kChunksPerRow);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      int row = block_row0 + 16 * i + 4 * j + r;
-      row = row < T ? row : T - 1;
-      xx[j] = load_stream16(Xh + (size_t)row * kChunksPerRow + c);
+      for (int j = 0; j < 4; ++j) xx[j] = load_stream16(tb + lane_off + j * (4 * kChunksPerRow));
+    } else {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        int row = block_row0 + 16 * i + 4 * j + r;
+        row = row < T ? row : T - 1;
+        xx[j] = load_stream16(Xh + (size_t)row * kChunksPerRow + c);
+      }
     }
   };
   auto stage_half = [&](const uint4 (&xx)[4], int buf) {
@@ -316,7 +314,7 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
     for (int mw = 0; mw < MTW; ++mw)
 #pragma unroll
       for (int e = 0; e < 4; ++e) part = fmaf(w2r[mw][e], activation<kAct>(acc[mw][e]), part);
-    part = sum_over_feature_blocks(part);
+    part = sum_over_row_blocks(part);
     if (half == 1) {
       if (r == 0) sum_lds[(i & 1) * 16 + c] = part;
     } else {

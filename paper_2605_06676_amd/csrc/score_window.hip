@@ -213,8 +213,7 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
       for (int mw = 0; mw < MTW; ++mw)
 #pragma unroll
         for (int e = 0; e < 4; ++e) part += __builtin_amdgcn_exp2f(fmaf(acc[mw][e], log2_scale, -ref[mw][e]));
-      part += __shfl_xor(part, 16, 64);
-      part += __shfl_xor(part, 32, 64);
+      part = sum_over_row_blocks(part);
       if (r == 0 && row0 + c < prefix) votes[row0 + c] = part;
     }
   };
