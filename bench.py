@@ -653,7 +653,8 @@ def layerwise(ctx, lkv, W, w, scorer, dev, n_streams=2, layers_per_call=1, count
     s_fill, s_evicts = torch.cuda.Stream(), [torch.cuda.Stream() for _ in range(n_streams)]
     counts = None
     if counted:
-        counts = torch.empty((n_seg, 2048), dtype=torch.int32, device=dev)
+        # counters plus room for the bitmaps that let a call over few long heads split every head over several workgroups
+        counts = torch.empty((lkv.lkv_counts_bytes_split(n_seg, max(Ts)) // 4,), dtype=torch.int32, device=dev)
         lkv.lkv_clear_counts(ctx, counts, n_seg)
         torch.cuda.synchronize()
 

@@ -197,6 +197,11 @@ lkv_status lkv_select(lkv_ctx *ctx, const lkv_cache *cache, const float *const *
  *          lkv_clear_counts serves any number of score / select pairs.  The two calls must see the
  *          same cache geometry and the scores must not change in between. */
 size_t lkv_counts_bytes(int64_t n_segments);
+/* The same plus room for two bitmaps of max_seq_len bits per segment behind the counters (no need to clear them).
+ * Given a buffer of this size, lkv_evict_layer splits the top-k pass over the scores of every head over several
+ * workgroups when a call covers few heads that are too long for the on-chip key cache (one layer of a
+ * 65536-token or longer prompt: 8 heads would otherwise keep 8 compute units busy). */
+size_t lkv_counts_bytes_split(int64_t n_segments, int32_t max_seq_len);
 lkv_status lkv_clear_counts(lkv_ctx *ctx, uint32_t *counts, int64_t n_segments, void *stream);
 lkv_status lkv_score_counted(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *scorer,
                              float *const *scores, uint32_t *counts, void *stream);
@@ -289,11 +294,14 @@ lkv_status lkv_plan_offsets(lkv_ctx *ctx, int64_t n_segments, const int32_t *bud
  * counts      : NULL, or DEVICE uint32 [n_seq * n_layers * H, 2048] as for lkv_score_counted (all zero
  *               on entry, left zero): the scoring then counts for the top-k.  Ignored when scorer is NULL.
  *               Calls that run at the same time on different streams touch different segments'
- *               counters, so they can share the buffer. */
+ *               counters, so they can share the buffer.
+ * counts_bytes: size of that buffer: lkv_counts_bytes(n_segments), or lkv_counts_bytes_split(n_segments,
+ *               longest sequence) to let the call split long heads over several workgroups; smaller:
+ *               LKV_ERR_WORKSPACE */
 lkv_status lkv_evict_layer(lkv_ctx *ctx, const lkv_cache *layer, int32_t layer_index, int32_t n_layers,
                            const lkv_scorer *scorer, const int32_t *budgets, const int32_t *offsets,
                            float *const *scores, int32_t *idx, void *kp, void *vp, uint32_t *counts,
-                           void *stream);
+                           size_t counts_bytes, void *stream);
 
 /* ---- Decode-time growth of the packed cache -----------------------------------------------
  * The paper evicts during prefill (Sec. 1), lets step t attend every cached token up to t (Eq. 1)

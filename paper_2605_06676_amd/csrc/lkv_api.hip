@@ -271,6 +271,12 @@ size_t lkv_counts_bytes(int64_t n_segments) {
   return n_segments > 0 ? (size_t)n_segments * lkv::kLevel0Bins * sizeof(uint32_t) : 0;
 }
 
+size_t lkv_counts_bytes_split(int64_t n_segments, int32_t max_seq_len) {
+  if (n_segments <= 0 || max_seq_len <= 0) return 0;
+  const size_t words = ((size_t)max_seq_len + 31) / 32;
+  return lkv_counts_bytes(n_segments) + (size_t)n_segments * 2 * words * sizeof(uint32_t);
+}
+
 lkv_status lkv_clear_counts(lkv_ctx* ctx, uint32_t* counts, int64_t n_segments, void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (counts == nullptr || !aligned16(counts)) return fail(ctx, LKV_ERR_INVALID_ARG, "counts is NULL or not 16-byte aligned");
@@ -596,7 +602,8 @@ lkv_status lkv_plan_offsets(lkv_ctx* ctx, int64_t n_segments, const int32_t* bud
 
 lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_index, int32_t n_layers,
                            const lkv_scorer* scorer, const int32_t* budgets, const int32_t* offsets,
-                           float* const* scores, int32_t* idx, void* kp, void* vp, uint32_t* counts, void* stream) {
+                           float* const* scores, int32_t* idx, void* kp, void* vp, uint32_t* counts, size_t counts_bytes,
+                           void* stream) {
   if (ctx == nullptr) return LKV_ERR_INVALID_ARG;
   if (lkv_status st = check_cache(ctx, layer, true)) return st;
   if (counts != nullptr && !aligned16(counts)) return fail(ctx, LKV_ERR_INVALID_ARG, "counts is not 16-byte aligned");
@@ -653,6 +660,21 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   } else {
     counts = nullptr;   // the scores came from elsewhere: nothing has counted them
   }
+  // room behind the counters for two bitmaps per segment lets a launch over few long heads split each head's pass over
+  // the scores over several workgroups
+  uint32_t* pre_maps = nullptr;
+  int pre_words = 0;
+  if (counts != nullptr) {
+    if (counts_bytes < lkv_counts_bytes(n_seg))
+      return fail(ctx, LKV_ERR_WORKSPACE, "counts: need %zu bytes, got %zu", lkv_counts_bytes(n_seg), counts_bytes);
+    const size_t words = (counts_bytes - lkv_counts_bytes(n_seg)) / ((size_t)n_seg * 2 * sizeof(uint32_t));
+    int max_T = 0;
+    for (int s = 0; s < layer->n_seq; ++s) max_T = layer->seq_len[s] > max_T ? layer->seq_len[s] : max_T;
+    if (words >= ((size_t)max_T + 31) / 32) {
+      pre_maps = counts + (size_t)n_seg * lkv::kLevel0Bins;
+      pre_words = (int)(words < ((size_t)lkv::select_max_bitmap_tokens() / 32) ? words : (size_t)lkv::select_max_bitmap_tokens() / 32);
+    }
+  }
 
   hipStream_t st = as_stream(stream);
   lkv::SeqTable tab;
@@ -668,7 +690,7 @@ lkv_status lkv_evict_layer(lkv_ctx* ctx, const lkv_cache* layer, int32_t layer_i
   tab.n = layer->n_seq;
   // select: segment of (sequence i, view head j) is i * n_layers * H + layer_index * H + j, offsets already on the device
   lkv::launch_select(tab, nullptr, (int)n_seg, const_cast<int32_t*>(offsets), idx, layer_index * H, heads_all, st, nullptr,
-                     nullptr, nullptr, counts);
+                     nullptr, nullptr, counts, pre_maps, pre_words);
   if (hipError_t e = hipGetLastError()) return hip_fail(ctx, e, "lkv_evict_layer select launch");
   // compact: one contiguous row range per sequence
   for (int i = 0; i < layer->n_seq; ++i) {

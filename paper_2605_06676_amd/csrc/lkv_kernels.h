@@ -31,7 +31,9 @@ int select_inline_capacity();
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
                    int32_t* idx, int seg_base, int seg_stride, hipStream_t stream,
                    const float* ragged_scores = nullptr, const int32_t* ragged_start = nullptr,
-                   const int32_t* ragged_len = nullptr, uint32_t* counts = nullptr);
+                   const int32_t* ragged_len = nullptr, uint32_t* counts = nullptr, uint32_t* pre_maps = nullptr,
+                   int pre_words = 0);
+int select_max_bitmap_tokens();
 
 // counts.hip
 void launch_clear_counts(uint32_t* counts, int64_t n_segments, hipStream_t stream);

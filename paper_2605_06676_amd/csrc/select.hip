@@ -51,6 +51,9 @@ constexpr int kSelMaxBitmapT = (kSelRegionBytes - kSelStageBytes) / 8 * 32;   //
 static_assert(kSelMaxCachedKeys * 4 + 2 * ((kSelMaxCachedKeys + 31) / 32) * 4 <= kSelRegionBytes, "key cache + bitmaps");
 constexpr int kSelBatch = 8;                                // loads in flight per thread
 constexpr int kSelInlineOffsets = 640;                      // offsets that fit the kernel arguments next to the launch table
+constexpr int kSelSplitMaxHeads = 64;                       // launches with at most this many (long) heads split each head's pass
+constexpr int kSelSplitTargetBlocks = 256;                  // over about this many workgroups in all,
+constexpr int kSelSplitMax = 32;                            // at most this many per head
 
 struct InlineOffsets {
   int32_t v[kSelInlineOffsets];
@@ -319,6 +322,8 @@ template <bool kInline, bool kCounted>
 __global__ void __launch_bounds__(kSelThreads)
 select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __restrict__ offsets, int32_t* __restrict__ idx,
               uint32_t* __restrict__ counts,
+              const uint32_t* __restrict__ pre_maps /* per segment [2][pre_words]: written by select_classify_kernel, or null */,
+              int pre_words,
               int seg_base, int seg_stride /* global segment = seg_base + sequence * seg_stride + head */,
               int cached_limit /* heads of at most this many tokens use the LDS key cache */,
               int bitmap_limit /* longer heads up to this many tokens use the LDS bitmaps */,
@@ -445,20 +450,42 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
     uint32_t* gt_map = region;
     uint32_t* eq_map = region + n_words;
     uint32_t* cand = region + bitmap_stage_off;
-    for (int i = tid; i < 2 * n_words; i += kSelThreads) region[i] = 0;
-    if (tid == 0) sh.cand_count = 0;
-    __syncthreads();
-    for_each_global_key(u, T, [&](uint32_t key, int i) {
-      const uint32_t top = key >> 21;
-      if (top > bin0) {
-        atomicOr(&gt_map[i >> 5], 1u << (i & 31));
-      } else if (top == bin0) {
-        // (handing out slots per wave with a ballot was measured slower than the plain atomic)
-        const uint32_t slot = atomicAdd(&sh.cand_count, 1u);
-        if (slot < (uint32_t)kSelCandCap) cand[slot] = (uint32_t)i;
+    if (kCounted && pre_maps != nullptr) {
+      // the pass over the scores has been done by the blocks of select_classify_kernel: take its two bitmaps
+      // (above the undecided bin / inside it) and list the tokens inside
+      const uint32_t* pre_gt = pre_maps + (size_t)seg * 2 * pre_words;
+      const uint32_t* pre_in = pre_gt + pre_words;
+      for (int i = tid; i < n_words; i += kSelThreads) { gt_map[i] = pre_gt[i]; eq_map[i] = 0; }
+      if (tid == 0) sh.cand_count = 0;
+      __syncthreads();
+      for (int w0 = 0; w0 < n_words; w0 += kSelThreads) {   // uniform trip counts, here and in the inner loop
+        const int w = w0 + tid;
+        uint32_t bits = w < n_words ? pre_in[w] : 0u;
+        while (__ballot(bits != 0u) != 0ull) {
+          if (bits) {
+            const uint32_t slot = atomicAdd(&sh.cand_count, 1u);
+            if (slot < (uint32_t)kSelCandCap) cand[slot] = ((uint32_t)w << 5) + (uint32_t)__builtin_ctz(bits);
+            bits &= bits - 1;
+          }
+        }
       }
-    });
-    __syncthreads();
+      __syncthreads();
+    } else {
+      for (int i = tid; i < 2 * n_words; i += kSelThreads) region[i] = 0;
+      if (tid == 0) sh.cand_count = 0;
+      __syncthreads();
+      for_each_global_key(u, T, [&](uint32_t key, int i) {
+        const uint32_t top = key >> 21;
+        if (top > bin0) {
+          atomicOr(&gt_map[i >> 5], 1u << (i & 31));
+        } else if (top == bin0) {
+          // (handing out slots per wave with a ballot was measured slower than the plain atomic)
+          const uint32_t slot = atomicAdd(&sh.cand_count, 1u);
+          if (slot < (uint32_t)kSelCandCap) cand[slot] = (uint32_t)i;
+        }
+      });
+      __syncthreads();
+    }
     auto count_listed = [&](auto fn) {
       for (uint32_t j = tid; j < n_cand; j += kSelThreads) fn(order_key(u[cand[j]]));
     };
@@ -496,6 +523,69 @@ select_kernel(SeqTable tab, InlineOffsets inl, SelRagged ragged, int32_t* __rest
   }
 }
 
+
+// First half of a top-k whose heads are split over several workgroups (launches over few, long heads: one layer at
+// a time).  Needs the first-level counts of the scoring launch.  Every block finds the undecided first-level bin of
+// its head from the counts (a 2048-bin scan, repeated in each block rather than communicated) and classifies its
+// slice of the scores against it into two global bitmaps: above the bin (kept for certain), and inside it (the
+// candidates the remaining two levels choose from).  select_kernel then starts from the bitmaps instead of passing
+// over the scores.  The counters are left as they are (select_kernel reads them again and zeroes them).  A head
+// whose undecided bin holds more tokens than select_kernel can list is skipped here and takes the unsplit route there.
+__global__ void __launch_bounds__(kSelThreads)
+select_classify_kernel(SeqTable tab, const int32_t* __restrict__ offsets, const uint32_t* __restrict__ counts,
+                       uint32_t* __restrict__ pre_maps, int pre_words, int seg_base, int seg_stride, int split) {
+  __shared__ SelShared sh;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int local_seg = blockIdx.x / split;
+  const int part = blockIdx.x - local_seg * split;
+  const int seq = seq_of_unit(tab, local_seg);
+  const int lh = local_seg - tab.first[seq];
+  const int seg = seg_base + seq * seg_stride + lh;
+  const int T = tab.T[seq];
+  const float* u = tab.scores[seq] + (size_t)lh * (size_t)T;
+  const int budget = offsets[seg + 1] - offsets[seg];
+  if (budget <= 0 || budget >= T) return;
+  const uint32_t* my_counts = counts + (size_t)seg * kLevel0Bins;
+  for (int i = tid; i < kSelBins; i += kSelThreads) sh.hist[i] = my_counts[i];
+  __syncthreads();
+  uint32_t prefix = 0, prefix_mask = 0, need = (uint32_t)budget;
+  const uint32_t n_cand = descend_level(sh, 0, prefix, prefix_mask, need, [](auto) {}, true);
+  if (n_cand > (uint32_t)kSelCandCap) return;
+  const uint32_t bin0 = prefix >> 21;
+  uint32_t* out_gt = pre_maps + (size_t)seg * 2 * pre_words;
+  uint32_t* out_in = out_gt + pre_words;
+  // slices of whole 64-token groups (two bitmap words per wave step)
+  const int groups = (T + 63) >> 6;
+  const int per = (groups + split - 1) / split;
+  const int g_lo = part * per, g_hi = min(groups, g_lo + per);
+  constexpr int kU = 4;
+  for (int g0 = g_lo + wave; g0 < g_hi; g0 += kSelWaves * kU) {
+    float v[kU];
+#pragma unroll
+    for (int k = 0; k < kU; ++k) {
+      const int i = (g0 + k * kSelWaves) * 64 + lane;
+      v[k] = u[i < T ? i : T - 1];
+    }
+#pragma unroll
+    for (int k = 0; k < kU; ++k) {
+      const int g = g0 + k * kSelWaves;
+      const int i = g * 64 + lane;
+      const uint32_t top = order_key(v[k]) >> 21;
+      const bool in = g < g_hi && i < T;
+      const unsigned long long m_gt = __ballot(in && top > bin0);
+      const unsigned long long m_in = __ballot(in && top == bin0);
+      if (g < g_hi && lane < 2) {
+        const int w = 2 * g + lane;
+        if (w < pre_words) {
+          out_gt[w] = (uint32_t)(m_gt >> (32 * lane));
+          out_in[w] = (uint32_t)(m_in >> (32 * lane));
+        }
+      }
+    }
+  }
+}
+
 hipError_t select_prepare() {
   const int lds = (int)(sizeof(SelShared) + (size_t)kSelRegionBytes);
   const void* kernels[] = {reinterpret_cast<const void*>(select_kernel<false, false>),
@@ -508,13 +598,15 @@ hipError_t select_prepare() {
 }
 
 int select_inline_capacity() { return kSelInlineOffsets; }
+int select_max_bitmap_tokens() { return kSelMaxBitmapT; }
 
 // `host_offsets` non-null: all n_total_segments + 1 offsets are passed in the kernel arguments
 // (n_total_segments < kSelInlineOffsets) and the kernel writes the device array; null: the
 // device array has already been filled.
 void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total_segments, int32_t* offsets,
                    int32_t* idx, int seg_base, int seg_stride, hipStream_t stream, const float* ragged_scores,
-                   const int32_t* ragged_start, const int32_t* ragged_len, uint32_t* counts) {
+                   const int32_t* ragged_start, const int32_t* ragged_len, uint32_t* counts, uint32_t* pre_maps,
+                   int pre_words) {
   const int segs = tab.first[tab.n];
   if (segs <= 0) return;
   // the LDS region is sized for the longest sequence of this launch that can use it
@@ -539,10 +631,24 @@ void launch_select(const SeqTable& tab, const int32_t* host_offsets, int n_total
     for (int i = 0; i <= n_total_segments; ++i) inl.v[i] = host_offsets[i];
   const dim3 grid(segs), block(kSelThreads);
   const size_t lds = sizeof(SelShared) + region;
+  // Few long heads (a layer at a time): split the pass over the scores of every head over several workgroups first.
+  // Needs the first-level counts, room for the two bitmaps, heads too long for the key cache and offsets on the device.
+  bool split_heads = counts != nullptr && pre_maps != nullptr && host_offsets == nullptr && ragged_scores == nullptr &&
+                     cached_limit == 0 && bitmap_limit > 0 && segs <= kSelSplitMaxHeads;
+  for (int i = 0; i < tab.n && split_heads; ++i)
+    if (tab.T[i] > kSelMaxBitmapT || (tab.T[i] + 31) / 32 > pre_words) split_heads = false;
+  if (split_heads) {
+    int split = kSelSplitTargetBlocks / segs;
+    split = split > kSelSplitMax ? kSelSplitMax : split;
+    hipLaunchKernelGGL(select_classify_kernel, dim3(segs * split), block, 0, stream, tab, offsets, counts, pre_maps,
+                       pre_words, seg_base, seg_stride, split);
+  } else {
+    pre_maps = nullptr;
+  }
 #define LKV_SELECT_LAUNCH(kInline, kCounted)                                                                          \
   hipLaunchKernelGGL((select_kernel<kInline, kCounted>), grid, block, lds, stream, tab, inl, ragged, offsets, idx,     \
-                     counts, seg_base, seg_stride, cached_limit, bitmap_limit, (int)cached_stage_off,                  \
-                     (int)bitmap_stage_off)
+                     counts, pre_maps, pre_words, seg_base, seg_stride, cached_limit, bitmap_limit,                    \
+                     (int)cached_stage_off, (int)bitmap_stage_off)
   if (host_offsets != nullptr) {
     if (counts != nullptr) LKV_SELECT_LAUNCH(true, true); else LKV_SELECT_LAUNCH(true, false);
   } else {

@@ -22,7 +22,7 @@ _STATUS = {0: "LKV_OK", 1: "LKV_ERR_INVALID_ARG", 2: "LKV_ERR_UNSUPPORTED", 3: "
 
 EXPORTS = ("lkv_create", "lkv_destroy", "lkv_last_error", "lkv_version", "lkv_score",
            "lkv_score_window_workspace_bytes", "lkv_score_window", "lkv_select",
-           "lkv_counts_bytes", "lkv_clear_counts", "lkv_score_counted", "lkv_select_counted",
+           "lkv_counts_bytes", "lkv_counts_bytes_split", "lkv_clear_counts", "lkv_score_counted", "lkv_select_counted",
            "lkv_compact", "lkv_decode_workspace_bytes", "lkv_decode_attn", "lkv_decode_attn_static", "lkv_soft_topk_max_n",
            "lkv_soft_topk", "lkv_soft_topk_backward", "lkv_soft_topk_batched", "lkv_soft_topk_backward_batched",
            "lkv_head_budgets", "lkv_plan_offsets", "lkv_evict_layer", "lkv_compact_grow",
@@ -85,6 +85,8 @@ def load_library() -> C.CDLL:
     lib.lkv_select.restype = C.c_int
     lib.lkv_counts_bytes.argtypes = [C.c_int64]
     lib.lkv_counts_bytes.restype = C.c_size_t
+    lib.lkv_counts_bytes_split.argtypes = [C.c_int64, C.c_int32]
+    lib.lkv_counts_bytes_split.restype = C.c_size_t
     lib.lkv_clear_counts.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     lib.lkv_clear_counts.restype = C.c_int
     lib.lkv_score_counted.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(_Scorer), C.POINTER(C.c_void_p), C.c_void_p,
@@ -111,7 +113,7 @@ def load_library() -> C.CDLL:
     lib.lkv_plan_offsets.restype = C.c_int
     lib.lkv_evict_layer.argtypes = [C.c_void_p, C.POINTER(_Cache), C.c_int32, C.c_int32, C.POINTER(_Scorer),
                                     C.POINTER(C.c_int32), C.c_void_p, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
-                                    C.c_void_p, C.c_void_p, C.c_void_p]
+                                    C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.lkv_evict_layer.restype = C.c_int
     lib.lkv_compact_grow.argtypes = [C.c_void_p, C.POINTER(_Cache), C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p,
                                      C.c_int64, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -283,6 +285,10 @@ def lkv_counts_bytes(n_segments: int) -> int:
     return int(load_library().lkv_counts_bytes(int(n_segments)))
 
 
+def lkv_counts_bytes_split(n_segments: int, max_seq_len: int) -> int:
+    return int(load_library().lkv_counts_bytes_split(int(n_segments), int(max_seq_len)))
+
+
 def lkv_clear_counts(ctx: Context, counts, n_segments: int, stream=None) -> None:
     """counts: GPU uint8/int32 buffer of lkv_counts_bytes(n_segments) bytes; zeroed by a fill kernel."""
     assert counts.numel() * counts.element_size() >= lkv_counts_bytes(n_segments)
@@ -433,7 +439,8 @@ def lkv_evict_layer(ctx: Context, layer: Cache, layer_index: int, n_layers: int,
     sp = (C.c_void_p * layer.n_seq)(*[s.data_ptr() for s in scores])
     ctx._check(ctx.lib.lkv_evict_layer(ctx.h, C.byref(layer.c), layer_index, n_layers, sc,
                                        b.ctypes.data_as(C.POINTER(C.c_int32)), _ptr(offsets), sp, _ptr(idx), _ptr(kp),
-                                       _ptr(vp), _ptr(counts), _stream_ptr(stream)))
+                                       _ptr(vp), _ptr(counts), 0 if counts is None else counts.numel() * counts.element_size(),
+                                       _stream_ptr(stream)))
 
 
 def lkv_compact_grow(ctx: Context, cache: Cache, scores: Sequence, idx, offsets, total_kept: int, slack: int, kp, vp,

@@ -168,3 +168,84 @@ def test_counted_calls_report_argument_errors(ctx):
         ctx._check(lib.lkv_clear_counts(ctx.h, counts.data_ptr() + 4, 2, None))
     assert e.value.status == 1
     assert lkv.lkv_counts_bytes(3) == 3 * 2048 * 4 and lkv.lkv_counts_bytes(0) == 0
+
+
+def _layerwise_equals_whole(ctx, w, Ts, seed, split, Ks=None, Vs=None, sc=None, Bs=None, orders=((1, None),)):
+    if Ks is None:
+        Ks, Vs, Bs = [], [], []
+        for s, T in enumerate(Ts):
+            K, V = W.draw_kv(w, T, s, seed)
+            Ks.append(K); Vs.append(V); Bs.append(W.draw_budgets(w, T, s, seed))
+        sc = W.draw_scorer(w, seed)
+    Qs = [W.draw_q(w, s, seed) for s in range(len(Ts))]
+    whole = G.GpuRun(ctx, Ks, Vs, Qs, sc, Bs, w.Hq)
+    whole.run_all()
+    idx_ref = []
+    for s in range(len(Ts)):
+        idx_ref.append(O.select_all(whole.scores[s].cpu().numpy(), np.asarray(Bs[s]).reshape(w.L, w.H))[0])
+    assert np.array_equal(whole.idx.cpu().numpy()[:whole.total], np.concatenate(idx_ref))
+    n_seg = whole.cache.n_segments
+    nbytes = lkv.lkv_counts_bytes_split(n_seg, max(Ts)) if split else lkv.lkv_counts_bytes(n_seg)
+    for m, order in orders:
+        lay = G.LayerwiseRun(ctx, Ks, Vs, Qs, sc, Bs, w.Hq)
+        counts = torch.full((nbytes // 4,), 0x33333333, dtype=torch.int32, device="cuda")      # the bitmaps need no clearing
+        lkv.lkv_clear_counts(ctx, counts, n_seg)
+        lay.evict_layerwise(order=order, layers_per_call=m, counts=counts)
+        lay.decode()
+        torch.cuda.synchronize()
+        n = whole.total
+        assert torch.equal(lay.offsets, whole.offsets) and torch.equal(lay.idx[:n], whole.idx[:n]), f"m={m}: indices"
+        assert torch.equal(lay.kp[:n].view(torch.int16), whole.kp[:n].view(torch.int16))
+        assert torch.equal(lay.vp[:n].view(torch.int16), whole.vp[:n].view(torch.int16))
+        assert torch.equal(lay.out, whole.out)
+        assert int(counts[:n_seg * 2048].abs().max()) == 0, "counters not left zero"
+
+
+@pytest.mark.parametrize("scorer,hidden,T", [("mlp", 64, 40000), ("linear", 0, 70001), ("mlp", 128, 34305), ("mlp", 32, 131072)])
+def test_long_heads_split_over_several_workgroups(ctx, scorer, hidden, T):
+    # one layer at a time over heads too long for the on-chip key cache, with room for the bitmaps behind the
+    # counters: every head's pass over the scores is split over several workgroups; the result must not change
+    L, H = (1, 2) if T > 100000 else (3, 2)
+    w = W.scaled(W.CONFIGS[0], L=L, H=H, Hq=2 * H, scorer=scorer, hidden=hidden, act="gelu", per_head=hidden == 128, b_min=16, R=0.1)
+    _layerwise_equals_whole(ctx, w, [T], seed=3, split=True, orders=((1, None), (2, None)) if L > 1 else ((1, None),))
+
+
+def test_split_route_with_two_long_sequences_and_without_room_for_the_bitmaps(ctx):
+    w = W.scaled(W.CONFIGS[0], n_seq=2, L=2, H=2, Hq=4, scorer="mlp", hidden=48, act="silu", b_min=8)
+    _layerwise_equals_whole(ctx, w, [36001, 50000], seed=5, split=True)
+    _layerwise_equals_whole(ctx, w, [36001, 50000], seed=5, split=False)      # counters only: the unsplit counted route
+
+
+def test_split_route_falls_back_when_the_undecided_bin_is_too_full(ctx):
+    # scores of one head crowd into one first-level bin ([1, 1.25): one value of the top 11 key bits): more
+    # candidates than the top-k lists, so that head takes the unsplit route inside the same launch; the other head
+    # is split as usual.  A one-hot linear scorer makes the scores key channel 0.
+    T = 45000
+    w = W.scaled(W.CONFIGS[0], L=2, H=2, Hq=4, b_min=8)
+    K, V = W.draw_kv(w, T, 0, 9)
+    rng = np.random.default_rng(9)
+    col = W.bf16_bits_to_f32(K[:, :, :, 0]).copy()                           # [L, H, T]
+    col[0, 0, :] = 1.0 + rng.integers(0, 32, size=T).astype(np.float32) / 128.0     # 32 bf16 values in [1, 1.25)
+    col[1, 1, : T // 2] = np.float32(3.0)                                    # a long run of ties in the other layer
+    K[:, :, :, 0] = W.f32_to_bf16_bits(col)
+    sc = W.draw_scorer(w, 9)
+    sc["w1"][:] = 0
+    sc["w1"][:, :, 0] = W.f32_to_bf16_bits(np.float32(1.0))
+    sc["b1"][:] = 0
+    B = np.array([[20000, 3000], [9000, 30000]], dtype=np.int32)
+    _layerwise_equals_whole(ctx, w, [T], seed=9, split=True, Ks=[K], Vs=[V], sc=sc, Bs=[B])
+
+
+def test_counts_buffer_too_small_is_an_error(ctx):
+    w = W.scaled(W.CONFIGS[0], L=2, H=2, Hq=4, b_min=4)
+    K, V = W.draw_kv(w, 300, 0, 1)
+    run = G.LayerwiseRun(ctx, [K], [V], [W.draw_q(w, 0, 1)], W.draw_scorer(w, 1), [W.draw_budgets(w, 300, 0, 1)], w.Hq)
+    lkv.lkv_plan_offsets(ctx, run.budgets, run.offsets)
+    view = lkv.Cache([run.k[0][0:1]], [run.v[0][0:1]], w.Hq)
+    scratch = [torch.empty((1, w.H, 300), dtype=torch.float32, device="cuda")]
+    small = torch.zeros((3 * 2048,), dtype=torch.int32, device="cuda")          # 4 segments need 4 x 2048 counters
+    with pytest.raises(lkv.LkvError) as e:
+        lkv.lkv_evict_layer(ctx, view, 0, w.L, run.scorer, run.budgets, run.offsets, scratch, run.idx, run.kp, run.vp, counts=small)
+    assert e.value.status == 3
+    assert lkv.lkv_counts_bytes_split(4, 100) == 4 * 2048 * 4 + 4 * 2 * 4 * 4
+    torch.cuda.synchronize()
