@@ -17,6 +17,7 @@
 //    with w2 are per-lane work, finished by two cross-lane adds.
 // The next two 16-token tiles are prefetched into registers while the current
 // one is multiplied; b1 and w2 are read from LDS.
+#include <type_traits>
 #include "lkv_act.h"
 #include "lkv_common.h"
 
@@ -101,7 +102,7 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       int row = row0 + 4 * j + r;
-      row = row < T ? row : T - 1;   // ragged tail: re-read the last row, result unused
+      row = row < wave_row1 ? row : wave_row1 - 1;   // past the block's rows: re-read its last row, result unused
       kk[j] = load_stream16(Kh + (size_t)row * kChunksPerRow + c);
       vv[j] = load_stream16(Vh + (size_t)row * kChunksPerRow + c);
     }
@@ -153,18 +154,24 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
   };
 
   if (wave_row0 < wave_row1) {
+    // No branch encloses a load between its issue and the staging that waits for it: the compiler counts the
+    // loads still in flight at a wait from the path on which the fewest were issued, so a conditional load makes
+    // every wait drain the whole queue.  Loads past the block's rows are clamped instead of skipped.
     load_tile(ka, va, wave_row0);
-    if (wave_row0 + kStep < wave_row1) load_tile(kb, vb, wave_row0 + kStep);
+    load_tile(kb, vb, wave_row0 + kStep);
+    int row0 = wave_row0;
 #pragma unroll 1
-    for (int row0 = wave_row0; row0 < wave_row1; row0 += 2 * kStep) {
+    for (; row0 + kStep < wave_row1; row0 += 2 * kStep) {
       stage_tile(ka, va);
-      if (row0 + 2 * kStep < wave_row1) load_tile(ka, va, row0 + 2 * kStep);
+      load_tile(ka, va, row0 + 2 * kStep);
       multiply_tile(row0);
-      if (row0 + kStep < wave_row1) {
-        stage_tile(kb, vb);
-        if (row0 + 3 * kStep < wave_row1) load_tile(kb, vb, row0 + 3 * kStep);
-        multiply_tile(row0 + kStep);
-      }
+      stage_tile(kb, vb);
+      load_tile(kb, vb, row0 + 3 * kStep);
+      multiply_tile(row0 + kStep);
+    }
+    if (row0 < wave_row1) {
+      stage_tile(ka, va);
+      multiply_tile(row0);
     }
   }
   if (kCount) {
@@ -265,18 +272,21 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   const uint4* Xb = Xh + (size_t)block_row0 * kChunksPerRow;            // uniform
   const int lane_off = r * kChunksPerRow + c;                           // in 16-byte pieces; + 64 per group of four rows
   const int full_tiles = (T - block_row0) >> 4;                         // tiles of this block with all 16 rows inside the head
+  // No branch encloses a load between its issue and the staging that waits for it (the compiler counts the loads
+  // still in flight at a wait from the path on which the fewest were issued, so a conditional load makes every
+  // wait drain the whole queue): tiles past the block's rows are clamped, not skipped.
+  const int last_row = block_row0 + block_rows - 1;
+  auto load_half_fast = [&](uint4 (&xx)[4], int i) {   // tile i lies wholly inside the block's rows
+    const uint4* tb = Xb + (size_t)i * (16 * kChunksPerRow);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) xx[j] = load_stream16(tb + lane_off + j * (4 * kChunksPerRow));
+  };
   auto load_half = [&](uint4 (&xx)[4], int i) {
-    if (i < full_tiles) {
-      const uint4* tb = Xb + (size_t)i * (16 * kChunksPerRow);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) xx[j] = load_stream16(tb + lane_off + j * (4 * kChunksPerRow));
-    } else {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        int row = block_row0 + 16 * i + 4 * j + r;
-        row = row < T ? row : T - 1;
-        xx[j] = load_stream16(Xh + (size_t)row * kChunksPerRow + c);
-      }
+    for (int j = 0; j < 4; ++j) {
+      int row = block_row0 + 16 * i + 4 * j + r;
+      row = row < last_row ? row : last_row;
+      xx[j] = load_stream16(Xh + (size_t)row * kChunksPerRow + c);
     }
   };
   auto stage_half = [&](const uint4 (&xx)[4], int buf) {
@@ -288,7 +298,7 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   // One step: products, activation and output layer of tile i; store of tile i - 1 (wave 0 adds the partner's
   // partial sums, which barrier i - 1 made visible); staging of tile i + 1, whose registers then fetch tile i + 3;
   // barrier i.
-  auto step = [&](uint4 (&x_next)[4], int i) {
+  auto step = [&](uint4 (&x_next)[4], int i, auto fast) {
     f32x4_t acc[MTW];
 #pragma unroll
     for (int mw = 0; mw < MTW; ++mw) acc[mw] = b1r[mw];
@@ -320,22 +330,29 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
     } else {
       prev = part;
     }
-    if (i + 1 < n_tiles) {
-      stage_half(x_next, (i + 1) & 1);
-      if (i + 3 < n_tiles) load_half(x_next, i + 3);
-    }
+    stage_half(x_next, (i + 1) & 1);   // past the last tile: rows nobody reads
+    if (decltype(fast)::value) load_half_fast(x_next, i + 3); else load_half(x_next, i + 3);
     __syncthreads();
   };
+  const int fast_tiles = min(n_tiles, full_tiles);   // tiles with all 16 rows inside the block and the head
+  int i = 0;
   load_half(xa, 0);
-  if (1 < n_tiles) load_half(xb, 1);
+  load_half(xb, 1);
   stage_half(xa, 0);
-  if (2 < n_tiles) load_half(xa, 2);
+  load_half(xa, 2);
   __syncthreads();   // tile 0 is in LDS
 #pragma unroll 1
-  for (int i = 0; i < n_tiles; i += 2) {
-    step(xb, i);                               // stages the odd tile i + 1
-    if (i + 1 < n_tiles) step(xa, i + 1);      // uniform condition around the barrier
+  for (; i + 4 < fast_tiles; i += 2) {           // both steps fetch whole tiles: tiles i + 3 and i + 4
+    step(xb, i, std::true_type{});               // stages the odd tile i + 1
+    step(xa, i + 1, std::true_type{});
   }
+#pragma unroll 1
+  for (; i + 1 < n_tiles; i += 2) {
+    step(xb, i, std::false_type{});
+    step(xa, i + 1, std::false_type{});
+  }
+  if (i < n_tiles) step(xb, i, std::false_type{});
+
   if (half == 0) {
     const int row = block_row0 + 16 * (n_tiles - 1) + c;
     if (r == 0 && row < T) {
