@@ -146,11 +146,15 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
   // Staging: thread (half, r, c) brings piece c of rows 16 nt + 8 half + r and 16 nt + 8 half + 4 + r of each step.
   constexpr int NT = kWinTilesPerStep;
   uint4 xa[2 * NT], xb[2 * NT];
+  // No branch encloses a load between its issue and the staging that waits for it: the compiler counts the loads
+  // still in flight at a wait from the path on which the fewest were issued, so a conditional load makes every wait
+  // drain the whole queue.  Steps past the block's rows are clamped instead of skipped.
+  const int last_row = block_row0 + block_rows - 1;
   auto load_step = [&](uint4 (&xx)[2 * NT], int i) {
 #pragma unroll
     for (int j = 0; j < 2 * NT; ++j) {
       int row = block_row0 + 16 * NT * i + 16 * (j >> 1) + 8 * half + 4 * (j & 1) + r;
-      row = row < T ? row : T - 1;   // ragged tail: re-read the last row, masked below
+      row = row < last_row ? row : last_row;   // past the block's rows: re-read its last row, masked below
       xx[j] = load_stream16(Kh + (size_t)row * kChunksPerRow + c);
     }
   };
@@ -226,24 +230,24 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
     const unsigned char* xt = x_lds + (i & 1) * kWinStepLds;
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) products(acc[nt], xt + nt * kWinTileLds);
-    if (i + 1 < n_steps) {
-      stage_step(x_next, (i + 1) & 1);
-      if (i + 3 < n_steps) load_step(x_next, i + 3);
-    }
+    stage_step(x_next, (i + 1) & 1);               // past the last step: rows nobody reads
+    load_step(x_next, i + 3);
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) finish(acc[nt], NT * i + nt);
     __syncthreads();
   };
   load_step(xa, 0);
-  if (1 < n_steps) load_step(xb, 1);
+  load_step(xb, 1);
   stage_step(xa, 0);
-  if (2 < n_steps) load_step(xa, 2);
+  load_step(xa, 2);
   __syncthreads();
+  int i = 0;
 #pragma unroll 1
-  for (int i = 0; i < n_steps; i += 2) {
+  for (; i + 1 < n_steps; i += 2) {
     step(xb, i);                                   // stages the odd step i + 1
-    if (i + 1 < n_steps) step(xa, i + 1);          // uniform condition around the barrier
+    step(xa, i + 1);
   }
+  if (i < n_steps) step(xb, i);
 
   if (kPass == 1) {
     // one (reference, sum) pair per row: merge the 16 token lanes
