@@ -153,8 +153,8 @@ lkv_status lkv_score(lkv_ctx *ctx, const lkv_cache *cache, const lkv_scorer *sco
  * scale     : positive, finite (1 / sqrt(d) in Eq. 1)
  * scores    : HOST [n_seq] of DEVICE pointers, each fp32 [L, H, T_s]
  * workspace : DEVICE, 256-byte aligned, at least lkv_score_window_workspace_bytes(cache)
- *             bytes (votes and per-block normaliser pairs, about 16 bytes per
- *             cached key row and head); contents are scratch. */
+ *             bytes (per-block normaliser pairs, about 8 bytes per cached key
+ *             row and head); contents are scratch. */
 size_t lkv_score_window_workspace_bytes(const lkv_cache *cache);
 lkv_status lkv_score_window(lkv_ctx *ctx, const lkv_cache *cache, const void *const *q_win,
                             const float *const *lse_win, int32_t window, int32_t pool_width, int32_t pool_kind,

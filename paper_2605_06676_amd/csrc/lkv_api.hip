@@ -293,7 +293,7 @@ size_t lkv_score_window_workspace_bytes(const lkv_cache* cache) {
   size_t need = 0;
   for (int s = 0; s < cache->n_seq; ++s) {
     if (cache->seq_len[s] < 1) return 0;
-    need += lkv::score_window_votes_bytes(heads, cache->seq_len[s]) + lkv::score_window_pairs_bytes(heads, cache->seq_len[s]);
+    need += lkv::score_window_pairs_bytes(heads, cache->seq_len[s]);
   }
   return need;
 }
@@ -345,24 +345,21 @@ lkv_status lkv_score_window(lkv_ctx* ctx, const lkv_cache* cache, const void* co
   while (s < cache->n_seq) {
     lkv::WinTable tab;
     memset(&tab, 0, sizeof(tab));
-    int64_t blocks = 0, pool_blocks = 0;
+    int64_t blocks = 0;
     int n = 0;
     while (s < cache->n_seq && n < lkv::kMaxSeqPerLaunch) {
       const int T = cache->seq_len[s];
-      const int64_t mine = heads * ((T + rpb - 1) / rpb), pool = heads * ((T + 1023) / 1024);
-      if (n > 0 && (blocks + mine >= ((int64_t)1 << 31) - 1 || pool_blocks + pool >= ((int64_t)1 << 31) - 1)) break;
+      const int64_t mine = heads * ((T + rpb - 1) / rpb);
+      if (n > 0 && blocks + mine >= ((int64_t)1 << 31) - 1) break;
       tab.k[n] = static_cast<const uint16_t*>(cache->k[s]);
       tab.q[n] = static_cast<const uint16_t*>(q_win[s]);
       tab.scores[n] = scores[s];
       tab.lse[n] = lse_win != nullptr ? lse_win[s] : nullptr;
-      tab.votes[n] = reinterpret_cast<float*>(ws);
-      ws += lkv::score_window_votes_bytes(heads, T);
       tab.partial[n] = reinterpret_cast<float*>(ws);
       ws += lkv::score_window_pairs_bytes(heads, T);
       tab.T[n] = T;
       tab.first[n] = (int32_t)blocks;
       blocks += mine;
-      pool_blocks += pool;
       ++n;
       ++s;
     }

@@ -30,13 +30,12 @@ struct SeqTable {
   int32_t n;
 };
 
-// The same for the observation-window scorer, which reads keys and window queries and needs two
-// workspace arrays per sequence.
+// The same for the observation-window scorer, which reads keys and window queries and needs a
+// workspace array per sequence.
 struct WinTable {
   const uint16_t* k[kMaxSeqPerLaunch];
   const uint16_t* q[kMaxSeqPerLaunch];           // window queries [L, Hq, W, 128]
   float* scores[kMaxSeqPerLaunch];               // [L, H, T]
-  float* votes[kMaxSeqPerLaunch];                // workspace [2, L H, T]
   float* partial[kMaxSeqPerLaunch];              // workspace [L H, blocks per head, padded rows, 2]
   const float* lse[kMaxSeqPerLaunch];            // optional: log-normalisers of the window rows [L, Hq, W], or null
   int32_t T[kMaxSeqPerLaunch];

@@ -20,7 +20,6 @@ int score_mlp_rows_per_block(int T, int heads, int hidden);
 // score_window.hip
 int score_window_max_rows();
 int score_window_rows_per_block(int64_t tokens_times_heads);
-size_t score_window_votes_bytes(int64_t heads, int T);
 size_t score_window_pairs_bytes(int64_t heads, int T);
 void launch_score_window(const WinTable& tab, int heads, int window, int group, int pool_width, int pool_kind,
                          int rows_per_block, float scale, hipStream_t stream);

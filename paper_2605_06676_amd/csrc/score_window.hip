@@ -14,8 +14,10 @@
 //           the window), written as a (reference, sum) pair per block;
 //   merge   the pairs of all blocks of a head into each row's log-normaliser (a small kernel);
 //   pass 2  recomputes the logits and adds exp(logit - normaliser) over the rows: the token's vote,
-//           each wave of a block writing the share of its own rows;
-//   pool    adds the two shares, takes the group mean, smooths and writes the scores.
+//           the two waves of a block adding their rows' shares in LDS; then the block takes the
+//           group mean, smooths and writes the scores of its keys.  The pooling reaches into the
+//           neighbouring blocks' keys, so a block also computes the votes of up to two tiles on
+//           either side of its own (3 to 6 % more work, less than a pooling launch costs).
 // Keeping the logits instead would cost as many bytes as reading the keys again (G W = 128
 // logits per 128-element key).  A caller that still has the log-normalisers of the window rows
 // (the prefill's attention kernel computes them for every query) passes them in: pass 1 and the
@@ -41,6 +43,8 @@ constexpr int kWinTileLds = kWinTokTile * kWinRowStride;
 constexpr int kWinTilesPerStep = 2;     // tiles staged, multiplied and finished between two barriers
 constexpr int kWinStepLds = kWinTilesPerStep * kWinTileLds;
 constexpr int kWinMaxRowsPerBlock = 1024;
+constexpr int kWinMaxReach = 31;                // pooling widths up to 63
+constexpr int kWinVoteSlots = kWinMaxRowsPerBlock + 32 + kWinMaxReach + 17;   // pass 2: a block's keys, two tiles before, the reach after, rounded up to a tile
 constexpr float kWinRebase = 64.f;               // log2 distance at which pass 1 moves a reference
 constexpr float kWinNoRef = -1e30f;              // reference of a row that has seen no key yet
 
@@ -63,7 +67,8 @@ __device__ __forceinline__ float row16_allreduce_max(float x) {
 // never counted).
 template <int MTW, int kPass>
 __global__ void __launch_bounds__(kWinThreads, 2)
-score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_per_block, float log2_scale) {
+score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_per_block, float log2_scale,
+                    int reach /* pass 2: pooling reach c, width 2 c + 1 */, int pool_kind, float inv_group) {
   extern __shared__ __align__(16) unsigned char smem[];
   constexpr int RP = 32 * MTW;                      // padded rows of the block
 
@@ -75,10 +80,21 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
   const int chunk = local - lh * chunks;
   const int prefix = T - window;                    // tokens that are scored
 
-  const int block_row0 = chunk * rows_per_block;
-  const int block_end = kPass == 1 ? T : prefix;    // pass 2 has nothing to do inside the window
-  if (block_row0 >= block_end) return;
-  const int block_rows = min(block_end - block_row0, rows_per_block);
+  // The block's own keys, and the keys it multiplies: in pass 2 also those within the pooling's reach on either
+  // side (whole tiles before, single keys after), as far as they lie inside the prefix.
+  const int own_row0 = chunk * rows_per_block;
+  const int own_end = min(T, own_row0 + rows_per_block);
+  const int block_end_all = kPass == 1 ? T : prefix;    // pass 2 has no votes to compute inside the window
+  float* out = tab.scores[seq] + (size_t)lh * T;
+  if (own_row0 >= block_end_all) {
+    if (kPass == 2)   // a block of window tokens
+      for (int j = own_row0 + (int)threadIdx.x; j < own_end; j += kWinThreads) out[j] = INFINITY;
+    return;
+  }
+  const int halo = kPass == 2 ? ((reach + 15) >> 4) << 4 : 0;
+  const int block_row0 = max(0, own_row0 - halo);
+  const int block_end = kPass == 1 ? own_end : min(prefix, own_end + reach);
+  const int block_rows = block_end - block_row0;
   const int n_tiles = (block_rows + 15) >> 4;
 
   const int lane = threadIdx.x & 63;
@@ -86,8 +102,10 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
   const int r = lane >> 4;
   const int c = lane & 15;
   unsigned char* x_lds = smem;   // the staged keys of two steps
-  // pass 2: this wave's share of the votes (its rows only) goes to its own half of the workspace
-  float* votes = tab.votes[seq] + ((size_t)half * heads + lh) * T;
+  // pass 2: the votes of the keys the block multiplies; both waves add the shares of their rows
+  float* v_lds = reinterpret_cast<float*>(smem + 2 * kWinStepLds);
+  if (kPass == 2)
+    for (int i = threadIdx.x; i < kWinVoteSlots; i += kWinThreads) v_lds[i] = 0.f;   // ordered by the barrier below
 
   // A fragments: window row 16 (half MTW + mw) + c, features 32 ks + 8 r .. +7
   bf16x8_t qfrag[MTW][4];
@@ -218,7 +236,8 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
 #pragma unroll
         for (int e = 0; e < 4; ++e) part += __builtin_amdgcn_exp2f(fmaf(acc[mw][e], log2_scale, -ref[mw][e]));
       part = sum_over_row_blocks(part);
-      if (r == 0 && row0 + c < prefix) votes[row0 + c] = part;
+      // two additions to a zero: the same sum whichever wave comes first
+      if (r == 0 && row0 + c < block_end) atomicAdd(&v_lds[row0 + c - block_row0], part);
     }
   };
 
@@ -249,6 +268,33 @@ score_window_kernel(WinTable tab, int heads, int window, int n_rows, int rows_pe
   }
   if (i < n_steps) step(xb, i);
 
+  if (kPass == 2) {
+    // Scores of the block's own keys: centred pooling over the votes inside the prefix (votes are non-negative and
+    // the slots outside hold zeros, which change neither rule), group mean, +inf on window tokens.  The last
+    // barrier of the loop has made all votes visible.
+    const float inv_width = 1.f / (float)(2 * reach + 1);
+    for (int j = own_row0 + (int)threadIdx.x; j < own_end; j += kWinThreads) {
+      float sc = INFINITY;
+      if (j < prefix) {
+        const int lo = j - reach - block_row0;   // may be negative at the start of the head
+        sc = 0.f;
+        if (pool_kind == 0) {
+          for (int u = 0; u <= 2 * reach; ++u) {
+            const int t = lo + u;
+            sc = fmaxf(sc, t >= 0 && t < block_rows ? v_lds[t] : 0.f);
+          }
+          sc *= inv_group;
+        } else {
+          for (int u = 0; u <= 2 * reach; ++u) {
+            const int t = lo + u;
+            sc += t >= 0 && t < block_rows ? v_lds[t] : 0.f;
+          }
+          sc *= inv_width * inv_group;
+        }
+      }
+      out[j] = sc;
+    }
+  }
   if (kPass == 1) {
     // one (reference, sum) pair per row: merge the 16 token lanes
     float* part = tab.partial[seq] + (part_row0 + (size_t)chunk * RP) * 2;
@@ -296,46 +342,6 @@ score_window_merge_kernel(WinTable tab, int heads, int n_rows, int rows_per_bloc
   lse[row] = out;
 }
 
-// Scores from votes: centred pooling of width 2 c + 1 over the prefix, +inf on the window tokens.
-// kind 0: maximum over the part of the span inside the prefix; kind 1: sum over it divided by the width.
-__global__ void __launch_bounds__(256)
-score_window_pool_kernel(WinTable tab, int heads, int window, int reach, int kind, float inv_group) {
-  const int seq = win_seq_of_unit(tab, blockIdx.x);
-  const int local = blockIdx.x - tab.first[seq];
-  const int T = tab.T[seq];
-  const int tiles = (T + 1023) >> 10;
-  const int lh = local / tiles;
-  const int tile = local - lh * tiles;
-  const int prefix = T - window;
-  const float* va = tab.votes[seq] + (size_t)lh * T;               // the two waves' shares of the votes
-  const float* vb = tab.votes[seq] + ((size_t)heads + lh) * T;
-  float* out = tab.scores[seq] + (size_t)lh * T;
-  const float inv_width = 1.f / (float)(2 * reach + 1);
-  // the summed votes of the tile and of `reach` neighbours on either side, once, through LDS
-  __shared__ float v_lds[1024 + 64];
-  const int base = tile * 1024 - reach;
-  for (int t = threadIdx.x; t < 1024 + 2 * reach; t += 256) {
-    const int j = base + t;
-    v_lds[t] = j >= 0 && j < prefix ? va[j] + vb[j] : 0.f;     // votes are non-negative: zeros change neither rule
-  }
-  __syncthreads();
-  for (int t = threadIdx.x; t < min(1024, T - tile * 1024); t += 256) {
-    const int j = tile * 1024 + t;
-    float s = INFINITY;
-    if (j < prefix) {
-      s = 0.f;
-      if (kind == 0) {
-        for (int u = 0; u <= 2 * reach; ++u) s = fmaxf(s, v_lds[t + u]);
-        s *= inv_group;
-      } else {
-        for (int u = 0; u <= 2 * reach; ++u) s += v_lds[t + u];
-        s *= inv_width * inv_group;
-      }
-    }
-    out[j] = s;
-  }
-}
-
 int score_window_max_rows() { return 128; }
 
 int score_window_rows_per_block(int64_t tokens_times_heads) {
@@ -346,52 +352,44 @@ int score_window_rows_per_block(int64_t tokens_times_heads) {
   return rows;
 }
 
-// Workspace of one sequence: votes [2, heads, T] (one share per wave of a block), then pairs [heads, ceil(T / 128), 128, 2] (the largest the
-// pairs can get: the smallest block and the most padded rows) followed by the merged normalisers
-// [heads, 128]; both parts 256-byte aligned.
-size_t score_window_votes_bytes(int64_t heads, int T) { return ((size_t)2 * heads * T * sizeof(float) + 255) & ~(size_t)255; }
+// Workspace of one sequence: pairs [heads, ceil(T / 128), 128, 2] (the largest the pairs can get: the smallest
+// block and the most padded rows) followed by the merged normalisers [heads, 128]; 256-byte aligned.
 size_t score_window_pairs_bytes(int64_t heads, int T) {
   return ((size_t)heads * (((T + 127) / 128) * 2 + 1) * 128 * sizeof(float) + 255) & ~(size_t)255;
 }
 
 template <int MTW>
 static void launch_passes(const WinTable& tab, int heads, int window, int n_rows, int rows_per_block, float log2_scale,
-                          hipStream_t stream) {
+                          int reach, int pool_kind, float inv_group, hipStream_t stream) {
   const int blocks = tab.first[tab.n];
-  const size_t lds1 = 2 * kWinStepLds;   // both passes
+  const size_t lds1 = 2 * kWinStepLds;
+  const size_t lds2 = lds1 + kWinVoteSlots * sizeof(float);
   if (tab.lse[0] == nullptr) {   // all sequences of a call come with normalisers, or none does
     hipLaunchKernelGGL((score_window_kernel<MTW, 1>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
-                       n_rows, rows_per_block, log2_scale);
+                       n_rows, rows_per_block, log2_scale, 0, 0, 0.f);
     hipLaunchKernelGGL(score_window_merge_kernel, dim3(tab.n * heads), dim3(128), 0, stream, tab, heads, n_rows,
                        rows_per_block, 32 * MTW);
   }
-  hipLaunchKernelGGL((score_window_kernel<MTW, 2>), dim3(blocks), dim3(kWinThreads), lds1, stream, tab, heads, window,
-                     n_rows, rows_per_block, log2_scale);
+  hipLaunchKernelGGL((score_window_kernel<MTW, 2>), dim3(blocks), dim3(kWinThreads), lds2, stream, tab, heads, window,
+                     n_rows, rows_per_block, log2_scale, reach, pool_kind, inv_group);
 }
 
-// `tab.first` counts the blocks of the two passes; the pooling kernel derives its own grid.
+// `tab.first` counts the blocks of the passes (the same grid for both).
 void launch_score_window(const WinTable& tab, int heads, int window, int group, int pool_width, int pool_kind,
                          int rows_per_block, float scale, hipStream_t stream) {
   if (tab.n <= 0) return;
   const int n_rows = group * window;
   const float log2_scale = scale * 1.44269504088896340736f;
   const float inv_group = 1.f / (float)group;
+  const int reach = (pool_width - 1) / 2;
+  if (reach > kWinMaxReach) return;   // the host checks the width before
   switch ((n_rows + 31) / 32) {
-    case 1: launch_passes<1>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
-    case 2: launch_passes<2>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
-    case 3: launch_passes<3>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
-    case 4: launch_passes<4>(tab, heads, window, n_rows, rows_per_block, log2_scale, stream); break;
+    case 1: launch_passes<1>(tab, heads, window, n_rows, rows_per_block, log2_scale, reach, pool_kind, inv_group, stream); break;
+    case 2: launch_passes<2>(tab, heads, window, n_rows, rows_per_block, log2_scale, reach, pool_kind, inv_group, stream); break;
+    case 3: launch_passes<3>(tab, heads, window, n_rows, rows_per_block, log2_scale, reach, pool_kind, inv_group, stream); break;
+    case 4: launch_passes<4>(tab, heads, window, n_rows, rows_per_block, log2_scale, reach, pool_kind, inv_group, stream); break;
     default: return;
   }
-  WinTable pool = tab;
-  int64_t blocks = 0;
-  for (int i = 0; i < tab.n; ++i) {
-    pool.first[i] = (int32_t)blocks;
-    blocks += (int64_t)heads * ((tab.T[i] + 1023) >> 10);
-  }
-  pool.first[tab.n] = (int32_t)blocks;
-  hipLaunchKernelGGL(score_window_pool_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, pool, heads, window,
-                     (pool_width - 1) / 2, pool_kind, inv_group);
 }
 
 }  // namespace lkv
