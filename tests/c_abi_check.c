@@ -29,7 +29,7 @@ int main(void) {
   cache.head_dim = 128;
   cache.seq_len = lens;
 
-  /* host arithmetic only: votes (two shares of 4 bytes) and normaliser pairs per key row and head */
+  /* host arithmetic only: the normaliser pairs of the window scorer, at least 8 bytes per key row and head */
   ws = lkv_score_window_workspace_bytes(&cache);
   CHECK(ws % 256 == 0);
   CHECK(ws >= (size_t)6 * (1000 + 37) * 8);
