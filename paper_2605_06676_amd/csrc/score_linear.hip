@@ -8,6 +8,10 @@
 // products of a row are summed with four DPP adds.  A wave owns 64 consecutive
 // tokens and lane (r, c) ends up holding the score of token 4c + r, which makes
 // the result store one fully used 256-byte line per wave.
+//
+// A block's 256 rows are cut at multiples of 256 rows of the whole tensor rather than of the head, so that blocks
+// read 64 KB-aligned runs of K and V and write 1 KB-aligned runs of scores whatever T is: with windows that start
+// at each head's first row, a T that is not a multiple of 32 cost 2 to 5 % of the bandwidth.
 #include "lkv_common.h"
 
 namespace lkv {
@@ -17,13 +21,20 @@ constexpr int kScoreRowsPerWave = 64;
 constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * (kScoreBlockThreads / 64);   // 256
 constexpr int kScoreUnroll = 4;   // row groups whose loads are in flight together (8 loads per lane)
 
+// Blocks are windows of 256 rows of the whole [L, H, T] tensor.  When T is a multiple of 256 every head starts on a
+// window; otherwise a head's first row can lie anywhere inside one and the head needs up to one block more.
+__host__ __device__ inline int score_linear_blocks_per_head_impl(int T) {
+  return (T & (kScoreRowsPerBlock - 1)) == 0 ? T / kScoreRowsPerBlock : (T + 2 * kScoreRowsPerBlock - 2) / kScoreRowsPerBlock;
+}
+int score_linear_blocks_per_head(int T) { return score_linear_blocks_per_head_impl(T); }
+
 __global__ void __launch_bounds__(kScoreBlockThreads)
 score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __restrict__ b1,
                     int heads_per_scorer_row /* H if per-layer scorer, 1 if per-head */) {
   const int seq = seq_of_unit(tab, blockIdx.x);
   const int local = blockIdx.x - tab.first[seq];
   const int T = tab.T[seq];
-  const int tiles = (T + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock;
+  const int tiles = score_linear_blocks_per_head_impl(T);
   const int lh = local / tiles;                 // flattened (layer, head)
   const int tile = local - lh * tiles;
   const int scorer = lh / heads_per_scorer_row; // per-layer: lh / H = layer; per-head: lh
@@ -45,8 +56,12 @@ score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* 
   const size_t head_row0 = (size_t)lh * (size_t)T;
   const uint4* Kh = reinterpret_cast<const uint4*>(tab.k[seq]) + head_row0 * kChunksPerRow;
   const uint4* Vh = reinterpret_cast<const uint4*>(tab.v[seq]) + head_row0 * kChunksPerRow;
-  const int row_base = tile * kScoreRowsPerBlock + wave * kScoreRowsPerWave;
-  if (row_base >= T) return;     // whole wave past the end (wave-uniform)
+  // Blocks are cut at multiples of 256 rows of the whole [L, H, T] tensor, not of the head: a head whose first row
+  // is not such a multiple gets a short first block, and every other block reads 64 KB-aligned runs of K and V
+  // (and writes 1 KB-aligned runs of scores) whatever T is.
+  const int lead = (int)(head_row0 & (size_t)(kScoreRowsPerBlock - 1));
+  const int row_base = tile * kScoreRowsPerBlock - lead + wave * kScoreRowsPerWave;
+  if (row_base >= T || row_base + kScoreRowsPerWave <= 0) return;     // whole wave outside the head (wave-uniform)
 
   float mine = 0.f;
 #pragma unroll
@@ -55,7 +70,8 @@ score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* 
 #pragma unroll
     for (int u = 0; u < kScoreUnroll; ++u) {
       int row = row_base + 4 * (j0 + u) + r;
-      row = row < T ? row : T - 1;             // ragged tail: re-read the last row, result unused
+      row = row < T ? row : T - 1;             // rows outside the head: re-read its first or last row, result unused
+      row = row < 0 ? 0 : row;
       kk[u] = load_stream16(Kh + (size_t)row * kChunksPerRow + c);
       vv[u] = load_stream16(Vh + (size_t)row * kChunksPerRow + c);
     }
@@ -74,7 +90,7 @@ score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* 
     }
   }
   const int out_row = row_base + 4 * c + r;
-  if (out_row < T) tab.scores[seq][head_row0 + out_row] = mine + bias;
+  if (out_row >= 0 && out_row < T) tab.scores[seq][head_row0 + out_row] = mine + bias;
 }
 
 void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b1, int heads_per_scorer_row,
@@ -85,6 +101,6 @@ void launch_score_linear(const SeqTable& tab, const uint16_t* w1, const float* b
                      b1, heads_per_scorer_row);
 }
 
-int score_linear_blocks_per_head(int T) { return (T + kScoreRowsPerBlock - 1) / kScoreRowsPerBlock; }
+
 
 }  // namespace lkv
