@@ -9,9 +9,9 @@
 // tokens and lane (r, c) ends up holding the score of token 4c + r, which makes
 // the result store one fully used 256-byte line per wave.
 //
-// A block's 256 rows are cut at multiples of 256 rows of the whole tensor rather than of the head, so that blocks
-// read 64 KB-aligned runs of K and V and write 1 KB-aligned runs of scores whatever T is: with windows that start
-// at each head's first row, a T that is not a multiple of 32 cost 2 to 5 % of the bandwidth.
+// A block's 256 rows are cut at 64 KB boundaries of the key array rather than at the head's first row, so that
+// blocks read aligned runs whatever T is: with windows that start at each head's first row, a T that is not a
+// multiple of 32 cost 2 to 5 % of the bandwidth.
 #include "lkv_common.h"
 
 namespace lkv {
@@ -21,10 +21,10 @@ constexpr int kScoreRowsPerWave = 64;
 constexpr int kScoreRowsPerBlock = kScoreRowsPerWave * (kScoreBlockThreads / 64);   // 256
 constexpr int kScoreUnroll = 4;   // row groups whose loads are in flight together (8 loads per lane)
 
-// Blocks are windows of 256 rows of the whole [L, H, T] tensor.  When T is a multiple of 256 every head starts on a
-// window; otherwise a head's first row can lie anywhere inside one and the head needs up to one block more.
+// Blocks are 64 KB windows of the key array's address space (256 rows).  A head's first row can lie anywhere inside
+// a window, so a head needs up to one block more than its rows fill; a block with no row of the head exits at once.
 __host__ __device__ inline int score_linear_blocks_per_head_impl(int T) {
-  return (T & (kScoreRowsPerBlock - 1)) == 0 ? T / kScoreRowsPerBlock : (T + 2 * kScoreRowsPerBlock - 2) / kScoreRowsPerBlock;
+  return (T + 2 * kScoreRowsPerBlock - 2) / kScoreRowsPerBlock;
 }
 int score_linear_blocks_per_head(int T) { return score_linear_blocks_per_head_impl(T); }
 
@@ -56,10 +56,11 @@ score_linear_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* 
   const size_t head_row0 = (size_t)lh * (size_t)T;
   const uint4* Kh = reinterpret_cast<const uint4*>(tab.k[seq]) + head_row0 * kChunksPerRow;
   const uint4* Vh = reinterpret_cast<const uint4*>(tab.v[seq]) + head_row0 * kChunksPerRow;
-  // Blocks are cut at multiples of 256 rows of the whole [L, H, T] tensor, not of the head: a head whose first row
-  // is not such a multiple gets a short first block, and every other block reads 64 KB-aligned runs of K and V
-  // (and writes 1 KB-aligned runs of scores) whatever T is.
-  const int lead = (int)(head_row0 & (size_t)(kScoreRowsPerBlock - 1));
+  // Blocks are cut at 64 KB boundaries of the key array's addresses, not at multiples of 256 rows of the head: a
+  // head whose first row does not sit on such a boundary gets a short first block, and every other block reads
+  // 64 KB-aligned runs of K (and, when V and the scores are allocated alike, of V; 1 KB-aligned runs of scores)
+  // whatever T is and wherever the tensor, or a layer view of it, starts.
+  const int lead = (int)((reinterpret_cast<uintptr_t>(Kh) >> 8) & (uintptr_t)(kScoreRowsPerBlock - 1));
   const int row_base = tile * kScoreRowsPerBlock - lead + wave * kScoreRowsPerWave;
   if (row_base >= T || row_base + kScoreRowsPerWave <= 0) return;     // whole wave outside the head (wave-uniform)
 
