@@ -192,8 +192,7 @@ score_mlp_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float* __r
 // and with two waves per SIMD there is little else to run: the output-layer weights therefore stay in
 // registers, the bias is read at the top of the step together with the operand fragments, and the
 // four-lane sums use row swaps instead of LDS shuffles (together 7 % faster than with all three in
-// LDS).  Issuing the products of tile i ahead of the activations of tile i - 1 (a second accumulator
-// set), a third register set for rows in flight, or no barrier at all changed nothing measurable.
+// LDS).  A third register set for rows in flight, or no barrier at all, changed nothing measurable.
 constexpr int kWideThreads = 128;
 
 template <int MTW, int kAct, bool kCount>
@@ -295,11 +294,7 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
       *reinterpret_cast<uint4*>(x_lds + buf * kMlpWaveLds + (4 * j + r) * kMlpRowStride + half * 256 + c * 16) = xx[j];
   };
   float prev = 0.f;   // wave 0: its own partial sums of the tile before this one
-  // One step: products, activation and output layer of tile i; store of tile i - 1 (wave 0 adds the partner's
-  // partial sums, which barrier i - 1 made visible); staging of tile i + 1, whose registers then fetch tile i + 3;
-  // barrier i.
-  auto step = [&](uint4 (&x_next)[4], int i, auto fast) {
-    f32x4_t acc[MTW];
+  auto products = [&](f32x4_t (&acc)[MTW], int i) {   // W1 times the staged tile i, bias as the initial value
 #pragma unroll
     for (int mw = 0; mw < MTW; ++mw) acc[mw] = b1r[mw];
     const unsigned char* xt = x_lds + (i & 1) * kMlpWaveLds;
@@ -311,6 +306,8 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
       for (int mw = 0; mw < MTW; ++mw)
         acc[mw] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wfrag[mw][ks], xv, acc[mw], 0, 0, 0);
     }
+  };
+  auto store_before = [&](int i) {   // scores of tile i - 1: wave 0 adds the partner's partial sums, visible since barrier i - 1
     if (half == 0 && i >= 1) {
       const int row = block_row0 + 16 * (i - 1) + c;
       if (r == 0 && row < T) {
@@ -319,6 +316,8 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
         if (kCount) atomicAdd(&hist_lds[order_key(u) >> kLevel0Shift], 1u);
       }
     }
+  };
+  auto finish = [&](const f32x4_t (&acc)[MTW], int i) {   // activation and output layer of tile i, partial sums exchanged
     float part = 0.f;
 #pragma unroll
     for (int mw = 0; mw < MTW; ++mw)
@@ -330,8 +329,10 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
     } else {
       prev = part;
     }
-    stage_half(x_next, (i + 1) & 1);   // past the last tile: rows nobody reads
-    if (decltype(fast)::value) load_half_fast(x_next, i + 3); else load_half(x_next, i + 3);
+  };
+  auto advance = [&](uint4 (&x_next)[4], int stage_tile, int load_tile, auto fast) {   // then the step's barrier
+    stage_half(x_next, stage_tile & 1);   // past the last tile: rows nobody reads
+    if (decltype(fast)::value) load_half_fast(x_next, load_tile); else load_half(x_next, load_tile);
     __syncthreads();
   };
   const int fast_tiles = min(n_tiles, full_tiles);   // tiles with all 16 rows inside the block and the head
@@ -341,17 +342,54 @@ score_mlp_wide_kernel(SeqTable tab, const uint16_t* __restrict__ w1, const float
   stage_half(xa, 0);
   load_half(xa, 2);
   __syncthreads();   // tile 0 is in LDS
+  if (!kCount) {
+    // Pipelined in the wave: the products of tile i + 1 sit in one scheduling region with the activations of tile i
+    // (a second accumulator set), so that matrix and vector instructions alternate; tiles are staged one step
+    // earlier for it.  1 % faster than the plain order below; with the histogram's registers on top it spills.
+    f32x4_t acc0[MTW], acc1[MTW];
+    auto step = [&](const f32x4_t (&acc_cur)[MTW], f32x4_t (&acc_next)[MTW], uint4 (&x_next)[4], int i, auto fast) {
+      store_before(i);
+      products(acc_next, i + 1);   // after the last tile: a stale buffer, result dropped
+      finish(acc_cur, i);
+      advance(x_next, i + 2, i + 4, fast);
+    };
+    products(acc0, 0);
+    stage_half(xb, 1);
+    load_half(xb, 3);
+    __syncthreads();   // tile 1 is in LDS, the fragments of tile 0 have been read
 #pragma unroll 1
-  for (; i + 4 < fast_tiles; i += 2) {           // both steps fetch whole tiles: tiles i + 3 and i + 4
-    step(xb, i, std::true_type{});               // stages the odd tile i + 1
-    step(xa, i + 1, std::true_type{});
-  }
+    for (; i + 5 < fast_tiles; i += 2) {           // both steps fetch whole tiles: tiles i + 4 and i + 5
+      step(acc0, acc1, xa, i, std::true_type{});
+      step(acc1, acc0, xb, i + 1, std::true_type{});
+    }
 #pragma unroll 1
-  for (; i + 1 < n_tiles; i += 2) {
-    step(xb, i, std::false_type{});
-    step(xa, i + 1, std::false_type{});
+    for (; i + 1 < n_tiles; i += 2) {
+      step(acc0, acc1, xa, i, std::false_type{});
+      step(acc1, acc0, xb, i + 1, std::false_type{});
+    }
+    if (i < n_tiles) step(acc0, acc1, xa, i, std::false_type{});
+  } else {
+    // One step: products, activation and output layer of tile i; store of tile i - 1; staging of tile i + 1, whose
+    // registers then fetch tile i + 3; barrier i.
+    auto step = [&](uint4 (&x_next)[4], int i, auto fast) {
+      f32x4_t acc[MTW];
+      products(acc, i);
+      store_before(i);
+      finish(acc, i);
+      advance(x_next, i + 1, i + 3, fast);
+    };
+#pragma unroll 1
+    for (; i + 4 < fast_tiles; i += 2) {           // both steps fetch whole tiles: tiles i + 3 and i + 4
+      step(xb, i, std::true_type{});               // stages the odd tile i + 1
+      step(xa, i + 1, std::true_type{});
+    }
+#pragma unroll 1
+    for (; i + 1 < n_tiles; i += 2) {
+      step(xb, i, std::false_type{});
+      step(xa, i + 1, std::false_type{});
+    }
+    if (i < n_tiles) step(xb, i, std::false_type{});
   }
-  if (i < n_tiles) step(xb, i, std::false_type{});
 
   if (half == 0) {
     const int row = block_row0 + 16 * (n_tiles - 1) + c;
