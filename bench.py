@@ -46,11 +46,11 @@ SCORE_KERNEL_SOURCES = {
 MEASURED_SCORE_TRAFFIC = {
     # workload name: (bytes per launch, sha256[:16] of the kernel's sources, profile)
     "cfg1-L32-H8-T32768-linear": (4328897267, "8df6ec869a771fd8", "profiles/all_kernels__cfg1-L32-H8-T32768-linear.md"),
-    "cfg2-L32-H8-T131072-mlp64gelu": (17337390572, "129f4cbc937ec62a", "profiles/all_kernels__cfg2-L32-H8-T131072-mlp64gelu.md"),
+    "cfg2-L32-H8-T131072-mlp64gelu": (17337369377, "8610e17d31f2b4e3", "profiles/all_kernels__cfg2-L32-H8-T131072-mlp64gelu.md"),
     "cfg3-16seq-T4096..16384-linear": (22846926438, "8df6ec869a771fd8", "profiles/all_kernels__cfg3-16seq-T4096-16384-linear.md"),
-    "cfg4-8seq-L28-H4-g7-T65536-mlp64gelu": (30386293955, "129f4cbc937ec62a", "profiles/all_kernels__cfg4-8seq-L28-H4-g7-T65536-mlp64gelu.md"),
-    "paper-L32-H8-T32768-mlp128silu-per-head": (4468904279, "129f4cbc937ec62a", "profiles/all_kernels__paper-L32-H8-T32768-mlp128silu-per-head.md"),
-    "paper-L36-H8-T32768-mlp128silu-per-head": (5027139711, "129f4cbc937ec62a", "profiles/all_kernels__paper-L36-H8-T32768-mlp128silu-per-head.md"),
+    "cfg4-8seq-L28-H4-g7-T65536-mlp64gelu": (30386206836, "8610e17d31f2b4e3", "profiles/all_kernels__cfg4-8seq-L28-H4-g7-T65536-mlp64gelu.md"),
+    "paper-L32-H8-T32768-mlp128silu-per-head": (4469725727, "8610e17d31f2b4e3", "profiles/all_kernels__paper-L32-H8-T32768-mlp128silu-per-head.md"),
+    "paper-L36-H8-T32768-mlp128silu-per-head": (5028391389, "8610e17d31f2b4e3", "profiles/all_kernels__paper-L36-H8-T32768-mlp128silu-per-head.md"),
 }
 
 
